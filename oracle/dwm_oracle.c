@@ -1,0 +1,379 @@
+/*
+ * FP64 CPU oracle for the Decomposable Winograd Method (DWM) forward convolution.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may include, link or call
+ * this file; it exists so that tests, the smoke check and the benchmark's CPU
+ * baseline leg have an independent statement of what the GPU path must compute.
+ * It shares no code, tables or helpers with the HIP library.
+ *
+ * Two independent computations of the same result:
+ *
+ *   O1  oracle_direct_f64      the plain definition of a strided, zero-padded 2-D
+ *                              cross-correlation (what the paper calls "regular
+ *                              convolution"; its aggregation step states that DWM's
+ *                              result is equal to it, Sec. 4.1 "Aggregation").
+ *   O2  oracle_dwm_f64         the paper's five steps, in its order (Sec. 4.1 bullet
+ *                              list, Fig. 3): splitting, transformation, calculation,
+ *                              detransformation, aggregation; stride handled by the
+ *                              phase grouping of Sec. 4.1 "Stride > 1" (eq. 12-14),
+ *                              size by the consecutive 3-tap cut of Sec. 4.1 "Large
+ *                              kernel size" (eq. 8-11).
+ *
+ * All arithmetic is double precision; inputs are the float32 arrays the GPU sees,
+ * widened on load.  Layouts: x[N][C][H][W], w[K][C][R][S], y[N][K][OH][OW], dense.
+ * Cross-correlation semantics (the printed F(2,3) matrices of Sec. 3.2 compute
+ * y_j = sum_k d_{j+k} g_k): y[n,k,oh,ow] = sum_{c,r,q} xp[n,c,oh*s+r,ow*s+q] w[k,c,r,q],
+ * xp = x zero-padded by P on all four sides.
+ *
+ * Pins: see tests/test_oracle_*.py (rational-arithmetic identity of every F(2,l),
+ * the printed F(2,3) matrices, Table 3 multiplication counts, closed forms, a
+ * library float64 convolution, brute force, and O2 == O1 to 1e-12).
+ */
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* O1: direct convolution, the definition                                     */
+/* ------------------------------------------------------------------------- */
+
+static double direct_point(const float* x, const float* w, int C, int H, int W,
+                           int R, int S, int s, int P, int n, int k, int oh, int ow)
+{
+    double acc = 0.0;
+    for (int c = 0; c < C; ++c)
+        for (int r = 0; r < R; ++r)
+            for (int q = 0; q < S; ++q) {
+                int ih = oh * s + r - P;
+                int iw = ow * s + q - P;
+                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue; /* zero padding */
+                double xv = (double)x[(((size_t)n * C + c) * H + ih) * W + iw];
+                double wv = (double)w[(((size_t)k * C + c) * R + r) * S + q];
+                acc += xv * wv;
+            }
+    return acc;
+}
+
+int oracle_out_size(int H, int R, int s, int P) { return (H + 2 * P - R) / s + 1; }
+
+/* y[N][K][OH][OW] <- direct convolution.  Returns 0, or 1 on a bad shape. */
+int oracle_direct_f64(const float* x, const float* w, double* y,
+                      int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = oracle_out_size(H, R, s, P), OW = oracle_out_size(W, S, s, P);
+    const long long NK = (long long)N * K;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long nk = 0; nk < NK; ++nk) {
+        int n = (int)(nk / K), k = (int)(nk % K);
+        for (int oh = 0; oh < OH; ++oh)
+            for (int ow = 0; ow < OW; ++ow)
+                y[(((size_t)n * K + k) * OH + oh) * OW + ow] =
+                    direct_point(x, w, C, H, W, R, S, s, P, n, k, oh, ow);
+    }
+    return 0;
+}
+
+/* out[i] <- y at flat output index idx[i] (index into [N][K][OH][OW]); for sampled
+ * checks at sizes where the whole output is too slow to compute. */
+int oracle_direct_f64_at(const float* x, const float* w, const long long* idx, long long n_idx,
+                         double* out, int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = oracle_out_size(H, R, s, P), OW = oracle_out_size(W, S, s, P);
+    const long long total = (long long)N * K * OH * OW;
+    for (long long i = 0; i < n_idx; ++i)
+        if (idx[i] < 0 || idx[i] >= total) return 1;
+#pragma omp parallel for schedule(static)
+    for (long long i = 0; i < n_idx; ++i) {
+        long long f = idx[i];
+        int ow = (int)(f % OW); f /= OW;
+        int oh = (int)(f % OH); f /= OH;
+        int k = (int)(f % K);
+        int n = (int)(f / K);
+        out[i] = direct_point(x, w, C, H, W, R, S, s, P, n, k, oh, ow);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Winograd F(2,l) matrices, l = 1, 2, 3                                      */
+/* ------------------------------------------------------------------------- */
+/*
+ * F(2,3): B^T, G, A^T exactly as printed in Sec. 3.2 (the F(2,3) display).
+ * F(2,2) and the one-tap case are named by the paper (Sec. 4.1: "apply F(2,2) or
+ * F(2,3)") but not printed.  Reading taken here, fixed by Table 3's counts (a
+ * 2-tap piece costs 3 multiplications, a 1-tap piece costs 2):
+ *   F(2,2): m1=(d0-d1)g0, m2=d1(g0+g1), m3=(d2-d1)g1; y0=m1+m2, y1=m2+m3
+ *   F(2,1): m1=d0 g0, m2=d1 g0 (no transform at all)
+ * Stored in 4x4 / 4x3 / 2x4 arrays, upper-left corner used: tile length l+1.
+ */
+static const double BT_[4][4][4] = {
+    {{0}},
+    /* l=1 */ {{1, 0, 0, 0}, {0, 1, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}},
+    /* l=2 */ {{1, -1, 0, 0}, {0, 1, 0, 0}, {0, -1, 1, 0}, {0, 0, 0, 0}},
+    /* l=3 */ {{1, 0, -1, 0}, {0, 1, 1, 0}, {0, -1, 1, 0}, {0, 1, 0, -1}},
+};
+static const double G_[4][4][3] = {
+    {{0}},
+    /* l=1 */ {{1, 0, 0}, {1, 0, 0}, {0, 0, 0}, {0, 0, 0}},
+    /* l=2 */ {{1, 0, 0}, {1, 1, 0}, {0, 1, 0}, {0, 0, 0}},
+    /* l=3 */ {{1, 0, 0}, {0.5, 0.5, 0.5}, {0.5, -0.5, 0.5}, {0, 0, 1}},
+};
+static const double AT_[4][2][4] = {
+    {{0}},
+    /* l=1 */ {{1, 0, 0, 0}, {0, 1, 0, 0}},
+    /* l=2 */ {{1, 1, 0, 0}, {0, 1, 1, 0}},
+    /* l=3 */ {{1, 1, 1, 0}, {0, 1, -1, -1}},
+};
+
+/* Copy the matrices of F(2,l) out (row-major BT[(l+1)x(l+1)], G[(l+1)xl], AT[2x(l+1)]). */
+int oracle_winograd_matrices(int l, double* BT, double* G, double* AT)
+{
+    if (l < 1 || l > 3) return 1;
+    const int t = l + 1;
+    for (int i = 0; i < t; ++i)
+        for (int j = 0; j < t; ++j) BT[i * t + j] = BT_[l][i][j];
+    for (int i = 0; i < t; ++i)
+        for (int j = 0; j < l; ++j) G[i * l + j] = G_[l][i][j];
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < t; ++j) AT[i * t + j] = AT_[l][i][j];
+    return 0;
+}
+
+/* 1-D F(2,l): Y = A^T [ (G g) .* (B^T d) ]   (Sec. 3.1, the 1-D formula) */
+int oracle_winograd_1d(int l, const double* g, const double* d, double* y2)
+{
+    if (l < 1 || l > 3) return 1;
+    const int t = l + 1;
+    double u[4], v[4];
+    for (int i = 0; i < t; ++i) {
+        u[i] = 0.0;
+        for (int j = 0; j < l; ++j) u[i] += G_[l][i][j] * g[j];
+        v[i] = 0.0;
+        for (int j = 0; j < t; ++j) v[i] += BT_[l][i][j] * d[j];
+    }
+    for (int o = 0; o < 2; ++o) {
+        y2[o] = 0.0;
+        for (int i = 0; i < t; ++i) y2[o] += AT_[l][o][i] * (u[i] * v[i]);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* O2 step 1: splitting of the kernel                                         */
+/* ------------------------------------------------------------------------- */
+/*
+ * A 1-D piece (p, j, l): phase p (taps whose index is p mod s, Sec. 4.1 eq. 12),
+ * offset j inside that phase's tap list, length l in {1,2,3} (Sec. 4.1 eq. 8: the
+ * list is cut into threes from the low end, the remainder last; number of cuts is
+ * ceil(n_p/3), n_p = ceil((r-p)/s) taps in phase p).  Its taps are g[s*(j+q)+p],
+ * q<l.  Only phases that hold a tap exist (p < min(s, r)).
+ */
+typedef struct { int p, j, l; } oracle_piece;
+
+int oracle_split_1d(int r, int s, oracle_piece* out, int max_out)
+{
+    int n = 0;
+    for (int p = 0; p < s && p < r; ++p) {
+        int n_p = (r - p + s - 1) / s;
+        for (int j = 0; j < n_p; j += 3) {
+            if (n >= max_out) return -1;
+            out[n].p = p;
+            out[n].j = j;
+            out[n].l = (n_p - j < 3) ? (n_p - j) : 3;
+            ++n;
+        }
+    }
+    return n;
+}
+
+/* A part (sub-kernel) = one piece per dimension ("nest the 1-D methods"). */
+typedef struct { int ph, jh, lh, pw, jw, lw; } oracle_part;
+
+#define ORACLE_MAX_PIECES 64
+
+/* parts[] <- cartesian product of the two 1-D splits; returns the count or -1. */
+int oracle_split_2d(int R, int S, int s, oracle_part* parts, int max_parts)
+{
+    oracle_piece hp[ORACLE_MAX_PIECES], wp[ORACLE_MAX_PIECES];
+    int nh = oracle_split_1d(R, s, hp, ORACLE_MAX_PIECES);
+    int nw = oracle_split_1d(S, s, wp, ORACLE_MAX_PIECES);
+    if (nh < 0 || nw < 0 || nh * nw > max_parts) return -1;
+    int n = 0;
+    for (int a = 0; a < nh; ++a)
+        for (int b = 0; b < nw; ++b) {
+            parts[n].ph = hp[a].p; parts[n].jh = hp[a].j; parts[n].lh = hp[a].l;
+            parts[n].pw = wp[b].p; parts[n].jw = wp[b].j; parts[n].lw = wp[b].l;
+            ++n;
+        }
+    return n;
+}
+
+/* Multiplications per 2x2 output tile per (k,c) pair: each part of size lh x lw
+ * costs (lh+1)(lw+1) (the counting model behind Table 3). */
+long long oracle_mults_per_tile(int R, int S, int s)
+{
+    oracle_part parts[ORACLE_MAX_PIECES * ORACLE_MAX_PIECES];
+    int n = oracle_split_2d(R, S, s, parts, ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (n < 0) return -1;
+    long long m = 0;
+    for (int i = 0; i < n; ++i) m += (long long)(parts[i].lh + 1) * (parts[i].lw + 1);
+    return m;
+}
+
+/* ------------------------------------------------------------------------- */
+/* O2 steps 1-2 per part: input slicing + transformation                      */
+/* ------------------------------------------------------------------------- */
+
+/* U[K][C][lh+1][lw+1] <- G_lh g G_lw^T,  g[a][b] = w[k][c][s(jh+a)+ph][s(jw+b)+pw] */
+int oracle_part_filter_transform(const float* w, int K, int C, int R, int S, int s,
+                                 const oracle_part* pt, double* U)
+{
+    const int lh = pt->lh, lw = pt->lw, th = lh + 1, tw = lw + 1;
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c) {
+            double g[3][3], Gg[4][3];
+            for (int a = 0; a < lh; ++a)
+                for (int b = 0; b < lw; ++b) {
+                    int r = s * (pt->jh + a) + pt->ph, q = s * (pt->jw + b) + pt->pw;
+                    if (r >= R || q >= S) return 1;
+                    g[a][b] = (double)w[(((size_t)k * C + c) * R + r) * S + q];
+                }
+            for (int i = 0; i < th; ++i)
+                for (int b = 0; b < lw; ++b) {
+                    Gg[i][b] = 0.0;
+                    for (int a = 0; a < lh; ++a) Gg[i][b] += G_[lh][i][a] * g[a][b];
+                }
+            double* u = U + ((size_t)k * C + c) * th * tw;
+            for (int i = 0; i < th; ++i)
+                for (int j = 0; j < tw; ++j) {
+                    double acc = 0.0;
+                    for (int b = 0; b < lw; ++b) acc += Gg[i][b] * G_[lw][j][b];
+                    u[i * tw + j] = acc;
+                }
+        }
+    return 0;
+}
+
+/*
+ * V[C][TH][TW][lh+1][lw+1] for image n <- B_lh^T d B_lw,
+ *   d[a][b] = xp[s(2ty+jh+a)+ph][s(2tx+jw+b)+pw]   (phase-p taps meet phase-p samples
+ *   of the PADDED input; raw index = padded index - P, zero outside the image).
+ * Tiles cover 2x2 output blocks: TH = ceil(OH/2), TW = ceil(OW/2).
+ */
+int oracle_part_input_transform(const float* x, int C, int H, int W, int s, int P,
+                                int TH, int TW, int n, const oracle_part* pt, double* V)
+{
+    const int lh = pt->lh, lw = pt->lw, th = lh + 1, tw = lw + 1;
+    for (int c = 0; c < C; ++c)
+        for (int ty = 0; ty < TH; ++ty)
+            for (int tx = 0; tx < TW; ++tx) {
+                double d[4][4], Bd[4][4];
+                for (int a = 0; a < th; ++a)
+                    for (int b = 0; b < tw; ++b) {
+                        int ih = s * (2 * ty + pt->jh + a) + pt->ph - P;
+                        int iw = s * (2 * tx + pt->jw + b) + pt->pw - P;
+                        d[a][b] = (ih < 0 || ih >= H || iw < 0 || iw >= W)
+                                      ? 0.0
+                                      : (double)x[(((size_t)n * C + c) * H + ih) * W + iw];
+                    }
+                for (int i = 0; i < th; ++i)
+                    for (int b = 0; b < tw; ++b) {
+                        Bd[i][b] = 0.0;
+                        for (int a = 0; a < th; ++a) Bd[i][b] += BT_[lh][i][a] * d[a][b];
+                    }
+                double* v = V + (((size_t)c * TH + ty) * TW + tx) * th * tw;
+                for (int i = 0; i < th; ++i)
+                    for (int j = 0; j < tw; ++j) {
+                        double acc = 0.0;
+                        for (int b = 0; b < tw; ++b) acc += Bd[i][b] * BT_[lw][j][b];
+                        v[i * tw + j] = acc;
+                    }
+            }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* O2: the whole method                                                       */
+/* ------------------------------------------------------------------------- */
+int oracle_dwm_f64(const float* x, const float* w, double* y,
+                   int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = oracle_out_size(H, R, s, P), OW = oracle_out_size(W, S, s, P);
+    const int TH = (OH + 1) / 2, TW = (OW + 1) / 2;
+
+    /* Splitting (kernel). */
+    oracle_part* parts = (oracle_part*)malloc(sizeof(oracle_part) * ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (!parts) return 2;
+    const int n_parts = oracle_split_2d(R, S, s, parts, ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (n_parts < 0) { free(parts); return 1; }
+
+    memset(y, 0, sizeof(double) * (size_t)N * K * OH * OW);
+    double* U = (double*)malloc(sizeof(double) * (size_t)K * C * 16);
+    double* V = (double*)malloc(sizeof(double) * (size_t)C * TH * TW * 16);
+    if (!U || !V) { free(parts); free(U); free(V); return 2; }
+
+    int rc = 0;
+    for (int ip = 0; ip < n_parts && !rc; ++ip) {
+        const oracle_part* pt = &parts[ip];
+        const int th = pt->lh + 1, tw = pt->lw + 1;
+        /* Transformation (kernel side): U = G g G^T. */
+        rc = oracle_part_filter_transform(w, K, C, R, S, s, pt, U);
+        for (int n = 0; n < N && !rc; ++n) {
+            /* Splitting (input side) + Transformation: V = B^T d B. */
+            rc = oracle_part_input_transform(x, C, H, W, s, P, TH, TW, n, pt, V);
+            if (rc) break;
+#pragma omp parallel for schedule(static)
+            for (int k = 0; k < K; ++k)
+                for (int ty = 0; ty < TH; ++ty)
+                    for (int tx = 0; tx < TW; ++tx) {
+                        /* Calculation: element-wise product, summed over channels. */
+                        double M[4][4];
+                        for (int i = 0; i < th; ++i)
+                            for (int j = 0; j < tw; ++j) M[i][j] = 0.0;
+                        for (int c = 0; c < C; ++c) {
+                            const double* u = U + ((size_t)k * C + c) * th * tw;
+                            const double* v = V + (((size_t)c * TH + ty) * TW + tx) * th * tw;
+                            for (int i = 0; i < th; ++i)
+                                for (int j = 0; j < tw; ++j) M[i][j] += u[i * tw + j] * v[i * tw + j];
+                        }
+                        /* Detransformation: A^T M A. */
+                        double AM[2][4];
+                        for (int a = 0; a < 2; ++a)
+                            for (int j = 0; j < tw; ++j) {
+                                AM[a][j] = 0.0;
+                                for (int i = 0; i < th; ++i) AM[a][j] += AT_[pt->lh][a][i] * M[i][j];
+                            }
+                        /* Aggregation: add this part's 2x2 block into the output. */
+                        for (int a = 0; a < 2; ++a)
+                            for (int b = 0; b < 2; ++b) {
+                                int oh = 2 * ty + a, ow = 2 * tx + b;
+                                if (oh >= OH || ow >= OW) continue;
+                                double acc = 0.0;
+                                for (int j = 0; j < tw; ++j) acc += AM[a][j] * AT_[pt->lw][b][j];
+                                y[(((size_t)n * K + k) * OH + oh) * OW + ow] += acc;
+                            }
+                    }
+        }
+    }
+    free(parts); free(U); free(V);
+    return rc;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
