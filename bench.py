@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the DWM forward convolution on one MI355X.
+
+A "step" is one dwm_conv_forward (input transform + contraction/output transform) over one
+synthetic batch that is already resident in HBM; the filter transform runs once before the
+timed region (it is a function of the weights only).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu-baseline]
+
+--config picks one of the five layers of dwm_workloads.CONFIGS (default 1, the stride-2
+downsampling layer the headline metric is quoted on).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "direct-conv-equivalent TFLOP/s of DWM conv (fp32, 1 GPU); MSE vs FP64 direct"
+PEAK_MFMA_F32 = 157.3  # TFLOP/s, dense fp32 MFMA, MI355X
+PEAK_HBM = 8000.0      # GB/s
+
+
+def cpu_baseline(x, w, L, target_s=12.0):
+    """The FP64 direct-convolution oracle, as it stands, on a bounded sample of this
+    workload's outputs: direct-equivalent TFLOP/s on the host cores."""
+    import numpy as np
+    import oracle
+    import dwm_workloads as wl
+
+    OH, OW = wl.out_hw(L)
+    total = L.N * L.K * OH * OW
+    rng = np.random.default_rng(7)
+    per_out = 2.0 * L.C * L.R * L.S
+    probe = min(total, 20000)
+    idx = rng.choice(total, probe, replace=False)
+    t0 = time.perf_counter()
+    oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
+    dt = time.perf_counter() - t0
+    n = int(min(total, max(probe, probe * target_s / max(dt, 1e-6))))
+    idx = rng.choice(total, n, replace=False)
+    t0 = time.perf_counter()
+    oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
+    dt = time.perf_counter() - t0
+    return {"value": per_out * n / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "%d of %d outputs of %s drawn uniformly, FP64 direct convolution" % (n, total, L.name)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--contract-variant", type=int, default=-1)
+    ap.add_argument("--input-variant", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "use --gpus 1. The forward path would shard over the batch with no exchange.")
+
+    import numpy as np
+    import torch
+
+    import dwm_workloads as wl
+    import paper_2002_00552_amd as dwm
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    L = wl.CONFIGS[args.config]
+    x, w = wl.make_layer_tensors(L, args.config)
+
+    plan = dwm.dwm_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    info = dwm.dwm_plan_info(plan)
+    if args.contract_variant >= 0:
+        dwm.dwm_plan_set_variant(plan, "contract", args.contract_variant)
+    if args.input_variant >= 0:
+        dwm.dwm_plan_set_variant(plan, "input", args.input_variant)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    U = torch.empty(dwm.dwm_plan_filter_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+    ws = torch.empty(dwm.dwm_plan_workspace_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+    y = torch.empty((L.N, L.K, info.OH, info.OW), dtype=torch.float32, device="cuda")
+    dwm.dwm_plan_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+    st = torch.cuda.current_stream().cuda_stream
+    xp, Up, yp = xd.data_ptr(), U.data_ptr(), y.data_ptr()
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st)
+    ev[1].record()
+    torch.cuda.synchronize()
+    filter_ms = ev[0].elapsed_time(ev[1])
+
+    for _ in range(args.warmup):
+        dwm.dwm_conv_forward(plan, xp, Up, yp, st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dwm.dwm_conv_forward(plan, xp, Up, yp, st)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = info.direct_flops / (dt / args.steps) / 1e12
+
+    # Per-kernel durations: the same K steps again, each stage bracketed by HIP events on the
+    # stream the kernels run on (torch's current stream is the one handed to the library).
+    e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        e[i][0].record()
+        dwm.dwm_input_transform(plan, xp, st)
+        e[i][1].record()
+        dwm.dwm_contract_output(plan, Up, yp, st)
+        e[i][2].record()
+    torch.cuda.synchronize()
+    in_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
+    ct_ms = sum(b.elapsed_time(c) for _, b, c in e) / args.steps
+
+    v_bytes = 4.0 * info.mults_per_tile * L.C * info.T
+    x_bytes, y_bytes = 4.0 * x.size, 4.0 * y.numel()
+    stages = {
+        "input_transform": {"ms": in_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + v_bytes,
+                            "achieved_GBps": (x_bytes + v_bytes) / in_ms / 1e6,
+                            "frac_of_hbm_peak": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM},
+        "contract_output": {"ms": ct_ms, "bound": "mfma", "algorithmic_flops": info.winograd_flops,
+                            "achieved_TFLOPs": info.winograd_flops / ct_ms / 1e9,
+                            "frac_of_mfma_peak": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32,
+                            "hbm_GBps_on_V_U_y": (v_bytes + y_bytes + 4.0 * U.numel()) / ct_ms / 1e6},
+        "filter_transform_once": {"ms": filter_ms},
+    }
+    if ct_ms >= in_ms:
+        roofline = {"kernel": "contract_output_kernel", "bound": "mfma",
+                    "achieved": info.winograd_flops / ct_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
+                    "frac": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32, "traffic": None}
+    else:
+        roofline = {"kernel": "input_transform_kernel", "bound": "hbm",
+                    "achieved": (x_bytes + v_bytes) / in_ms / 1e6, "peak": PEAK_HBM, "unit": "GB/s",
+                    "frac": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM, "traffic": None}
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": L.name, "N": L.N, "C": L.C, "H": L.H, "W": L.W, "K": L.K, "R": L.R, "S": L.S,
+                   "stride": L.stride, "pad": L.pad, "parts": info.n_parts,
+                   "mults_per_tile": info.mults_per_tile, "direct_GFLOP": info.direct_flops / 1e9,
+                   "winograd_GFLOP": info.winograd_flops / 1e9},
+        "roofline": roofline, "stages": stages,
+    }
+
+    if not args.no_check:
+        import oracle
+        yh = y.cpu().numpy()
+        rng = np.random.default_rng(99)
+        idx = rng.choice(yh.size, min(yh.size, 40000), replace=False)
+        ref = oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
+        got = yh.ravel()[idx].astype(np.float64)
+        mse = float(np.mean((got - ref) ** 2))
+        out["accuracy"] = {"max_rel_err": float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))),
+                           "mse_vs_fp64_direct": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
+                           "sampled_outputs": int(idx.size)}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(x, w, L)
+    dwm.dwm_plan_destroy(plan)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,154 @@
+/*
+ * libdwm -- forward 2-D convolution by the Decomposable Winograd Method (DWM) on
+ * AMD MI355X (gfx950), C ABI.
+ *
+ * The method (paper Sec. 4.1): a kernel that is large and/or strided is split into
+ * stride-1 sub-kernels ("parts") of size at most 3x3 -- taps are grouped by index
+ * modulo the stride (eq. 12-14) and each group is cut into consecutive runs of three
+ * (eq. 8-11) -- every part goes through a small Winograd F(2,l) (Sec. 3.1-3.2) and the
+ * parts' results are summed (the five steps of Sec. 4.1 / Fig. 3: splitting,
+ * transformation, calculation, detransformation, aggregation).  The result equals the
+ * ordinary convolution in exact arithmetic.
+ *
+ * Semantics of the whole path: cross-correlation, identical to a framework conv2d with
+ * no bias, dilation 1, groups 1, one stride for both dimensions and symmetric zero
+ * padding:
+ *     y[n,k,oh,ow] = sum_{c,r,q} xp[n,c,oh*stride+r,ow*stride+q] * w[k,c,r,q]
+ * with xp = x zero-padded by `pad` on all four sides, OH = (H+2*pad-R)/stride+1 (same
+ * for OW).  All tensors are dense float32: x[N][C][H][W], w[K][C][R][S], y[N][K][OH][OW].
+ *
+ * Memory and streams.  Every pointer named *_dev is DEVICE memory owned by the caller;
+ * the library never allocates or frees device memory, never synchronises, and enqueues
+ * all kernels on the hipStream_t passed as `stream` (a `void*`; NULL = default stream).
+ * A plan is host memory owned by the library (create/destroy).  A plan is immutable
+ * after dwm_plan_set_workspace, so it may be reused for any number of calls; two calls
+ * that use the same plan (hence the same workspace) must be ordered on one stream.
+ *
+ * Errors are return codes, never exceptions or aborts.  Launch errors reported by the
+ * HIP runtime come back as DWM_ERR_HIP.
+ */
+#ifndef DWM_H_
+#define DWM_H_
+
+#include <stddef.h>
+
+/* Exported symbols of the shared library. */
+#define DWM_API __attribute__((visibility("default")))
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dwm_plan dwm_plan_t;
+
+typedef enum {
+    DWM_OK = 0,
+    DWM_ERR_INVALID_ARG = 1, /* null pointer; N,C,H,W,K,R,S < 1; stride < 1; pad < 0; empty output */
+    DWM_ERR_UNSUPPORTED = 2, /* shape outside the limits stated at dwm_plan_create */
+    DWM_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or too small */
+    DWM_ERR_ALLOC = 4,       /* host allocation failed */
+    DWM_ERR_HIP = 5          /* the HIP runtime reported an error */
+} dwm_status_t;
+
+/* What the planner decided (all host-side integers). */
+typedef struct {
+    int N, C, H, W, K, R, S, stride, pad;
+    int OH, OW;               /* output size */
+    int TH, TW;               /* 2x2 output tiles per image: ceil(OH/2), ceil(OW/2) */
+    long long T;              /* N*TH*TW tiles */
+    int n_parts;              /* sub-kernels (Sec. 4.1 "Splitting") */
+    int n_classes;            /* distinct (len_h, len_w) among the parts */
+    int n_planes;             /* Winograd-domain planes = sum over classes of (len_h+1)(len_w+1) */
+    long long mults_per_tile; /* multiplications per 2x2 output tile per (k,c): sum over parts of
+                                 (len_h+1)(len_w+1), the counting model of Table 3 */
+    double direct_flops;      /* 2*N*K*C*R*S*OH*OW */
+    double winograd_flops;    /* 2*mults_per_tile*C*K*T */
+    int Kpad;                 /* rows per plane of the transformed filter (K rounded up) */
+    long long Tpad;           /* columns per plane of the transformed input (T rounded up) */
+} dwm_plan_info_t;
+
+/* One sub-kernel.  Its taps are w[.,.,stride*(off_h+a)+phase_h, stride*(off_w+b)+phase_w],
+ * a < len_h, b < len_w; for output (oh,ow) it meets padded input
+ * xp[stride*(oh+off_h+a)+phase_h][stride*(ow+off_w+b)+phase_w]. */
+typedef struct {
+    int phase_h, off_h, len_h;
+    int phase_w, off_w, len_w;
+    int cls;  /* class index: parts with equal (len_h, len_w) share transforms */
+    int slot; /* position inside its class: reduction index l = slot*C + c */
+} dwm_part_t;
+
+/* One class = all parts with the same (len_h, len_w).  They use the same F(2,len)
+ * matrices, so they are summed in the Winograd domain: the reduction of the class runs
+ * over l = slot*C + c, l < L = n_parts*C (rounded up to Lpad with zeros).
+ * Layouts (offsets in floats from the start of the buffer; fh <= len_h, fw <= len_w):
+ *   transformed filter  Ugw[u_offset + ((fh*(len_w+1)+fw)*Kpad + k)*Lpad + l]
+ *   transformed input   ws [v_offset + ((fh*(len_w+1)+fw)*Lpad + l)*Tpad + t],
+ *                       t = (n*TH + ty)*TW + tx
+ */
+typedef struct {
+    int len_h, len_w;
+    int n_parts;
+    int L, Lpad;
+    long long u_offset, v_offset;
+} dwm_class_t;
+
+/*
+ * Splitting, kernel side (Sec. 4.1: eq. 12 for the stride, eq. 8 for the size; the two
+ * combined as its last paragraph says).  Host only; no GPU call is made.
+ * Limits: at most 16 one-dimensional pieces per dimension (e.g. R <= 48 at stride 1),
+ * N*TH*TW and every buffer's element count below 2^31.  Returns DWM_ERR_INVALID_ARG for
+ * non-positive sizes, negative pad or an empty output, DWM_ERR_UNSUPPORTED beyond the limits.
+ * *out is set only on DWM_OK and must be released with dwm_plan_destroy.
+ */
+DWM_API dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad);
+DWM_API dwm_status_t dwm_plan_destroy(dwm_plan_t* plan);
+
+/* Introspection of the decomposition (host only). */
+DWM_API dwm_status_t dwm_plan_info(const dwm_plan_t* plan, dwm_plan_info_t* info);
+DWM_API dwm_status_t dwm_plan_part(const dwm_plan_t* plan, int i, dwm_part_t* part);     /* i < n_parts   */
+DWM_API dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls);   /* i < n_classes */
+
+/* Bytes of the transformed filter Ugw and of the workspace (the transformed input V). */
+DWM_API size_t dwm_plan_filter_bytes(const dwm_plan_t* plan);
+DWM_API size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan);
+
+/* Hand the plan its workspace: caller-owned device memory, 256-byte aligned, at least
+ * dwm_plan_workspace_bytes(plan) long, alive as long as the plan is used.  No GPU call. */
+DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size_t bytes);
+
+/* Pick a kernel variant for a stage ("input", "contract"); variant < 0 restores the
+ * planner's own choice.  For tuning and tests; results are the same up to fp32 rounding. */
+DWM_API dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int variant);
+
+/*
+ * Transformation, kernel side (Sec. 4.1 "Transformation"; Sec. 3.1 eq. 4): for every part,
+ * U = G g G^T with g the part's taps, written into Ugw_dev in the per-class layout above
+ * (padding rows/columns are written as zeros).  w_dev is [K][C][R][S].  Asynchronous.
+ */
+DWM_API dwm_status_t dwm_filter_transform(const dwm_plan_t* plan, const float* w_dev, float* Ugw_dev, void* stream);
+
+/*
+ * The forward convolution (Sec. 4.1, all five steps on the input side): slices the
+ * input per part and phase, V = B^T d B, per-plane contraction over (part, channel)
+ * M = sum U .* V, detransformation A^T M A and aggregation over parts into y.
+ * x_dev [N][C][H][W], Ugw_dev from dwm_filter_transform, y_dev [N][K][OH][OW] fully
+ * overwritten.  Needs the workspace.  Asynchronous on `stream`.
+ */
+DWM_API dwm_status_t dwm_conv_forward(const dwm_plan_t* plan, const float* x_dev, const float* Ugw_dev,
+                              float* y_dev, void* stream);
+
+/* The two stages of dwm_conv_forward on their own (for per-stage tests and timing):
+ * dwm_input_transform fills the workspace with V (Sec. 4.1 "Splitting" of the input and
+ * "Transformation"); dwm_contract_output reads V from the workspace and does the
+ * "Calculation", "Detransformation" and "Aggregation" steps.  Calling them in this order
+ * on one stream is exactly dwm_conv_forward. */
+DWM_API dwm_status_t dwm_input_transform(const dwm_plan_t* plan, const float* x_dev, void* stream);
+DWM_API dwm_status_t dwm_contract_output(const dwm_plan_t* plan, const float* Ugw_dev, float* y_dev, void* stream);
+
+DWM_API const char* dwm_status_string(dwm_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DWM_H_ */

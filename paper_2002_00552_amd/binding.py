@@ -1,0 +1,145 @@
+"""ctypes binding of libdwm.so: same names as include/dwm.h, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  There is no CPU fallback: if
+libdwm.so has not been built (python -m paper_2002_00552_amd.build), loading fails loudly.
+Device pointers are plain integers (e.g. torch.Tensor.data_ptr()); `stream` is a
+hipStream_t handle as an integer (e.g. torch.cuda.current_stream().cuda_stream).
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdwm.so")
+
+DWM_OK, DWM_ERR_INVALID_ARG, DWM_ERR_UNSUPPORTED, DWM_ERR_WORKSPACE, DWM_ERR_ALLOC, DWM_ERR_HIP = range(6)
+
+
+class DwmError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        RuntimeError.__init__(self, "%s: %s (status %d)" % (where, dwm_status_string(status), status))
+
+
+class dwm_plan_info_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad",
+                                            "OH", "OW", "TH", "TW")] + [
+        ("T", ctypes.c_longlong), ("n_parts", ctypes.c_int), ("n_classes", ctypes.c_int),
+        ("n_planes", ctypes.c_int), ("mults_per_tile", ctypes.c_longlong),
+        ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double),
+        ("Kpad", ctypes.c_int), ("Tpad", ctypes.c_longlong)]
+
+
+class dwm_part_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("phase_h", "off_h", "len_h", "phase_w", "off_w", "len_w",
+                                            "cls", "slot")]
+
+
+class dwm_class_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("len_h", "len_w", "n_parts", "L", "Lpad")] + [
+        ("u_offset", ctypes.c_longlong), ("v_offset", ctypes.c_longlong)]
+
+
+_P = ctypes.c_void_p
+_I = ctypes.c_int
+_SIGNATURES = {
+    "dwm_plan_create": (_I, [ctypes.POINTER(_P)] + [_I] * 9),
+    "dwm_plan_destroy": (_I, [_P]),
+    "dwm_plan_info": (_I, [_P, ctypes.POINTER(dwm_plan_info_t)]),
+    "dwm_plan_part": (_I, [_P, _I, ctypes.POINTER(dwm_part_t)]),
+    "dwm_plan_class": (_I, [_P, _I, ctypes.POINTER(dwm_class_t)]),
+    "dwm_plan_filter_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_plan_workspace_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_plan_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
+    "dwm_plan_set_variant": (_I, [_P, ctypes.c_char_p, _I]),
+    "dwm_filter_transform": (_I, [_P, _P, _P, _P]),
+    "dwm_conv_forward": (_I, [_P, _P, _P, _P, _P]),
+    "dwm_input_transform": (_I, [_P, _P, _P]),
+    "dwm_contract_output": (_I, [_P, _P, _P, _P]),
+    "dwm_status_string": (ctypes.c_char_p, [_I]),
+}
+EXPORTS = sorted(_SIGNATURES)
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libdwm.so is not built: run `python -m paper_2002_00552_amd.build` "
+                              "(there is no CPU fallback)")
+        _lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(_lib, name)
+            fn.restype, fn.argtypes = res, args
+    return _lib
+
+
+def _check(status, where):
+    if status != DWM_OK:
+        raise DwmError(status, where)
+
+
+def dwm_status_string(status):
+    return lib().dwm_status_string(int(status)).decode()
+
+
+def dwm_plan_create(N, C, H, W, K, R, S, stride, pad):
+    h = _P()
+    _check(lib().dwm_plan_create(ctypes.byref(h), N, C, H, W, K, R, S, stride, pad), "dwm_plan_create")
+    return h
+
+
+def dwm_plan_destroy(plan):
+    _check(lib().dwm_plan_destroy(plan), "dwm_plan_destroy")
+
+
+def dwm_plan_info(plan):
+    info = dwm_plan_info_t()
+    _check(lib().dwm_plan_info(plan, ctypes.byref(info)), "dwm_plan_info")
+    return info
+
+
+def dwm_plan_part(plan, i):
+    part = dwm_part_t()
+    _check(lib().dwm_plan_part(plan, i, ctypes.byref(part)), "dwm_plan_part")
+    return part
+
+
+def dwm_plan_class(plan, i):
+    cls = dwm_class_t()
+    _check(lib().dwm_plan_class(plan, i, ctypes.byref(cls)), "dwm_plan_class")
+    return cls
+
+
+def dwm_plan_filter_bytes(plan):
+    return int(lib().dwm_plan_filter_bytes(plan))
+
+
+def dwm_plan_workspace_bytes(plan):
+    return int(lib().dwm_plan_workspace_bytes(plan))
+
+
+def dwm_plan_set_workspace(plan, ws_dev, nbytes):
+    _check(lib().dwm_plan_set_workspace(plan, ws_dev, nbytes), "dwm_plan_set_workspace")
+
+
+def dwm_plan_set_variant(plan, stage, variant):
+    _check(lib().dwm_plan_set_variant(plan, stage.encode(), variant), "dwm_plan_set_variant")
+
+
+def dwm_filter_transform(plan, w_dev, Ugw_dev, stream=None):
+    _check(lib().dwm_filter_transform(plan, w_dev, Ugw_dev, stream), "dwm_filter_transform")
+
+
+def dwm_conv_forward(plan, x_dev, Ugw_dev, y_dev, stream=None):
+    _check(lib().dwm_conv_forward(plan, x_dev, Ugw_dev, y_dev, stream), "dwm_conv_forward")
+
+
+def dwm_input_transform(plan, x_dev, stream=None):
+    _check(lib().dwm_input_transform(plan, x_dev, stream), "dwm_input_transform")
+
+
+def dwm_contract_output(plan, Ugw_dev, y_dev, stream=None):
+    _check(lib().dwm_contract_output(plan, Ugw_dev, y_dev, stream), "dwm_contract_output")

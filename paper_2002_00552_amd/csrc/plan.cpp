@@ -1,0 +1,247 @@
+// Host planner and C ABI of libdwm: the "Splitting" step on the kernel side
+// (paper Sec. 4.1: eq. 12 groups taps by index modulo the stride, eq. 8 cuts each group
+// into consecutive runs of three) plus the bookkeeping that lays the Winograd-domain
+// planes out in memory.  Pure integer logic; no GPU call is made in this file.
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "plan.hpp"
+
+namespace {
+
+using namespace dwm;
+
+long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
+
+// Split one kernel dimension of r taps at stride s into pieces, longest class first.
+// Within a phase the taps are cut 3,3,...,remainder from the low end (eq. 8; the number
+// of cuts is ceil(n/3)).  Returns the piece count or -1 if it exceeds kMaxPieces.
+int split_dimension(int r, int s, DevPiece* out, int start[4], int count[4])
+{
+    DevPiece tmp[kMaxPieces];
+    int n = 0;
+    const int phases = s < r ? s : r;  // phases beyond the kernel length hold no tap
+    for (int p = 0; p < phases; ++p) {
+        const int taps = (r - p + s - 1) / s;
+        for (int j = 0; j < taps; j += 3) {
+            if (n == kMaxPieces) return -1;
+            const int rest = taps - j;
+            tmp[n++] = DevPiece{p, j, rest < 3 ? rest : 3};
+        }
+    }
+    int m = 0;
+    for (int len = 3; len >= 1; --len) {
+        start[len] = m;
+        for (int i = 0; i < n; ++i)
+            if (tmp[i].l == len) out[m++] = tmp[i];
+        count[len] = m - start[len];
+    }
+    return n;
+}
+
+// A^T of F(2,l), row a, column f (Sec. 3.2 for l=3; the 2-tap and 1-tap cases use the
+// three- and two-multiplication forms whose entries are all 0/1).
+int at_entry(int l, int a, int f)
+{
+    static const int AT3[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
+    static const int AT2[2][3] = {{1, 1, 0}, {0, 1, 1}};
+    static const int AT1[2][2] = {{1, 0}, {0, 1}};
+    return l == 3 ? AT3[a][f] : l == 2 ? AT2[a][f] : AT1[a][f];
+}
+
+}  // namespace
+
+extern "C" {
+
+dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad)
+{
+    if (!out) return DWM_ERR_INVALID_ARG;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return DWM_ERR_INVALID_ARG;
+    if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return DWM_ERR_INVALID_ARG;
+    if (pad > (1 << 20) || H > (1 << 20) || W > (1 << 20)) return DWM_ERR_UNSUPPORTED;
+
+    dwm_plan* p = new (std::nothrow) dwm_plan;
+    if (!p) return DWM_ERR_ALLOC;
+    std::memset(p, 0, sizeof(*p));
+    DevPlan& d = p->d;
+    d.N = N; d.C = C; d.H = H; d.W = W; d.K = K; d.R = R; d.S = S; d.s = stride; d.P = pad;
+    d.OH = (H + 2 * pad - R) / stride + 1;
+    d.OW = (W + 2 * pad - S) / stride + 1;
+    d.TH = (d.OH + 1) / 2;
+    d.TW = (d.OW + 1) / 2;
+    const long long T = (long long)N * d.TH * d.TW;
+    const long long Tpad = round_up(T, kTAlign);
+    const long long Kpad = round_up(K, kKAlign);
+    const long long lim = (1LL << 31) - 1;
+
+    int sh[4], ch[4], sw[4], cw[4];
+    d.nh = split_dimension(R, stride, d.ph, sh, ch);
+    d.nw = split_dimension(S, stride, d.pw, sw, cw);
+    bool ok = d.nh > 0 && d.nw > 0 && Tpad < lim && (long long)N * K * d.OH * d.OW < lim &&
+              (long long)N * C * H * W < lim && (long long)K * C * R * S < lim;
+
+    long long u_off = 0, v_off = 0, mults = 0;
+    int n_parts = 0;
+    if (ok) {
+        d.T = (int)T; d.Tpad = (int)Tpad; d.Kpad = (int)Kpad;
+        for (int lh = 3; lh >= 1; --lh)
+            for (int lw = 3; lw >= 1; --lw) {
+                if (!ch[lh] || !cw[lw]) continue;
+                DevClass& q = d.cls[d.ncls];
+                q.lh = lh; q.lw = lw;
+                q.h0 = sh[lh]; q.hn = ch[lh]; q.w0 = sw[lw]; q.wn = cw[lw];
+                const long long L = (long long)q.hn * q.wn * C;
+                const long long Lpad = round_up(L, kLAlign);
+                const int planes = (lh + 1) * (lw + 1);
+                if (Lpad >= lim) { ok = false; break; }
+                q.L = (int)L; q.Lpad = (int)Lpad;
+                q.row0 = d.rows_total; q.plane0 = p->planes.n;
+                q.u_off = u_off; q.v_off = v_off;
+                d.rows_total += q.Lpad;
+                for (int fh = 0; fh <= lh; ++fh)
+                    for (int fw = 0; fw <= lw; ++fw) {
+                        DevPlaneEntry& e = p->planes.e[p->planes.n++];
+                        const long long pl = fh * (lw + 1) + fw;
+                        e.u_off64 = (uint32_t)((u_off + pl * Kpad * Lpad) / 64);
+                        e.v_off64 = (uint32_t)((v_off + pl * Lpad * Tpad) / 64);
+                        e.Lpad = q.Lpad;
+                        int coef = 0;
+                        for (int a = 0; a < 2; ++a)
+                            for (int b = 0; b < 2; ++b) {
+                                const int v = at_entry(lh, a, fh) * at_entry(lw, b, fw);
+                                coef |= (v == 0 ? 0 : v > 0 ? 1 : 3) << (2 * (2 * a + b));
+                            }
+                        e.coef = coef;
+                    }
+                u_off += planes * Kpad * Lpad;
+                v_off += planes * Lpad * Tpad;
+                if (u_off >= lim * 32 || v_off >= lim * 32) { ok = false; break; }
+                for (int a = 0; a < q.hn; ++a)
+                    for (int b = 0; b < q.wn; ++b) {
+                        dwm_part_t& pt = p->parts[n_parts++];
+                        pt.phase_h = d.ph[q.h0 + a].p; pt.off_h = d.ph[q.h0 + a].j; pt.len_h = lh;
+                        pt.phase_w = d.pw[q.w0 + b].p; pt.off_w = d.pw[q.w0 + b].j; pt.len_w = lw;
+                        pt.cls = d.ncls; pt.slot = a * q.wn + b;
+                        mults += planes;
+                    }
+                ++d.ncls;
+            }
+    }
+    if (!ok) {
+        delete p;
+        return DWM_ERR_UNSUPPORTED;
+    }
+    p->filter_floats = (size_t)u_off;
+    p->ws_floats = (size_t)v_off;
+    p->ws = nullptr;
+    p->variant_input = p->variant_contract = -1;
+
+    dwm_plan_info_t& in = p->info;
+    in.N = N; in.C = C; in.H = H; in.W = W; in.K = K; in.R = R; in.S = S; in.stride = stride; in.pad = pad;
+    in.OH = d.OH; in.OW = d.OW; in.TH = d.TH; in.TW = d.TW; in.T = T;
+    in.n_parts = n_parts; in.n_classes = d.ncls; in.n_planes = p->planes.n;
+    in.mults_per_tile = mults;
+    in.direct_flops = 2.0 * N * K * C * R * S * d.OH * d.OW;
+    in.winograd_flops = 2.0 * (double)mults * C * K * (double)T;
+    in.Kpad = d.Kpad; in.Tpad = d.Tpad;
+    *out = p;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_destroy(dwm_plan_t* plan)
+{
+    if (!plan) return DWM_ERR_INVALID_ARG;
+    delete plan;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_info(const dwm_plan_t* plan, dwm_plan_info_t* info)
+{
+    if (!plan || !info) return DWM_ERR_INVALID_ARG;
+    *info = plan->info;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_part(const dwm_plan_t* plan, int i, dwm_part_t* part)
+{
+    if (!plan || !part || i < 0 || i >= plan->info.n_parts) return DWM_ERR_INVALID_ARG;
+    *part = plan->parts[i];
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls)
+{
+    if (!plan || !cls || i < 0 || i >= plan->d.ncls) return DWM_ERR_INVALID_ARG;
+    const dwm::DevClass& q = plan->d.cls[i];
+    cls->len_h = q.lh; cls->len_w = q.lw; cls->n_parts = q.hn * q.wn;
+    cls->L = q.L; cls->Lpad = q.Lpad; cls->u_offset = q.u_off; cls->v_offset = q.v_off;
+    return DWM_OK;
+}
+
+size_t dwm_plan_filter_bytes(const dwm_plan_t* plan) { return plan ? plan->filter_floats * sizeof(float) : 0; }
+size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan) { return plan ? plan->ws_floats * sizeof(float) : 0; }
+
+dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size_t bytes)
+{
+    if (!plan) return DWM_ERR_INVALID_ARG;
+    if (!ws_dev || ((uintptr_t)ws_dev & 255u) || bytes < plan->ws_floats * sizeof(float)) return DWM_ERR_WORKSPACE;
+    plan->ws = static_cast<float*>(ws_dev);
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int variant)
+{
+    if (!plan || !stage) return DWM_ERR_INVALID_ARG;
+    if (!std::strcmp(stage, "input")) plan->variant_input = variant;
+    else if (!std::strcmp(stage, "contract")) plan->variant_contract = variant;
+    else return DWM_ERR_INVALID_ARG;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_filter_transform(const dwm_plan_t* plan, const float* w_dev, float* Ugw_dev, void* stream)
+{
+    if (!plan || !w_dev || !Ugw_dev) return DWM_ERR_INVALID_ARG;
+    return dwm::launch_filter_transform(*plan, w_dev, Ugw_dev, stream);
+}
+
+dwm_status_t dwm_input_transform(const dwm_plan_t* plan, const float* x_dev, void* stream)
+{
+    if (!plan || !x_dev) return DWM_ERR_INVALID_ARG;
+    if (!plan->ws) return DWM_ERR_WORKSPACE;
+    return dwm::launch_input_transform(*plan, x_dev, plan->ws, stream);
+}
+
+dwm_status_t dwm_contract_output(const dwm_plan_t* plan, const float* Ugw_dev, float* y_dev, void* stream)
+{
+    if (!plan || !Ugw_dev || !y_dev) return DWM_ERR_INVALID_ARG;
+    if (!plan->ws) return DWM_ERR_WORKSPACE;
+    return dwm::launch_contract_output(*plan, Ugw_dev, plan->ws, y_dev, stream);
+}
+
+dwm_status_t dwm_conv_forward(const dwm_plan_t* plan, const float* x_dev, const float* Ugw_dev,
+                              float* y_dev, void* stream)
+{
+    if (!plan || !x_dev || !Ugw_dev || !y_dev) return DWM_ERR_INVALID_ARG;
+    if (!plan->ws) return DWM_ERR_WORKSPACE;
+    dwm_status_t st = dwm::launch_input_transform(*plan, x_dev, plan->ws, stream);
+    if (st != DWM_OK) return st;
+    return dwm::launch_contract_output(*plan, Ugw_dev, plan->ws, y_dev, stream);
+}
+
+const char* dwm_status_string(dwm_status_t status)
+{
+    switch (status) {
+        case DWM_OK: return "ok";
+        case DWM_ERR_INVALID_ARG: return "invalid argument";
+        case DWM_ERR_UNSUPPORTED: return "unsupported shape";
+        case DWM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case DWM_ERR_ALLOC: return "host allocation failed";
+        case DWM_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

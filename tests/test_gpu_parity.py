@@ -1,0 +1,207 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the FP64 oracle.
+
+Bar (stated by the task's target): max |y_gpu - y_ref| / max |y_ref| <= 1e-4 with y_ref the
+FP64 direct convolution of the same float32 inputs.  Stage outputs (U, V) are exact up to
+fp32 rounding of a handful of additions, so they get 1e-6 relative to their max.
+"""
+import numpy as np
+import pytest
+import torch
+
+import dwm_workloads as wl
+import oracle
+import paper_2002_00552_amd as dwm
+from dwm_gpu import Runner, conv
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _rand(N, C, H, W, K, R, S, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, R, S)) * np.sqrt(2.0 / (C * R * S))).astype(np.float32)
+    return x, w
+
+
+def _relerr(y, ref):
+    return float(np.max(np.abs(y.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def _part_tuple(pt):
+    return (pt.phase_h, pt.off_h, pt.len_h, pt.phase_w, pt.off_w, pt.len_w)
+
+
+# ---- stage parity: filter transform and input transform against the oracle's stages ----
+
+STAGE_SHAPES = [  # N, C, H, W, K, R, S, stride, pad
+    (2, 3, 13, 15, 5, 5, 5, 1, 2),
+    (1, 4, 17, 12, 6, 3, 3, 2, 1),
+    (2, 3, 23, 22, 4, 7, 7, 2, 3),
+    (1, 2, 31, 29, 3, 11, 11, 4, 0),
+    (1, 5, 9, 10, 2, 1, 7, 1, 3),
+    (1, 20, 8, 8, 130, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", STAGE_SHAPES)
+def test_filter_transform_matches_oracle(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand(*shape[:7], seed=11)
+    r = Runner(*shape)
+    r.Ugw.fill_(float("nan"))
+    r.set_filter(w)
+    torch.cuda.synchronize()
+    U = r.Ugw.cpu().numpy()
+    assert np.all(np.isfinite(U))  # padding included: it must be written (as zeros)
+    classes, Kpad = r.classes(), r.info.Kpad
+    seen = np.zeros(U.size, bool)
+    for pt in r.parts():
+        q = classes[pt.cls]
+        th, tw = q.len_h + 1, q.len_w + 1
+        Ug = U[q.u_offset:q.u_offset + th * tw * Kpad * q.Lpad].reshape(th, tw, Kpad, q.Lpad)
+        ref = oracle.part_filter_transform(w, s, _part_tuple(pt))  # [K][C][th][tw]
+        got = Ug[:, :, :K, pt.slot * C:(pt.slot + 1) * C].transpose(2, 3, 0, 1)
+        assert np.max(np.abs(got - ref)) <= 1e-6 * max(np.max(np.abs(ref)), 1e-30)
+        # padding rows/columns are zero
+        assert np.all(Ug[:, :, K:, :] == 0) and np.all(Ug[:, :, :, q.L:] == 0)
+    r.close()
+
+
+@pytest.mark.parametrize("shape", STAGE_SHAPES)
+def test_input_transform_matches_oracle(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand(*shape[:7], seed=12)
+    r = Runner(*shape)
+    xd = torch.from_numpy(x).cuda()
+    dwm.dwm_input_transform(r.plan, xd.data_ptr(), r.stream())
+    torch.cuda.synchronize()
+    V = r.ws.cpu().numpy()
+    info, classes = r.info, r.classes()
+    TH, TW, T, Tpad = info.TH, info.TW, info.T, info.Tpad
+    for pt in r.parts():
+        q = classes[pt.cls]
+        th, tw = q.len_h + 1, q.len_w + 1
+        Vg = V[q.v_offset:q.v_offset + th * tw * q.Lpad * Tpad].reshape(th, tw, q.Lpad, Tpad)
+        assert np.all(Vg[:, :, q.L:, :] == 0)  # padded reduction rows must be zero
+        for n in range(N):
+            ref = oracle.part_input_transform(x, R, S, s, P, _part_tuple(pt), n)  # [C][TH][TW][th][tw]
+            got = Vg[:, :, pt.slot * C:(pt.slot + 1) * C, n * TH * TW:(n + 1) * TH * TW]
+            got = got.reshape(th, tw, C, TH, TW).transpose(2, 3, 4, 0, 1)
+            assert np.max(np.abs(got - ref)) <= 1e-6 * max(np.max(np.abs(ref)), 1e-30), (_part_tuple(pt), n)
+    r.close()
+
+
+# ---- end-to-end parity on small shapes that span several tiles and ragged tails ----
+
+E2E_SHAPES = [
+    (1, 16, 32, 32, 16, 5, 5, 1, 2),     # benchmark config 1
+    (2, 3, 13, 15, 5, 5, 5, 1, 2),
+    (3, 8, 19, 21, 70, 3, 3, 2, 1),      # K crosses a 64 tile, odd output
+    (2, 24, 14, 14, 40, 7, 7, 1, 3),
+    (2, 3, 37, 35, 33, 7, 7, 2, 3),
+    (2, 3, 43, 47, 20, 11, 11, 4, 0),    # odd OH/OW, 16 phases
+    (1, 5, 9, 10, 2, 1, 7, 1, 3),        # R != S
+    (1, 6, 10, 9, 3, 7, 1, 1, 3),
+    (2, 17, 12, 12, 9, 1, 1, 1, 0),      # 1x1: a single one-tap part
+    (1, 7, 11, 11, 4, 1, 1, 2, 0),       # stride beyond the kernel
+    (1, 4, 16, 16, 8, 2, 2, 2, 0),
+    (1, 3, 20, 18, 5, 4, 6, 3, 2),       # pad not a multiple of the stride
+    (1, 2, 12, 12, 3, 12, 12, 1, 0),     # a single output pixel
+    (5, 130, 7, 7, 129, 3, 3, 1, 1),     # reduction and K just past tile boundaries
+    (70, 2, 6, 6, 3, 3, 3, 1, 1),        # many images, T crosses several T tiles
+    (1, 3, 9, 300, 4, 3, 5, 1, 2),       # one long row
+]
+
+
+@pytest.mark.parametrize("shape", E2E_SHAPES)
+def test_forward_matches_fp64_direct(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand(*shape[:7], seed=100 + R * 7 + S)
+    ref = oracle.direct_f64(x, w, s, P)
+    y = conv(x, w, s, P)
+    assert y.shape == ref.shape
+    assert np.all(np.isfinite(y))
+    assert _relerr(y, ref) <= TOL, shape
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(3, 8, 19, 21, 70, 3, 3, 2, 1), (2, 24, 30, 30, 140, 7, 7, 1, 3),
+                                   (2, 3, 43, 47, 20, 11, 11, 4, 0)])
+def test_every_contraction_variant(shape, variant):
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand(*shape[:7], seed=5)
+    ref = oracle.direct_f64(x, w, s, P)
+    y = conv(x, w, s, P, variants={"contract": variant})
+    assert _relerr(y, ref) <= TOL
+
+
+def test_forward_is_deterministic_and_plan_reusable():
+    shape = (2, 24, 14, 14, 40, 7, 7, 1, 3)
+    x, w = _rand(*shape[:7], seed=9)
+    r = Runner(*shape)
+    r.set_filter(w)
+    y1 = r.forward(x).copy()
+    r.y.fill_(float("nan"))
+    y2 = r.forward(x).copy()
+    x2 = (x * 0.5).astype(np.float32)
+    y3 = r.forward(x2)
+    assert np.array_equal(y1, y2)
+    assert _relerr(y3, oracle.direct_f64(x2, w, 1, 3)) <= TOL
+    r.close()
+
+
+def test_staged_calls_equal_the_fused_entry_point():
+    shape = (2, 5, 21, 20, 9, 5, 5, 2, 2)
+    x, w = _rand(*shape[:7], seed=10)
+    r = Runner(*shape)
+    r.set_filter(w)
+    y1 = r.forward(x).copy()
+    r.y.fill_(float("nan"))
+    dwm.dwm_input_transform(r.plan, r.x.data_ptr(), r.stream())
+    dwm.dwm_contract_output(r.plan, r.Ugw.data_ptr(), r.y.data_ptr(), r.stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(y1, r.y.cpu().numpy())
+    r.close()
+
+
+def test_runs_on_a_side_stream():
+    shape = (1, 16, 32, 32, 16, 5, 5, 1, 2)
+    x, w = _rand(*shape[:7], seed=13)
+    ref = oracle.direct_f64(x, w, 1, 2)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        y = conv(x, w, 1, 2)
+    assert _relerr(y, ref) <= TOL
+
+
+# ---- the five benchmark layers at full size, in the launch configuration bench.py times ----
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
+def test_benchmark_layers_full_size(index):
+    """Whole layer on the GPU; the oracle computes 40 000 sampled outputs one by one (all of
+    them for config 1), plus the image border where padding and ragged tiles live."""
+    L = wl.CONFIGS[index]
+    x, w = wl.make_layer_tensors(L, index)
+    y = conv(x, w, L.stride, L.pad)
+    OH, OW = wl.out_hw(L)
+    assert y.shape == (L.N, L.K, OH, OW) and np.all(np.isfinite(y))
+    rng = np.random.default_rng(4242 + index)
+    if y.size <= 200000:
+        idx = np.arange(y.size)
+    else:
+        idx = rng.choice(y.size, 40000, replace=False)
+        # last image / last filter / last row and column: the ragged ends of every tiling
+        n, k = L.N - 1, L.K - 1
+        edge = [((n * L.K + k) * OH + OH - 1) * OW + j for j in range(OW)]
+        edge += [((n * L.K + k) * OH + i) * OW + OW - 1 for i in range(OH)]
+        edge += [j for j in range(OW)]
+        idx = np.unique(np.concatenate([idx, np.array(edge)]))
+    ref = oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
+    got = y.ravel()[idx].astype(np.float64)
+    scale = np.max(np.abs(ref))
+    assert np.max(np.abs(got - ref)) / scale <= TOL, L.name
+    mse = float(np.mean((got - ref) ** 2))
+    print("%s: max rel err %.3e, MSE %.3e, log10(MSE)+10 = %.2f" %
+          (L.name, np.max(np.abs(got - ref)) / scale, mse, np.log10(mse) + 10))

@@ -1,0 +1,133 @@
+"""CPU tests of the library's host side: exported symbols, the planner's decomposition
+(against Table 3 and the paper's printed 5x5 examples), layout bookkeeping and error
+codes.  No compute call is made, so no GPU is needed."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import dwm_workloads as wl
+import paper_2002_00552_amd as dwm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "dwm.h")).read()
+    declared = sorted(set(re.findall(r"DWM_API[^;(]*?\b(dwm_\w+)\s*\(", header)))
+    assert len(declared) >= 14
+    raw = ctypes.CDLL(dwm.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+    assert declared == dwm.EXPORTS  # the binding carries the same names
+
+
+def _plan(*a):
+    p = dwm.dwm_plan_create(*a)
+    return p, dwm.dwm_plan_info(p)
+
+
+def test_table3_counts_from_the_planner(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "table3_mults.txt"))
+            if l.strip() and not l.startswith("#")]
+    for k, s, direct_p, dwm_p, speed_p in rows:
+        k, s = int(k), int(s)
+        # 14x14 output: H chosen so that OH = 14 with same-style padding
+        H = 14 * s
+        p, info = _plan(1, 1, H, H, 1, k, k, s, k // 2)
+        assert info.OH >= 14 - 1
+        m = info.mults_per_tile
+        assert abs(49 * m - float(dwm_p)) <= 0.5 * 10 ** max(len(str(49 * m)) - 3, 0), (k, s, m)
+        assert abs(196 * k * k / (49 * m) - float(speed_p)) <= 0.005 + 1e-9
+        dwm.dwm_plan_destroy(p)
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_5x5_splits_as_the_paper_says(stride):
+    p, info = _plan(1, 1, 16, 16, 1, 5, 5, stride, 2)
+    sizes = sorted((dwm.dwm_plan_part(p, i).len_h, dwm.dwm_plan_part(p, i).len_w) for i in range(info.n_parts))
+    assert sizes == [(2, 2), (2, 3), (3, 2), (3, 3)]
+    dwm.dwm_plan_destroy(p)
+
+
+@pytest.mark.parametrize("R,S,s", [(r, q, s) for r in (1, 2, 3, 5, 7, 8, 11, 12) for q in (1, 3, 4, 7, 11)
+                                   for s in (1, 2, 3, 4, 6)])
+def test_taps_partition_and_layout(R, S, s):
+    C, K = 5, 7
+    p, info = _plan(2, C, 40, 41, K, R, S, s, 3)
+    cover = np.zeros((R, S), int)
+    classes = [dwm.dwm_plan_class(p, i) for i in range(info.n_classes)]
+    slots = {}
+    mults = 0
+    for i in range(info.n_parts):
+        pt = dwm.dwm_plan_part(p, i)
+        q = classes[pt.cls]
+        assert (q.len_h, q.len_w) == (pt.len_h, pt.len_w)
+        assert 0 <= pt.slot < q.n_parts and (pt.cls, pt.slot) not in slots
+        slots[(pt.cls, pt.slot)] = i
+        assert pt.phase_h < s and pt.phase_w < s
+        mults += (pt.len_h + 1) * (pt.len_w + 1)
+        for a in range(pt.len_h):
+            for b in range(pt.len_w):
+                cover[s * (pt.off_h + a) + pt.phase_h, s * (pt.off_w + b) + pt.phase_w] += 1
+    assert np.all(cover == 1)
+    assert mults == info.mults_per_tile
+    assert info.n_planes == sum((q.len_h + 1) * (q.len_w + 1) for q in classes)
+    # classes tile the two buffers without overlap
+    u_end = v_end = 0
+    for q in classes:
+        assert q.L == q.n_parts * C and q.Lpad >= q.L and q.Lpad % 16 == 0
+        assert q.u_offset == u_end and q.v_offset == v_end
+        planes = (q.len_h + 1) * (q.len_w + 1)
+        u_end += planes * info.Kpad * q.Lpad
+        v_end += planes * q.Lpad * info.Tpad
+    assert dwm.dwm_plan_filter_bytes(p) == 4 * u_end and dwm.dwm_plan_workspace_bytes(p) == 4 * v_end
+    assert info.Kpad >= K and info.Tpad >= info.T == 2 * info.TH * info.TW
+    dwm.dwm_plan_destroy(p)
+
+
+def test_benchmark_configs_plan_as_expected():
+    want = {0: (4, 49), 1: (4, 25), 2: (9, 100), 3: (9, 100), 4: (16, 225)}
+    for i, L in enumerate(wl.CONFIGS):
+        p, info = _plan(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+        assert (info.n_parts, info.mults_per_tile) == want[i]
+        assert info.direct_flops == wl.direct_flops(L)
+        assert (info.OH, info.OW) == wl.out_hw(L)
+        dwm.dwm_plan_destroy(p)
+
+
+def test_error_codes():
+    h = ctypes.c_void_p()
+    L = dwm.lib()
+    ok = (1, 1, 8, 8, 1, 3, 3, 1, 1)
+    assert L.dwm_plan_create(None, *ok) == dwm.DWM_ERR_INVALID_ARG
+    for pos in range(7):
+        bad = list(ok)
+        bad[pos] = 0
+        assert L.dwm_plan_create(ctypes.byref(h), *bad) == dwm.DWM_ERR_INVALID_ARG, pos
+    assert L.dwm_plan_create(ctypes.byref(h), 1, 1, 8, 8, 1, 3, 3, 0, 1) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_plan_create(ctypes.byref(h), 1, 1, 8, 8, 1, 3, 3, 1, -1) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_plan_create(ctypes.byref(h), 1, 1, 2, 2, 1, 3, 3, 1, 0) == dwm.DWM_ERR_INVALID_ARG  # empty output
+    assert L.dwm_plan_create(ctypes.byref(h), 1, 1, 80, 80, 1, 49, 3, 1, 0) == dwm.DWM_ERR_UNSUPPORTED  # 17 pieces
+    assert L.dwm_plan_create(ctypes.byref(h), 1, 1, 80, 80, 1, 48, 3, 1, 0) == dwm.DWM_OK
+    plan = h
+    # no workspace yet: every stage that needs it refuses before touching the GPU
+    one = ctypes.c_void_p(256)
+    assert L.dwm_conv_forward(plan, one, one, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_input_transform(plan, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_contract_output(plan, one, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_conv_forward(plan, None, one, one, None) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_filter_transform(plan, None, one, None) == dwm.DWM_ERR_INVALID_ARG
+    need = dwm.dwm_plan_workspace_bytes(plan)
+    assert L.dwm_plan_set_workspace(plan, ctypes.c_void_p(4096), need - 1) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_plan_set_workspace(plan, ctypes.c_void_p(4096 + 4), need) == dwm.DWM_ERR_WORKSPACE  # misaligned
+    assert L.dwm_plan_set_workspace(plan, None, need) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_plan_set_variant(plan, b"nonsense", 0) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_plan_part(plan, 10 ** 6, ctypes.byref(dwm.dwm_part_t())) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_plan_destroy(plan) == dwm.DWM_OK
+    assert L.dwm_plan_destroy(None) == dwm.DWM_ERR_INVALID_ARG
+    with pytest.raises(dwm.DwmError):
+        dwm.dwm_plan_create(0, 1, 1, 1, 1, 1, 1, 1, 0)
+    assert "workspace" in dwm.dwm_status_string(dwm.DWM_ERR_WORKSPACE)
