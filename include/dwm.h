@@ -109,7 +109,8 @@ DWM_API dwm_status_t dwm_plan_info(const dwm_plan_t* plan, dwm_plan_info_t* info
 DWM_API dwm_status_t dwm_plan_part(const dwm_plan_t* plan, int i, dwm_part_t* part);     /* i < n_parts   */
 DWM_API dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls);   /* i < n_classes */
 
-/* Bytes of the transformed filter Ugw and of the workspace (the transformed input V). */
+/* Bytes of the transformed filter Ugw and of the workspace (the transformed input V, plus
+ * partial output tiles and arrival counters of the contraction's split tiles). */
 DWM_API size_t dwm_plan_filter_bytes(const dwm_plan_t* plan);
 DWM_API size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan);
 
@@ -118,7 +119,12 @@ DWM_API size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan);
 DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size_t bytes);
 
 /* Pick a kernel variant for a stage ("input", "contract"); variant < 0 restores the
- * planner's own choice.  For tuning and tests; results are the same up to fp32 rounding. */
+ * planner's own choice.  For tuning and tests; results are the same up to fp32 rounding.
+ * The workspace size depends on the contraction variant: choose it BEFORE asking
+ * dwm_plan_workspace_bytes.  DWM_ERR_INVALID_ARG for an unknown stage or a variant that does
+ * not apply to this plan; DWM_ERR_WORKSPACE (variant unchanged) if a workspace was already
+ * handed over and is too small for the new variant.  After a change of the contraction
+ * variant, dwm_input_transform must run again before dwm_contract_output. */
 DWM_API dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int variant);
 
 /*
@@ -142,7 +148,9 @@ DWM_API dwm_status_t dwm_conv_forward(const dwm_plan_t* plan, const float* x_dev
  * dwm_input_transform fills the workspace with V (Sec. 4.1 "Splitting" of the input and
  * "Transformation"); dwm_contract_output reads V from the workspace and does the
  * "Calculation", "Detransformation" and "Aggregation" steps.  Calling them in this order
- * on one stream is exactly dwm_conv_forward. */
+ * on one stream is exactly dwm_conv_forward.  dwm_contract_output may be repeated on the
+ * same V; it must not be the first call on a fresh workspace (dwm_input_transform also
+ * clears the arrival counters the contraction uses). */
 DWM_API dwm_status_t dwm_input_transform(const dwm_plan_t* plan, const float* x_dev, void* stream);
 DWM_API dwm_status_t dwm_contract_output(const dwm_plan_t* plan, const float* Ugw_dev, float* y_dev, void* stream);
 

@@ -50,7 +50,54 @@ int at_entry(int l, int a, int f)
     return l == 3 ? AT3[a][f] : l == 2 ? AT2[a][f] : AT1[a][f];
 }
 
+int default_contract_variant(int lgran)
+{
+    return lgran >= 64 ? 12 : lgran >= 32 ? 11 : 10;
+}
+
 }  // namespace
+
+namespace dwm {
+
+bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
+{
+    const ContractVariant* cv = nullptr;
+    for (int i = 0; i < kNumContractVariants; ++i)
+        if (kContractVariants[i].id == variant) cv = &kContractVariants[i];
+    if (!cv || p.lgran % cv->lc != 0) return false;
+    ContractGeometry g{};
+    g.variant = variant;
+    g.nkt = (p.d.K + cv->kt() - 1) / cv->kt();
+    g.ntt = (p.d.T + cv->tt() - 1) / cv->tt();
+    const long long ntiles = (long long)g.nkt * g.ntt;
+    if (ntiles > 0x3fffffffLL) return false;
+    g.ntiles = (int)ntiles;
+    g.full8 = 8 * g.nkt * (g.ntt / 8);
+    long long n_iter = 0;
+    for (int i = 0; i < p.planes.n; ++i) n_iter += p.planes.e[i].Lpad / cv->lc;
+    if (n_iter > 0x3fffffLL) return false;
+    g.n_iter = (int)n_iter;
+    // Whole tiles for as many full rounds of the CUs as there are; the rest (less than one
+    // tile per CU) is cut into equal iteration ranges unless it nearly fills a round anyway.
+    g.n_full = g.ntiles / kNumCUs * kNumCUs;
+    int rest = g.ntiles - g.n_full;
+    if (rest * 10 >= kNumCUs * 9) { g.n_full = g.ntiles; rest = 0; }
+    g.n_sk_tiles = rest;
+    if (rest > 0) {
+        const long long total = (long long)rest * g.n_iter;
+        long long wgs = total < kNumCUs ? total : kNumCUs;
+        const long long ipw = (total + wgs - 1) / wgs;
+        wgs = (total + ipw - 1) / ipw;
+        g.sk_wgs = (int)wgs;
+        g.sk_ipw = (int)ipw;
+        g.sk_maxc = (int)((g.n_iter - 1) / ipw) + 2;
+        g.partial_floats = (size_t)rest * g.sk_maxc * cv->kt() * cv->tt() * 4;
+    }
+    *out = g;
+    return true;
+}
+
+}  // namespace dwm
 
 extern "C" {
 
@@ -83,6 +130,22 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     bool ok = d.nh > 0 && d.nw > 0 && Tpad < lim && (long long)N * K * d.OH * d.OW < lim &&
               (long long)N * C * H * W < lim && (long long)K * C * R * S < lim;
 
+    // Reduction granularity: the largest of 64/32/16 that costs at most 5 % more padded
+    // rows than 16 does (long reductions can then be staged in deeper chunks).
+    int lgran = kLAlign;
+    if (ok) {
+        long long rows[3] = {0, 0, 0};
+        const int cand[3] = {64, 32, 16};
+        for (int lh = 3; lh >= 1; --lh)
+            for (int lw = 3; lw >= 1; --lw) {
+                if (!ch[lh] || !cw[lw]) continue;
+                const long long L = (long long)ch[lh] * cw[lw] * C;
+                for (int g = 0; g < 3; ++g) rows[g] += (lh + 1) * (lw + 1) * round_up(L, cand[g]);
+            }
+        for (int g = 2; g >= 0; --g)
+            if (rows[g] * 100 <= rows[2] * 105) lgran = cand[g];
+    }
+
     long long u_off = 0, v_off = 0, mults = 0;
     int n_parts = 0;
     if (ok) {
@@ -94,7 +157,7 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
                 q.lh = lh; q.lw = lw;
                 q.h0 = sh[lh]; q.hn = ch[lh]; q.w0 = sw[lw]; q.wn = cw[lw];
                 const long long L = (long long)q.hn * q.wn * C;
-                const long long Lpad = round_up(L, kLAlign);
+                const long long Lpad = round_up(L, lgran);
                 const int planes = (lh + 1) * (lw + 1);
                 if (Lpad >= lim) { ok = false; break; }
                 q.L = (int)L; q.Lpad = (int)Lpad;
@@ -135,9 +198,15 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
         return DWM_ERR_UNSUPPORTED;
     }
     p->filter_floats = (size_t)u_off;
-    p->ws_floats = (size_t)v_off;
+    p->v_floats = (size_t)v_off;
     p->ws = nullptr;
-    p->variant_input = p->variant_contract = -1;
+    p->ws_bytes = 0;
+    p->lgran = lgran;
+    p->variant_input = -1;
+    if (!dwm::contract_geometry(*p, default_contract_variant(lgran), &p->geo)) {
+        delete p;
+        return DWM_ERR_UNSUPPORTED;
+    }
 
     dwm_plan_info_t& in = p->info;
     in.N = N; in.C = C; in.H = H; in.W = W; in.K = K; in.R = R; in.S = S; in.stride = stride; in.pad = pad;
@@ -182,22 +251,34 @@ dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls)
 }
 
 size_t dwm_plan_filter_bytes(const dwm_plan_t* plan) { return plan ? plan->filter_floats * sizeof(float) : 0; }
-size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan) { return plan ? plan->ws_floats * sizeof(float) : 0; }
+size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan) { return plan ? plan->ws_need_bytes() : 0; }
 
 dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size_t bytes)
 {
     if (!plan) return DWM_ERR_INVALID_ARG;
-    if (!ws_dev || ((uintptr_t)ws_dev & 255u) || bytes < plan->ws_floats * sizeof(float)) return DWM_ERR_WORKSPACE;
+    if (!ws_dev || ((uintptr_t)ws_dev & 255u) || bytes < plan->ws_need_bytes()) return DWM_ERR_WORKSPACE;
     plan->ws = static_cast<float*>(ws_dev);
+    plan->ws_bytes = bytes;
     return DWM_OK;
 }
 
 dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int variant)
 {
     if (!plan || !stage) return DWM_ERR_INVALID_ARG;
-    if (!std::strcmp(stage, "input")) plan->variant_input = variant;
-    else if (!std::strcmp(stage, "contract")) plan->variant_contract = variant;
-    else return DWM_ERR_INVALID_ARG;
+    if (!std::strcmp(stage, "input")) {
+        plan->variant_input = variant;
+        return DWM_OK;
+    }
+    if (std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
+    dwm::ContractGeometry g;
+    if (!dwm::contract_geometry(*plan, variant < 0 ? default_contract_variant(plan->lgran) : variant, &g))
+        return DWM_ERR_INVALID_ARG;
+    const dwm::ContractGeometry old = plan->geo;
+    plan->geo = g;
+    if (plan->ws && plan->ws_bytes < plan->ws_need_bytes()) {
+        plan->geo = old;  // the workspace already handed over cannot hold this variant's partial outputs
+        return DWM_ERR_WORKSPACE;
+    }
     return DWM_OK;
 }
 

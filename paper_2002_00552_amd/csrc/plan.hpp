@@ -12,7 +12,7 @@ constexpr int kMaxClasses = 9;  // (len_h, len_w) in {1,2,3}^2
 constexpr int kMaxPlanes = 81;  // sum over classes of (len_h+1)(len_w+1) = (2+3+4)^2
 constexpr int kKAlign = 128;    // Kpad is a multiple of this (largest K tile of any variant)
 constexpr int kTAlign = 256;    // Tpad is a multiple of this (largest T tile of any variant)
-constexpr int kLAlign = 16;     // Lpad is a multiple of this (largest reduction chunk)
+constexpr int kLAlign = 16;     // Lpad is a multiple of this at least (smallest reduction chunk)
 
 // A 1-D piece (Sec. 4.1): phase p, offset j inside the phase's tap list, length l.
 struct DevPiece {
@@ -57,6 +57,39 @@ struct PlaneTable {
     DevPlaneEntry e[kMaxPlanes];
 };
 
+// Shape of one contraction kernel variant: workgroup of WGM x WGN waves, each wave owning
+// (32*WM) x (32*WN) of the (K tile) x (T tile); reduction staged LC steps at a time
+// through NS LDS stages.
+struct ContractVariant {
+    int id, wgm, wgn, wm, wn, lc, ns;
+    int kt() const { return 32 * wm * wgm; }
+    int tt() const { return 32 * wn * wgn; }
+};
+constexpr ContractVariant kContractVariants[] = {
+    {10, 2, 2, 1, 1, 16, 4}, {11, 2, 2, 1, 1, 32, 3}, {12, 2, 2, 1, 1, 64, 2}, {13, 4, 2, 1, 1, 32, 2},
+    {14, 2, 4, 1, 1, 32, 3}, {15, 2, 2, 2, 1, 32, 2}, {16, 2, 2, 1, 2, 32, 2}, {17, 2, 2, 1, 1, 16, 2},
+};
+constexpr int kNumContractVariants = sizeof(kContractVariants) / sizeof(kContractVariants[0]);
+constexpr int kNumCUs = 256;  // MI355X
+
+// How the (K tile, T tile) grid is shared out for one variant.  Workgroups 0..n_full-1
+// each own one whole tile.  The remaining n_sk_tiles tiles (fewer than one per CU) are
+// cut along the flattened (plane, chunk) iteration axis into sk_wgs equal ranges, one
+// per extra workgroup, so that every CU ends up with the same amount of MFMA work; a
+// tile shared by several workgroups is summed from per-workgroup partial outputs by
+// whichever of them finishes last.
+struct ContractGeometry {
+    int variant;
+    int nkt, ntt, ntiles, full8;
+    int n_iter;      // chunks per tile = sum over planes of Lpad/LC
+    int n_full;      // whole-tile workgroups
+    int n_sk_tiles;  // tiles handled by the stream-K workgroups
+    int sk_wgs;      // stream-K workgroups
+    int sk_ipw;      // iterations per stream-K workgroup
+    int sk_maxc;     // partial-output slots per shared tile
+    size_t partial_floats;
+};
+
 }  // namespace dwm
 
 // The opaque plan of the C ABI.
@@ -65,13 +98,24 @@ struct dwm_plan {
     dwm::PlaneTable planes;
     dwm_plan_info_t info;
     dwm_part_t parts[dwm::kMaxPieces * dwm::kMaxPieces];
-    size_t filter_floats, ws_floats;
+    size_t filter_floats, v_floats;
+    dwm::ContractGeometry geo;
     float* ws;
-    int variant_input, variant_contract;  // < 0: planner's choice
+    size_t ws_bytes;
+    int lgran;  // every class's Lpad is a multiple of this (16, 32 or 64)
+    int variant_input;  // < 0: planner's choice
+
+    // workspace layout: [ V | partial outputs | arrival counters ]
+    size_t ws_need_bytes() const { return (v_floats + geo.partial_floats) * sizeof(float) + counters_bytes(); }
+    size_t counters_bytes() const { return ((size_t)geo.n_sk_tiles * sizeof(int) + 255) / 256 * 256; }
+    float* sk_partial() const { return ws ? ws + v_floats : nullptr; }
+    int* sk_counters() const { return ws ? reinterpret_cast<int*>(ws + v_floats + geo.partial_floats) : nullptr; }
 };
 
 namespace dwm {
-// kernels.hip
+// plan.cpp: geometry of a contraction variant for this plan; false if the variant does not apply
+bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out);
+// transforms.hip, contract.hip
 dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U, void* stream);
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream);
 dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const float* V, float* y, void* stream);

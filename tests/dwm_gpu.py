@@ -12,13 +12,13 @@ class Runner:
         self.plan = dwm.dwm_plan_create(N, C, H, W, K, R, S, stride, pad)
         self.info = dwm.dwm_plan_info(self.plan)
         dev = torch.device("cuda:0")
+        for stage, v in (variants or {}).items():  # before sizing: the workspace depends on the variant
+            dwm.dwm_plan_set_variant(self.plan, stage, v)
         self.Ugw = torch.empty(dwm.dwm_plan_filter_bytes(self.plan) // 4, dtype=torch.float32, device=dev)
         # poison the workspace so that anything the input transform fails to write shows up
         self.ws = torch.full((max(dwm.dwm_plan_workspace_bytes(self.plan) // 4, 1),), float("nan"),
                              dtype=torch.float32, device=dev)
         dwm.dwm_plan_set_workspace(self.plan, self.ws.data_ptr(), self.ws.numel() * 4)
-        for stage, v in (variants or {}).items():
-            dwm.dwm_plan_set_variant(self.plan, stage, v)
         self.y = torch.full((N, K, self.info.OH, self.info.OW), float("nan"), dtype=torch.float32, device=dev)
 
     def stream(self):

@@ -126,14 +126,20 @@ def test_forward_matches_fp64_direct(shape):
     assert _relerr(y, ref) <= TOL, shape
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [10, 11, 12, 13, 14, 15, 16, 17])
 @pytest.mark.parametrize("shape", [(3, 8, 19, 21, 70, 3, 3, 2, 1), (2, 24, 30, 30, 140, 7, 7, 1, 3),
+                                   (3, 64, 19, 21, 70, 3, 3, 2, 1), (2, 64, 14, 18, 130, 5, 5, 1, 2),
                                    (2, 3, 43, 47, 20, 11, 11, 4, 0)])
 def test_every_contraction_variant(shape, variant):
     N, C, H, W, K, R, S, s, P = shape
     x, w = _rand(*shape[:7], seed=5)
     ref = oracle.direct_f64(x, w, s, P)
-    y = conv(x, w, s, P, variants={"contract": variant})
+    try:
+        y = conv(x, w, s, P, variants={"contract": variant})
+    except dwm.DwmError as e:
+        # a variant whose reduction chunk is coarser than the plan's padding refuses the launch
+        assert e.status == dwm.DWM_ERR_INVALID_ARG
+        pytest.skip("variant %d does not apply to this shape" % variant)
     assert _relerr(y, ref) <= TOL
 
 

@@ -83,7 +83,8 @@ def test_taps_partition_and_layout(R, S, s):
         planes = (q.len_h + 1) * (q.len_w + 1)
         u_end += planes * info.Kpad * q.Lpad
         v_end += planes * q.Lpad * info.Tpad
-    assert dwm.dwm_plan_filter_bytes(p) == 4 * u_end and dwm.dwm_plan_workspace_bytes(p) == 4 * v_end
+    # V comes first in the workspace; partial tiles and counters of the contraction follow
+    assert dwm.dwm_plan_filter_bytes(p) == 4 * u_end and dwm.dwm_plan_workspace_bytes(p) >= 4 * v_end
     assert info.Kpad >= K and info.Tpad >= info.T == 2 * info.TH * info.TW
     dwm.dwm_plan_destroy(p)
 
