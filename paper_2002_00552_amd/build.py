@@ -5,6 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdwm.so")
+PROBE_LIB = os.path.join(HERE, "libdwm_probe.so")
 SOURCES = ["plan.cpp", "transforms.hip", "contract.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -22,7 +23,9 @@ def stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "plan.hpp"), os.path.join(HERE, "..", "include", "dwm.h")]
+    if not os.path.exists(PROBE_LIB):
+        return True
+    deps = sources() + [os.path.join(CSRC, "probe.hip"), os.path.join(CSRC, "plan.hpp"), os.path.join(HERE, "..", "include", "dwm.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -39,6 +42,13 @@ def build(force=True, verbose=False):
     if verbose and out.strip():
         print(out)
     os.replace(tmp, LIB)
+    # the peak probes (streaming copy / fill / read, fp32 MFMA loop) live in a library of their own
+    tmp = PROBE_LIB + ".%d.tmp" % os.getpid()
+    cmd = [HIPCC] + FLAGS + ["-x", "hip", os.path.join(CSRC, "probe.hip"), "-o", tmp]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    os.replace(tmp, PROBE_LIB)
     return LIB
 
 

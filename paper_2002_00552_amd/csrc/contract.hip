@@ -336,15 +336,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
-                        mine[((blk * 4 + q) * 16 + e) * NT] = Y[blk / WN][blk % WN][q][e];
-            __threadfence();  // release: the partial output is visible device-wide before the count
+                        __hip_atomic_store(&mine[((blk * 4 + q) * 16 + e) * NT], Y[blk / WN][blk % WN][q][e],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // The partial output is written with device-scope stores (they complete at the level
+            // all XCDs share), so waiting for them -- not a flush of the whole L2 -- is all the
+            // release that the arrival count below needs.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __syncthreads();
             if (tid == 0) s_last = atomicAdd(&counters[trel], 1) == nc - 1;
             __syncthreads();
             store = s_last != 0;
             __syncthreads();  // s_last may be rewritten for the next segment
             if (store) {
-                __threadfence();  // acquire: see the other contributors' partial outputs
+                // device-scope loads below bypass whatever this XCD's caches may hold
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                 // sum all contributions (this workgroup's own included) in contributor order,
                 // so the result does not depend on which workgroup happened to arrive last
                 for (int c = 0; c < nc; ++c) {
@@ -355,7 +360,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                         for (int q = 0; q < 4; ++q)
 #pragma unroll
                             for (int e = 0; e < 16; ++e) {
-                                const float v = src[((blk * 4 + q) * 16 + e) * NT];
+                                const float v = __hip_atomic_load(&src[((blk * 4 + q) * 16 + e) * NT],
+                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 const float old = Y[blk / WN][blk % WN][q][e];
                                 Y[blk / WN][blk % WN][q][e] = c == 0 ? v : old + v;
                             }

@@ -86,7 +86,10 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
     if (rest > 0) {
         const long long total = (long long)rest * g.n_iter;
         long long wgs = total < kNumCUs ? total : kNumCUs;
-        const long long ipw = (total + wgs - 1) / wgs;
+        long long ipw = (total + wgs - 1) / wgs;
+        // a tile is shared by at most about four workgroups: beyond that the summing of
+        // partial outputs costs more than the balance gains
+        if (ipw * 4 < g.n_iter) ipw = (g.n_iter + 3) / 4;
         wgs = (total + ipw - 1) / ipw;
         g.sk_wgs = (int)wgs;
         g.sk_ipw = (int)ipw;

@@ -42,6 +42,8 @@ STAGE_SHAPES = [  # N, C, H, W, K, R, S, stride, pad
     (1, 2, 31, 29, 3, 11, 11, 4, 0),
     (1, 5, 9, 10, 2, 1, 7, 1, 3),
     (1, 20, 8, 8, 130, 3, 3, 1, 1),
+    (1, 2, 150, 700, 2, 5, 5, 2, 2),     # wide image: several bands of tile rows
+    (1, 1, 90, 500, 1, 11, 11, 4, 0),
 ]
 
 
@@ -69,11 +71,12 @@ def test_filter_transform_matches_oracle(shape):
     r.close()
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("shape", STAGE_SHAPES)
-def test_input_transform_matches_oracle(shape):
+def test_input_transform_matches_oracle(shape, variant):
     N, C, H, W, K, R, S, s, P = shape
     x, w = _rand(*shape[:7], seed=12)
-    r = Runner(*shape)
+    r = Runner(*shape, variants={"input": variant})
     xd = torch.from_numpy(x).cuda()
     dwm.dwm_input_transform(r.plan, xd.data_ptr(), r.stream())
     torch.cuda.synchronize()
@@ -84,7 +87,7 @@ def test_input_transform_matches_oracle(shape):
         q = classes[pt.cls]
         th, tw = q.len_h + 1, q.len_w + 1
         Vg = V[q.v_offset:q.v_offset + th * tw * q.Lpad * Tpad].reshape(th, tw, q.Lpad, Tpad)
-        assert np.all(Vg[:, :, q.L:, :] == 0)  # padded reduction rows must be zero
+        assert np.all(Vg[:, :, q.L:, :T] == 0)  # padded reduction rows must be zero
         for n in range(N):
             ref = oracle.part_input_transform(x, R, S, s, P, _part_tuple(pt), n)  # [C][TH][TW][th][tw]
             got = Vg[:, :, pt.slot * C:(pt.slot + 1) * C, n * TH * TW:(n + 1) * TH * TW]
@@ -112,6 +115,8 @@ E2E_SHAPES = [
     (5, 130, 7, 7, 129, 3, 3, 1, 1),     # reduction and K just past tile boundaries
     (70, 2, 6, 6, 3, 3, 3, 1, 1),        # many images, T crosses several T tiles
     (1, 3, 9, 300, 4, 3, 5, 1, 2),       # one long row
+    (1, 2, 150, 700, 3, 5, 5, 2, 2),     # several bands of tile rows in the input transform
+    (2, 2, 301, 64, 3, 7, 3, 1, 3),      # tall image
 ]
 
 
