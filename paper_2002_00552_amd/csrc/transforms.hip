@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void input_transform_gather_kernel(DevPlan P, 
 }
 
 // ---------------------------------------------------------------------------------
-// Input transform, LDS-staged form (the one the planner uses).
+// Input transform, LDS-staged form (variant 0; measured no faster than the gather form).
 //
 // A workgroup owns one image n, one channel c and a band of BT tile rows.  It reads the
 // input rows the band needs ONCE, coalesced, into LDS -- zero padding written explicitly,
@@ -368,7 +368,7 @@ dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream)
 {
     const DevPlan& d = p.d;
-    if (p.variant_input == 1) {  // gather form: no LDS, one thread per (row, tile)
+    if (p.variant_input != 0) {  // gather form (the default): no LDS, one thread per (row, tile)
         if (d.rows_total > 65535) return DWM_ERR_UNSUPPORTED;
         dim3 grid(d.Tpad / 256, d.rows_total), block(256);
         hipLaunchKernelGGL(input_transform_gather_kernel, grid, block, 0, (hipStream_t)stream, d, x, V,
