@@ -90,6 +90,10 @@ typedef struct {
     int n_parts;
     int L, Lpad;
     long long u_offset, v_offset;
+    long long ut_offset; /* -1 unless the layer uses the single-kernel forward path (few input
+                            channels); then Ugw also holds the class transposed, filters fastest:
+                            Ugw[ut_offset + ((fh*(len_w+1)+fw)*Lt + l)*Kpad + k], zero for l >= L, k >= K */
+    int Lt;              /* L rounded up to even (0 if ut_offset is -1) */
 } dwm_class_t;
 
 /*

@@ -36,7 +36,8 @@ class dwm_part_t(ctypes.Structure):
 
 class dwm_class_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("len_h", "len_w", "n_parts", "L", "Lpad")] + [
-        ("u_offset", ctypes.c_longlong), ("v_offset", ctypes.c_longlong)]
+        ("u_offset", ctypes.c_longlong), ("v_offset", ctypes.c_longlong), ("ut_offset", ctypes.c_longlong),
+        ("Lt", ctypes.c_int)]
 
 
 _P = ctypes.c_void_p

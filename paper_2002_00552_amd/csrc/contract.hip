@@ -21,6 +21,7 @@
 // the same order, by the last workgroup to arrive (no workgroup ever waits for another).
 #include <hip/hip_runtime.h>
 
+#include "dma.hpp"
 #include "plan.hpp"
 
 namespace dwm {
@@ -32,25 +33,6 @@ struct ContractArgs {
     int OH, OW, TH, TW;
     ContractGeometry g;
 };
-
-// One 64-lane DMA: lane i's 16 bytes at g land at LDS byte address m0 + 16*i.
-// Issued through inline assembly on purpose: the compiler's own bookkeeping would wait for
-// ALL outstanding loads before any LDS read, which serialises the ring; here the only
-// wait is the explicit vmcnt before the barrier.
-__device__ __forceinline__ void dma16(const float* g, uint32_t lds_byte_addr_uniform)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(g), "s"(lds_byte_addr_uniform)
-                 : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
 
 // XOR pattern of U-tile row i: which 16-byte column group sits in which slot, chosen so
 // that 8 or 16 consecutive lanes reading the same logical group hit distinct banks.

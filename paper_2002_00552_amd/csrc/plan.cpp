@@ -206,6 +206,8 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     p->ws_bytes = 0;
     p->lgran = lgran;
     p->variant_input = -1;
+    p->variant_forward = -1;
+    p->fused_ok = false;
     if (!dwm::contract_geometry(*p, default_contract_variant(lgran), &p->geo)) {
         delete p;
         return DWM_ERR_UNSUPPORTED;
@@ -219,6 +221,24 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     in.direct_flops = 2.0 * N * K * C * R * S * d.OH * d.OW;
     in.winograd_flops = 2.0 * (double)mults * C * K * (double)T;
     in.Kpad = d.Kpad; in.Tpad = d.Tpad;
+    p->fused_ok = dwm::fused_setup(*p, &p->fused);
+    if (p->fused_ok) {
+        // the single-kernel path reads U transposed (filters fastest): a second copy after the first
+        long long ut = (long long)p->filter_floats;
+        d.has_ut = 1;
+        for (int i = 0; i < d.ncls; ++i) {
+            dwm::DevClass& q = d.cls[i];
+            q.Lt = (q.L + 1) & ~1;
+            q.ut_off = ut;
+            const int planes = (q.lh + 1) * (q.lw + 1);
+            for (int pl = 0; pl < planes; ++pl)
+                p->planes.e[q.plane0 + pl].ut_off64 = (uint32_t)((ut + (long long)pl * q.Lt * d.Kpad) / 64);
+            ut += (long long)planes * q.Lt * d.Kpad;
+        }
+        // every plane is read a fixed number of rows deep: 32 rows of slack after the last one
+        p->ut_begin = p->filter_floats;
+        p->filter_floats = (size_t)ut + (size_t)32 * d.Kpad;
+    }
     *out = p;
     return DWM_OK;
 }
@@ -250,6 +270,8 @@ dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls)
     const dwm::DevClass& q = plan->d.cls[i];
     cls->len_h = q.lh; cls->len_w = q.lw; cls->n_parts = q.hn * q.wn;
     cls->L = q.L; cls->Lpad = q.Lpad; cls->u_offset = q.u_off; cls->v_offset = q.v_off;
+    cls->ut_offset = plan->d.has_ut ? q.ut_off : -1;
+    cls->Lt = plan->d.has_ut ? q.Lt : 0;
     return DWM_OK;
 }
 
@@ -270,6 +292,11 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
     if (!plan || !stage) return DWM_ERR_INVALID_ARG;
     if (!std::strcmp(stage, "input")) {
         plan->variant_input = variant;
+        return DWM_OK;
+    }
+    if (!std::strcmp(stage, "forward")) {
+        if (variant > 1 || (variant == 1 && !plan->fused_ok)) return DWM_ERR_INVALID_ARG;
+        plan->variant_forward = variant;
         return DWM_OK;
     }
     if (std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
@@ -310,6 +337,7 @@ dwm_status_t dwm_conv_forward(const dwm_plan_t* plan, const float* x_dev, const 
 {
     if (!plan || !x_dev || !Ugw_dev || !y_dev) return DWM_ERR_INVALID_ARG;
     if (!plan->ws) return DWM_ERR_WORKSPACE;
+    if (plan->use_fused()) return dwm::launch_fused_forward(*plan, x_dev, Ugw_dev, y_dev, stream);
     dwm_status_t st = dwm::launch_input_transform(*plan, x_dev, plan->ws, stream);
     if (st != DWM_OK) return st;
     return dwm::launch_contract_output(*plan, Ugw_dev, plan->ws, y_dev, stream);

@@ -3,6 +3,9 @@
 // arguments (DevPlan / PlaneTable below), so the library owns no device memory.
 #pragma once
 #include <cstdint>
+#ifdef __HIPCC__
+#include <hip/hip_runtime.h>
+#endif
 #include "../../include/dwm.h"
 
 namespace dwm {
@@ -28,6 +31,9 @@ struct DevClass {
     int row0;    // first row of this class in the flattened (class, l) row space
     int plane0;  // first plane of this class
     long long u_off, v_off;  // floats
+    long long ut_off;        // floats; transposed copy UT[plane][Lt][Kpad] (only if DevPlan::has_ut)
+    int Lt;                  // L rounded up to even
+    int pad_;
 };
 
 struct DevPlan {
@@ -37,6 +43,7 @@ struct DevPlan {
     int nh, nw;
     int ncls;
     int rows_total;  // sum over classes of Lpad
+    int has_ut;      // the filter transform also writes the transposed copy (single-kernel path)
     DevPiece ph[kMaxPieces];
     DevPiece pw[kMaxPieces];
     DevClass cls[kMaxClasses];
@@ -48,6 +55,7 @@ struct DevPlan {
 struct DevPlaneEntry {
     uint32_t u_off64;  // offset into Ugw in units of 64 floats
     uint32_t v_off64;  // offset into V   in units of 64 floats
+    uint32_t ut_off64; // offset of the transposed copy UT_p[Lt][Kpad] in units of 64 floats
     int32_t Lpad;
     int32_t coef;      // bits [2q+1:2q] of output q=2a+b: 0 -> 0, 1 -> +1, 3 -> -1
 };
@@ -90,6 +98,40 @@ struct ContractGeometry {
     size_t partial_floats;
 };
 
+// exact floor(n / d) for 0 <= n < 2^31, d >= 1, without a division
+struct FastDiv {
+    unsigned mul, shift;
+    void init(unsigned d)
+    {
+        shift = 0;
+        while ((1u << shift) < d) ++shift;
+        mul = (unsigned)((((unsigned long long)1 << 32) * ((1ull << shift) - d)) / d + 1);
+    }
+#ifdef __HIPCC__
+    __device__ __forceinline__ int div(int n) const
+    {
+        return (int)((__umulhi((unsigned)n, mul) + (unsigned)n) >> shift);
+    }
+#endif
+};
+
+// Geometry of the single-kernel forward path for layers whose whole input footprint of a
+// block of output tiles, all channels, fits in LDS (small C): see fused.hip.
+struct FusedArgs {
+    int BH, BW, nbh, nbw;  // block of tiles owned by a workgroup (BH*BW <= 64), blocks per image
+    int wgm;               // K blocks of 32 per workgroup (1..4)
+    int nkt;               // workgroups along K
+    int nphase, lwp, lw_in, nrows;  // staged input region: 2*stride phases, floats per (row, phase), columns, rows
+    int row_floats, chan_floats;    // LDS floats per staged row / per channel
+    int tile_row_step;              // LDS floats between vertically adjacent tiles' patches
+    int vrows;                      // rows of one V plane buffer in LDS (even, >= every class's L)
+    int rows_all;                   // sum over classes of Lt; row0[i] = first row of class i
+    int row0[kMaxClasses];
+    FastDiv div_bw, div_nphase, div_c;
+    int roff[kMaxPieces][4], coff[kMaxPieces][4];  // LDS offset of patch row a / column b of a piece
+    size_t lds_bytes;
+};
+
 }  // namespace dwm
 
 // The opaque plan of the C ABI.
@@ -99,11 +141,16 @@ struct dwm_plan {
     dwm_plan_info_t info;
     dwm_part_t parts[dwm::kMaxPieces * dwm::kMaxPieces];
     size_t filter_floats, v_floats;
+    size_t ut_begin;  // first float of the transposed copy in Ugw (single-kernel path only)
     dwm::ContractGeometry geo;
     float* ws;
     size_t ws_bytes;
     int lgran;  // every class's Lpad is a multiple of this (16, 32 or 64)
     int variant_input;  // < 0: planner's choice
+    bool fused_ok;      // the single-kernel path applies to this layer
+    int variant_forward;  // < 0: planner's choice (fused when it applies), 0: staged, 1: fused
+    dwm::FusedArgs fused;
+    bool use_fused() const { return fused_ok && variant_forward != 0; }
 
     // workspace layout: [ V | partial outputs | arrival counters ]
     size_t ws_need_bytes() const { return (v_floats + geo.partial_floats) * sizeof(float) + counters_bytes(); }
@@ -119,4 +166,7 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out);
 dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U, void* stream);
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream);
 dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const float* V, float* y, void* stream);
+// fused.hip
+bool fused_setup(const dwm_plan& p, FusedArgs* out);
+dwm_status_t launch_fused_forward(const dwm_plan& p, const float* x, const float* U, float* y, void* stream);
 }  // namespace dwm

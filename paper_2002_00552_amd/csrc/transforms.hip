@@ -108,8 +108,11 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(DevPlan P, const 
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (i < th && j < tw)
+            if (i < th && j < tw) {
                 U[(size_t)q.u_off + ((size_t)(i * tw + j) * P.Kpad + k) * q.Lpad + l] = u[i][j];
+                if (P.has_ut && l < q.Lt)
+                    U[(size_t)q.ut_off + ((size_t)(i * tw + j) * q.Lt + l) * P.Kpad + k] = u[i][j];
+            }
 }
 
 // ---------------------------------------------------------------------------------
@@ -213,17 +216,6 @@ __global__ __launch_bounds__(256) void input_transform_gather_kernel(DevPlan P, 
 // Lanes of a wave hold consecutive tiles, so every store is a contiguous run along t.
 // The workgroups with c == C write the zero rows that pad each class's reduction length.
 // ---------------------------------------------------------------------------------
-struct FastDiv {  // exact floor(n / d) for 0 <= n < 2^31, d >= 1, without a division
-    unsigned mul, shift;
-    __host__ void init(unsigned d)
-    {
-        shift = 0;
-        while ((1u << shift) < d) ++shift;
-        mul = (unsigned)((((unsigned long long)1 << 32) * ((1ull << shift) - d)) / d + 1);
-    }
-    __device__ __forceinline__ int div(int n) const { return (int)((__umulhi((unsigned)n, mul) + (unsigned)n) >> shift); }
-};
-
 struct InputArgs {
     int BT, nbands;    // tile rows per band, bands per image
     int nphase;        // 2*stride
@@ -358,10 +350,20 @@ static dwm_status_t check_launch()
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }
 
+__global__ __launch_bounds__(256) void zero_fill_kernel(float* __restrict__ p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
+}
+
 dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U, void* stream)
 {
     dim3 grid((p.d.rows_total + 255) / 256, p.d.Kpad), block(256);
     hipLaunchKernelGGL(filter_transform_kernel, grid, block, 0, (hipStream_t)stream, p.d, w, U);
+    if (p.d.has_ut) {  // the slack rows after the transposed copy (read, never used)
+        const size_t slack = (size_t)32 * p.d.Kpad;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(32), block, 0, (hipStream_t)stream,
+                           U + p.filter_floats - slack, slack);
+    }
     return check_launch();
 }
 

@@ -68,6 +68,11 @@ def test_filter_transform_matches_oracle(shape):
         assert np.max(np.abs(got - ref)) <= 1e-6 * max(np.max(np.abs(ref)), 1e-30)
         # padding rows/columns are zero
         assert np.all(Ug[:, :, K:, :] == 0) and np.all(Ug[:, :, :, q.L:] == 0)
+        if q.ut_offset >= 0:  # the transposed copy the single-kernel path reads
+            UT = U[q.ut_offset:q.ut_offset + th * tw * q.Lt * Kpad].reshape(th, tw, q.Lt, Kpad)
+            got_t = UT[:, :, pt.slot * C:(pt.slot + 1) * C, :K].transpose(3, 2, 0, 1)
+            assert np.array_equal(got_t, got)
+            assert np.all(UT[:, :, q.L:, :] == 0) and np.all(UT[:, :, :, K:] == 0)
     r.close()
 
 
@@ -120,12 +125,15 @@ E2E_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("path", ["staged", "auto"])
 @pytest.mark.parametrize("shape", E2E_SHAPES)
-def test_forward_matches_fp64_direct(shape):
+def test_forward_matches_fp64_direct(shape, path):
+    """'staged' forces input transform + contraction; 'auto' lets the planner use the
+    single-kernel path where it applies (few input channels)."""
     N, C, H, W, K, R, S, s, P = shape
     x, w = _rand(*shape[:7], seed=100 + R * 7 + S)
     ref = oracle.direct_f64(x, w, s, P)
-    y = conv(x, w, s, P)
+    y = conv(x, w, s, P, variants={"forward": 0 if path == "staged" else -1})
     assert y.shape == ref.shape
     assert np.all(np.isfinite(y))
     assert _relerr(y, ref) <= TOL, shape
@@ -140,7 +148,7 @@ def test_every_contraction_variant(shape, variant):
     x, w = _rand(*shape[:7], seed=5)
     ref = oracle.direct_f64(x, w, s, P)
     try:
-        y = conv(x, w, s, P, variants={"contract": variant})
+        y = conv(x, w, s, P, variants={"contract": variant, "forward": 0})
     except dwm.DwmError as e:
         # a variant whose reduction chunk is coarser than the plan's padding refuses the launch
         assert e.status == dwm.DWM_ERR_INVALID_ARG
@@ -166,7 +174,7 @@ def test_forward_is_deterministic_and_plan_reusable():
 def test_staged_calls_equal_the_fused_entry_point():
     shape = (2, 5, 21, 20, 9, 5, 5, 2, 2)
     x, w = _rand(*shape[:7], seed=10)
-    r = Runner(*shape)
+    r = Runner(*shape, variants={"forward": 0})
     r.set_filter(w)
     y1 = r.forward(x).copy()
     r.y.fill_(float("nan"))
@@ -188,6 +196,30 @@ def test_runs_on_a_side_stream():
 
 
 # ---- the five benchmark layers at full size, in the launch configuration bench.py times ----
+
+def test_single_kernel_path_is_chosen_only_where_it_applies():
+    few = dwm.dwm_plan_create(2, 3, 40, 40, 8, 7, 7, 2, 3)
+    many = dwm.dwm_plan_create(2, 64, 40, 40, 8, 7, 7, 2, 3)
+    dwm.dwm_plan_set_variant(few, "forward", 1)
+    with pytest.raises(dwm.DwmError):
+        dwm.dwm_plan_set_variant(many, "forward", 1)
+    dwm.dwm_plan_destroy(few)
+    dwm.dwm_plan_destroy(many)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 37, 35, 33, 7, 7, 2, 3), (3, 3, 50, 61, 100, 11, 11, 4, 0),
+                                   (2, 16, 33, 31, 130, 5, 5, 1, 2), (1, 1, 20, 20, 1, 3, 3, 1, 1),
+                                   (2, 5, 150, 140, 70, 3, 3, 2, 1), (1, 8, 20, 24, 40, 7, 1, 1, 3)])
+def test_single_kernel_path_matches_fp64_direct(shape):
+    """Shapes on which the single-kernel path applies, forced on: K from 1 to beyond one
+    workgroup's 128 filters, odd sizes, blocks of tiles that overhang the image."""
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand(*shape[:7], seed=31)
+    ref = oracle.direct_f64(x, w, s, P)
+    y = conv(x, w, s, P, variants={"forward": 1})
+    assert np.all(np.isfinite(y))
+    assert _relerr(y, ref) <= TOL, shape
+
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
 def test_benchmark_layers_full_size(index):
