@@ -64,7 +64,8 @@ typedef struct {
     double direct_flops;      /* 2*N*K*C*R*S*OH*OW */
     double winograd_flops;    /* 2*mults_per_tile*C*K*T */
     int Kpad;                 /* rows per plane of the transformed filter (K rounded up) */
-    long long Tpad;           /* columns per plane of the transformed input (T rounded up) */
+    long long Tpad;           /* tiles covered by the transformed input (T rounded up to 256) */
+    long long Vblock;         /* floats of one block of the transformed input: all planes' rows for 64 tiles */
 } dwm_plan_info_t;
 
 /* One sub-kernel.  Its taps are w[.,.,stride*(off_h+a)+phase_h, stride*(off_w+b)+phase_w],
@@ -82,8 +83,9 @@ typedef struct {
  * over l = slot*C + c, l < L = n_parts*C (rounded up to Lpad with zeros).
  * Layouts (offsets in floats from the start of the buffer; fh <= len_h, fw <= len_w):
  *   transformed filter  Ugw[u_offset + ((fh*(len_w+1)+fw)*Kpad + k)*Lpad + l]
- *   transformed input   ws [v_offset + ((fh*(len_w+1)+fw)*Lpad + l)*Tpad + t],
- *                       t = (n*TH + ty)*TW + tx
+ *   transformed input   ws [(t/64)*Vblock + v_offset + ((fh*(len_w+1)+fw)*Lpad + l)*64 + t%64],
+ *                       t = (n*TH + ty)*TW + tx: blocked by 64 tiles, so that what one workgroup
+ *                       of the contraction reads per step is one contiguous run
  */
 typedef struct {
     int len_h, len_w;

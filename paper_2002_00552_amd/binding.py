@@ -26,7 +26,7 @@ class dwm_plan_info_t(ctypes.Structure):
         ("T", ctypes.c_longlong), ("n_parts", ctypes.c_int), ("n_classes", ctypes.c_int),
         ("n_planes", ctypes.c_int), ("mults_per_tile", ctypes.c_longlong),
         ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double),
-        ("Kpad", ctypes.c_int), ("Tpad", ctypes.c_longlong)]
+        ("Kpad", ctypes.c_int), ("Tpad", ctypes.c_longlong), ("Vblock", ctypes.c_longlong)]
 
 
 class dwm_part_t(ctypes.Structure):

@@ -31,6 +31,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 struct ContractArgs {
     int K, T, Kpad, Tpad;
     int OH, OW, TH, TW;
+    int vblock;  // floats of one 64-tile block of V
     ContractGeometry g;
 };
 
@@ -85,8 +86,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
     for (int q = 0; q < B_I; ++q) {
         const int s = (wave * B_I + q) * 64 + lane;
         const int row = s / B_C4, sp = s % B_C4;
+        const int col = (sp ^ (((row >> 2) & 1) << 3)) * 4;  // column of the V tile this lane fetches
         b_row[q] = row;
-        b_col[q] = (sp ^ (((row >> 2) & 1) << 3)) * 4;
+        b_col[q] = (col >> 6) * A.vblock + (col & 63);       // V is blocked by 64 tiles
     }
     const int swz = a_swizzle<LC>(li);
 
@@ -122,11 +124,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
         auto point_at = [&](int pl, int ch) {
             const DevPlaneEntry e = PT.e[pl];
             const float* Ub = U + (size_t)e.u_off64 * 64 + (size_t)(kt * KT) * e.Lpad + ch * LC;
-            const float* Vb = V + (size_t)e.v_off64 * 64 + (size_t)(ch * LC) * A.Tpad + tt * TT;
+            const float* Vb = V + (size_t)(tt * (TT / 64)) * A.vblock + ((size_t)e.v_off64 + ch * LC) * 64;
 #pragma unroll
             for (int q = 0; q < A_I; ++q) pa[q] = Ub + (size_t)a_row[q] * e.Lpad + a_col[q];
 #pragma unroll
-            for (int q = 0; q < B_I; ++q) pb[q] = Vb + (size_t)b_row[q] * A.Tpad + b_col[q];
+            for (int q = 0; q < B_I; ++q) pb[q] = Vb + b_row[q] * 64 + b_col[q];
         };
         point_at(ip, ij);
         auto issue_one = [&](int d) {
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
 #pragma unroll
                 for (int q = 0; q < A_I; ++q) pa[q] += LC;
 #pragma unroll
-                for (int q = 0; q < B_I; ++q) pb[q] += (size_t)LC * A.Tpad;
+                for (int q = 0; q < B_I; ++q) pb[q] += LC * 64;
             } else {
                 ++ip;
                 ij = 0;
@@ -366,6 +368,7 @@ static dwm_status_t launch_variant(const dwm_plan& p, const float* U, const floa
     ContractArgs a;
     a.K = p.d.K; a.T = p.d.T; a.Kpad = p.d.Kpad; a.Tpad = p.d.Tpad;
     a.OH = p.d.OH; a.OW = p.d.OW; a.TH = p.d.TH; a.TW = p.d.TW;
+    a.vblock = p.d.vblock_rows * 64;
     a.g = p.geo;
     // the geometry was computed for exactly this shape of variant
     if (a.g.nkt != (p.d.K + KT - 1) / KT || a.g.ntt != (p.d.T + TT - 1) / TT || p.lgran % LC != 0)
@@ -394,6 +397,8 @@ dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const flo
         case 15: return launch_variant<2, 2, 2, 1, 32, 2>(p, U, V, y, stream);
         case 16: return launch_variant<2, 2, 1, 2, 32, 2>(p, U, V, y, stream);
         case 17: return launch_variant<2, 2, 1, 1, 16, 2>(p, U, V, y, stream);
+        case 18: return launch_variant<2, 2, 1, 1, 32, 4>(p, U, V, y, stream);
+        case 19: return launch_variant<2, 2, 1, 1, 64, 3>(p, U, V, y, stream);
         default: return DWM_ERR_INVALID_ARG;
     }
 }

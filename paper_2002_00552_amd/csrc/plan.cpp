@@ -82,10 +82,18 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
     g.n_full = g.ntiles / kNumCUs * kNumCUs;
     int rest = g.ntiles - g.n_full;
     if (rest * 10 >= kNumCUs * 9) { g.n_full = g.ntiles; rest = 0; }
+    long long sk_slots = kNumCUs;
+    if (p.sk_mode == 1 && rest > 0 && g.n_full == kNumCUs) {
+        // one full round plus a remainder: two EQUAL ranges per CU instead of a whole tile and
+        // a shorter range, so that the two resident workgroups of a CU finish together
+        g.n_full = 0;
+        rest = g.ntiles;
+        sk_slots = 2 * kNumCUs;
+    }
     g.n_sk_tiles = rest;
     if (rest > 0) {
         const long long total = (long long)rest * g.n_iter;
-        long long wgs = total < kNumCUs ? total : kNumCUs;
+        long long wgs = total < sk_slots ? total : sk_slots;
         long long ipw = (total + wgs - 1) / wgs;
         // a tile is shared by at most about four workgroups: beyond that the summing of
         // partial outputs costs more than the balance gains
@@ -165,14 +173,14 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
                 if (Lpad >= lim) { ok = false; break; }
                 q.L = (int)L; q.Lpad = (int)Lpad;
                 q.row0 = d.rows_total; q.plane0 = p->planes.n;
-                q.u_off = u_off; q.v_off = v_off;
+                q.u_off = u_off; q.v_row0 = (int)v_off;
                 d.rows_total += q.Lpad;
                 for (int fh = 0; fh <= lh; ++fh)
                     for (int fw = 0; fw <= lw; ++fw) {
                         DevPlaneEntry& e = p->planes.e[p->planes.n++];
                         const long long pl = fh * (lw + 1) + fw;
                         e.u_off64 = (uint32_t)((u_off + pl * Kpad * Lpad) / 64);
-                        e.v_off64 = (uint32_t)((v_off + pl * Lpad * Tpad) / 64);
+                        e.v_off64 = (uint32_t)(v_off + pl * Lpad);
                         e.Lpad = q.Lpad;
                         int coef = 0;
                         for (int a = 0; a < 2; ++a)
@@ -183,8 +191,8 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
                         e.coef = coef;
                     }
                 u_off += planes * Kpad * Lpad;
-                v_off += planes * Lpad * Tpad;
-                if (u_off >= lim * 32 || v_off >= lim * 32) { ok = false; break; }
+                v_off += planes * Lpad;  // rows of a V block so far
+                if (u_off >= lim * 32 || v_off * Tpad >= lim * 32) { ok = false; break; }
                 for (int a = 0; a < q.hn; ++a)
                     for (int b = 0; b < q.wn; ++b) {
                         dwm_part_t& pt = p->parts[n_parts++];
@@ -201,12 +209,14 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
         return DWM_ERR_UNSUPPORTED;
     }
     p->filter_floats = (size_t)u_off;
-    p->v_floats = (size_t)v_off;
+    d.vblock_rows = (int)v_off;
+    p->v_floats = (size_t)v_off * (size_t)Tpad;
     p->ws = nullptr;
     p->ws_bytes = 0;
     p->lgran = lgran;
     p->variant_input = -1;
     p->variant_forward = -1;
+    p->sk_mode = 0;
     p->fused_ok = false;
     if (!dwm::contract_geometry(*p, default_contract_variant(lgran), &p->geo)) {
         delete p;
@@ -221,6 +231,7 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     in.direct_flops = 2.0 * N * K * C * R * S * d.OH * d.OW;
     in.winograd_flops = 2.0 * (double)mults * C * K * (double)T;
     in.Kpad = d.Kpad; in.Tpad = d.Tpad;
+    in.Vblock = (long long)d.vblock_rows * 64;
     p->fused_ok = dwm::fused_setup(*p, &p->fused);
     if (p->fused_ok) {
         // the single-kernel path reads U transposed (filters fastest): a second copy after the first
@@ -269,7 +280,7 @@ dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls)
     if (!plan || !cls || i < 0 || i >= plan->d.ncls) return DWM_ERR_INVALID_ARG;
     const dwm::DevClass& q = plan->d.cls[i];
     cls->len_h = q.lh; cls->len_w = q.lw; cls->n_parts = q.hn * q.wn;
-    cls->L = q.L; cls->Lpad = q.Lpad; cls->u_offset = q.u_off; cls->v_offset = q.v_off;
+    cls->L = q.L; cls->Lpad = q.Lpad; cls->u_offset = q.u_off; cls->v_offset = (long long)q.v_row0 * 64;
     cls->ut_offset = plan->d.has_ut ? q.ut_off : -1;
     cls->Lt = plan->d.has_ut ? q.Lt : 0;
     return DWM_OK;
@@ -298,6 +309,13 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
         if (variant > 1 || (variant == 1 && !plan->fused_ok)) return DWM_ERR_INVALID_ARG;
         plan->variant_forward = variant;
         return DWM_OK;
+    }
+    if (!std::strcmp(stage, "split")) {  // 0: whole tiles + split remainder, 1: all tiles split evenly
+        const int old_mode = plan->sk_mode;
+        plan->sk_mode = variant == 1 ? 1 : 0;
+        const dwm_status_t st = dwm_plan_set_variant(plan, "contract", plan->geo.variant);
+        if (st != DWM_OK) plan->sk_mode = old_mode;
+        return st;
     }
     if (std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
     dwm::ContractGeometry g;

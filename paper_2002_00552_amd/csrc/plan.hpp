@@ -30,7 +30,9 @@ struct DevClass {
     int L, Lpad;
     int row0;    // first row of this class in the flattened (class, l) row space
     int plane0;  // first plane of this class
-    long long u_off, v_off;  // floats
+    long long u_off;         // floats
+    int v_row0;              // first row of the class inside a V block (a row = 64 tiles)
+    int pad2_;
     long long ut_off;        // floats; transposed copy UT[plane][Lt][Kpad] (only if DevPlan::has_ut)
     int Lt;                  // L rounded up to even
     int pad_;
@@ -43,6 +45,7 @@ struct DevPlan {
     int nh, nw;
     int ncls;
     int rows_total;  // sum over classes of Lpad
+    int vblock_rows; // rows of one V block = sum over planes of Lpad
     int has_ut;      // the filter transform also writes the transposed copy (single-kernel path)
     DevPiece ph[kMaxPieces];
     DevPiece pw[kMaxPieces];
@@ -54,7 +57,7 @@ struct DevPlan {
 // product enters the output tile (entries 0, +1, -1; packed two bits each).
 struct DevPlaneEntry {
     uint32_t u_off64;  // offset into Ugw in units of 64 floats
-    uint32_t v_off64;  // offset into V   in units of 64 floats
+    uint32_t v_off64;  // first row of the plane inside a V block (= offset in units of 64 floats)
     uint32_t ut_off64; // offset of the transposed copy UT_p[Lt][Kpad] in units of 64 floats
     int32_t Lpad;
     int32_t coef;      // bits [2q+1:2q] of output q=2a+b: 0 -> 0, 1 -> +1, 3 -> -1
@@ -76,6 +79,7 @@ struct ContractVariant {
 constexpr ContractVariant kContractVariants[] = {
     {10, 2, 2, 1, 1, 16, 4}, {11, 2, 2, 1, 1, 32, 3}, {12, 2, 2, 1, 1, 64, 2}, {13, 4, 2, 1, 1, 32, 2},
     {14, 2, 4, 1, 1, 32, 3}, {15, 2, 2, 2, 1, 32, 2}, {16, 2, 2, 1, 2, 32, 2}, {17, 2, 2, 1, 1, 16, 2},
+    {18, 2, 2, 1, 1, 32, 4}, {19, 2, 2, 1, 1, 64, 3},
 };
 constexpr int kNumContractVariants = sizeof(kContractVariants) / sizeof(kContractVariants[0]);
 constexpr int kNumCUs = 256;  // MI355X
@@ -147,6 +151,7 @@ struct dwm_plan {
     size_t ws_bytes;
     int lgran;  // every class's Lpad is a multiple of this (16, 32 or 64)
     int variant_input;  // < 0: planner's choice
+    int sk_mode;        // how leftover tiles are split (see contract_geometry)
     bool fused_ok;      // the single-kernel path applies to this layer
     int variant_forward;  // < 0: planner's choice (fused when it applies), 0: staged, 1: fused
     dwm::FusedArgs fused;

@@ -82,9 +82,10 @@ def test_taps_partition_and_layout(R, S, s):
         assert q.u_offset == u_end and q.v_offset == v_end
         planes = (q.len_h + 1) * (q.len_w + 1)
         u_end += planes * info.Kpad * q.Lpad
-        v_end += planes * q.Lpad * info.Tpad
+        v_end += planes * q.Lpad * 64  # offsets inside one block of 64 tiles
     # V comes first in the workspace; partial tiles and counters of the contraction follow
-    assert dwm.dwm_plan_workspace_bytes(p) >= 4 * v_end
+    assert info.Vblock == v_end and info.Tpad % 64 == 0
+    assert dwm.dwm_plan_workspace_bytes(p) >= 4 * info.Vblock * (info.Tpad // 64)
     if classes[0].ut_offset < 0:
         assert dwm.dwm_plan_filter_bytes(p) == 4 * u_end
     else:  # few input channels: a transposed copy of every class follows, then slack rows
