@@ -8,7 +8,9 @@ timed region (it is a function of the weights only).  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu-baseline]
 
 --config picks one of the five layers of dwm_workloads.CONFIGS (default 1, the stride-2
-downsampling layer the headline metric is quoted on).
+downsampling layer the headline metric is quoted on).  --paper-layer KERNEL,HW,STRIDE runs one
+of the paper's own single-layer shapes instead (Sec. 5: batch 256, same padding, 14x14 maps
+with 256 channels/filters or 28x28 with 128, standard-normal inputs AND weights).
 """
 import argparse
 import json
@@ -23,6 +25,26 @@ if ROOT not in sys.path:
 METRIC = "direct-conv-equivalent TFLOP/s of DWM conv (fp32, 1 GPU); MSE vs FP64 direct"
 PEAK_MFMA_F32 = 157.3  # TFLOP/s, dense fp32 MFMA, MI355X
 PEAK_HBM = 8000.0      # GB/s
+
+
+# HBM-side bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, each scaled by what the
+# counter reads for the copy probe of known size (factors 2.00 and 1.00); see profiles/.
+TRAFFIC = {
+    ("cfg2_3x3s2_c128k256_56", "contract_kernel"): 332.9e6,
+    ("cfg2_3x3s2_c128k256_56", "input_transform_kernel"): 232.5e6,
+}
+
+
+def _uses_single_kernel(dwm, plan, args):
+    """True if dwm_conv_forward runs the single-kernel path for this plan (few input channels)."""
+    if args.forward_variant == 0:
+        return False
+    try:
+        dwm.dwm_plan_set_variant(plan, "forward", 1)  # refused where the path does not apply
+    except dwm.DwmError:
+        return False
+    dwm.dwm_plan_set_variant(plan, "forward", args.forward_variant)
+    return True
 
 
 def cpu_baseline(x, w, L, target_s=12.0):
@@ -57,6 +79,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--paper-layer", type=str, default="", help="KERNEL,HW,STRIDE e.g. 7,14,1")
     ap.add_argument("--contract-variant", type=int, default=-1)
     ap.add_argument("--input-variant", type=int, default=-1)
     ap.add_argument("--split-mode", type=int, default=-1)
@@ -77,8 +100,13 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
-    L = wl.CONFIGS[args.config]
-    x, w = wl.make_layer_tensors(L, args.config)
+    if args.paper_layer:
+        kern, hw, stride = (int(v) for v in args.paper_layer.split(","))
+        L = wl.paper_layer(kern, hw, stride)
+        x, w = wl.make_layer_tensors(L, 100 * kern + hw + stride)
+    else:
+        L = wl.CONFIGS[args.config]
+        x, w = wl.make_layer_tensors(L, args.config)
 
     plan = dwm.dwm_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     info = dwm.dwm_plan_info(plan)
@@ -116,39 +144,61 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = info.direct_flops / (dt / args.steps) / 1e12
 
-    # Per-kernel durations: the same K steps again, each stage bracketed by HIP events on the
+    # Per-kernel durations: the same K steps again, each kernel bracketed by HIP events on the
     # stream the kernels run on (torch's current stream is the one handed to the library).
-    e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for i in range(args.steps):
-        e[i][0].record()
-        dwm.dwm_input_transform(plan, xp, st)
-        e[i][1].record()
-        dwm.dwm_contract_output(plan, Up, yp, st)
-        e[i][2].record()
-    torch.cuda.synchronize()
-    in_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
-    ct_ms = sum(b.elapsed_time(c) for _, b, c in e) / args.steps
-
+    fused = _uses_single_kernel(dwm, plan, args)
     v_bytes = 4.0 * info.mults_per_tile * L.C * info.T
     x_bytes, y_bytes = 4.0 * x.size, 4.0 * y.numel()
-    stages = {
-        "input_transform": {"ms": in_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + v_bytes,
-                            "achieved_GBps": (x_bytes + v_bytes) / in_ms / 1e6,
-                            "frac_of_hbm_peak": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM},
-        "contract_output": {"ms": ct_ms, "bound": "mfma", "algorithmic_flops": info.winograd_flops,
-                            "achieved_TFLOPs": info.winograd_flops / ct_ms / 1e9,
-                            "frac_of_mfma_peak": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32,
-                            "hbm_GBps_on_V_U_y": (v_bytes + y_bytes + 4.0 * U.numel()) / ct_ms / 1e6},
-        "filter_transform_once": {"ms": filter_ms},
-    }
-    if ct_ms >= in_ms:
-        roofline = {"kernel": "contract_output_kernel", "bound": "mfma",
-                    "achieved": info.winograd_flops / ct_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
-                    "frac": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32, "traffic": None}
+    e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    if fused:
+        for i in range(args.steps):
+            e[i][0].record()
+            dwm.dwm_conv_forward(plan, xp, Up, yp, st)
+            e[i][1].record()
+        torch.cuda.synchronize()
+        f_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
+        stages = {
+            "fused_forward": {"ms": f_ms, "algorithmic_flops": info.winograd_flops,
+                              "achieved_TFLOPs": info.winograd_flops / f_ms / 1e9,
+                              "frac_of_mfma_peak": info.winograd_flops / f_ms / 1e9 / PEAK_MFMA_F32,
+                              "hbm_GBps_on_x_y": (x_bytes + y_bytes) / f_ms / 1e6,
+                              "frac_of_hbm_peak": (x_bytes + y_bytes) / f_ms / 1e6 / PEAK_HBM},
+            "filter_transform_once": {"ms": filter_ms},
+        }
+        roofline = {"kernel": "fused_forward_kernel", "bound": "mfma",
+                    "achieved": info.winograd_flops / f_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
+                    "frac": info.winograd_flops / f_ms / 1e9 / PEAK_MFMA_F32,
+                    "traffic": TRAFFIC.get((L.name, "fused_forward_kernel"))}
     else:
-        roofline = {"kernel": "input_transform_kernel", "bound": "hbm",
-                    "achieved": (x_bytes + v_bytes) / in_ms / 1e6, "peak": PEAK_HBM, "unit": "GB/s",
-                    "frac": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM, "traffic": None}
+        for i in range(args.steps):
+            e[i][0].record()
+            dwm.dwm_input_transform(plan, xp, st)
+            e[i][1].record()
+            dwm.dwm_contract_output(plan, Up, yp, st)
+            e[i][2].record()
+        torch.cuda.synchronize()
+        in_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
+        ct_ms = sum(b.elapsed_time(c) for _, b, c in e) / args.steps
+        stages = {
+            "input_transform": {"ms": in_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + v_bytes,
+                                "achieved_GBps": (x_bytes + v_bytes) / in_ms / 1e6,
+                                "frac_of_hbm_peak": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM},
+            "contract_output": {"ms": ct_ms, "bound": "mfma", "algorithmic_flops": info.winograd_flops,
+                                "achieved_TFLOPs": info.winograd_flops / ct_ms / 1e9,
+                                "frac_of_mfma_peak": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32,
+                                "hbm_GBps_on_V_U_y": (v_bytes + y_bytes + 4.0 * U.numel()) / ct_ms / 1e6},
+            "filter_transform_once": {"ms": filter_ms},
+        }
+        if ct_ms >= in_ms:
+            roofline = {"kernel": "contract_kernel", "bound": "mfma",
+                        "achieved": info.winograd_flops / ct_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
+                        "frac": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32,
+                        "traffic": TRAFFIC.get((L.name, "contract_kernel"))}
+        else:
+            roofline = {"kernel": "input_transform_kernel", "bound": "hbm",
+                        "achieved": (x_bytes + v_bytes) / in_ms / 1e6, "peak": PEAK_HBM, "unit": "GB/s",
+                        "frac": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM,
+                        "traffic": TRAFFIC.get((L.name, "input_transform_kernel"))}
 
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -159,6 +209,7 @@ def main():
                    "mults_per_tile": info.mults_per_tile, "direct_GFLOP": info.direct_flops / 1e9,
                    "winograd_GFLOP": info.winograd_flops / 1e9},
         "roofline": roofline, "stages": stages,
+        "path": "single kernel (input staged in LDS)" if fused else "input transform + contraction",
     }
 
     if not args.no_check:
