@@ -124,8 +124,11 @@ DWM_API size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan);
  * dwm_plan_workspace_bytes(plan) long, alive as long as the plan is used.  No GPU call. */
 DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size_t bytes);
 
-/* Pick a kernel variant for a stage ("input", "contract"); variant < 0 restores the
- * planner's own choice.  For tuning and tests; results are the same up to fp32 rounding.
+/* Pick a kernel variant for a stage; variant < 0 restores the planner's own choice.
+ *   "contract": tile shape / chunk depth of the contraction kernel (ids in csrc/plan.hpp);
+ *   "forward":  0 = input transform + contraction, 1 = single kernel (few input channels only);
+ *   "input":    0 = blocks-fast, 1 = rows-fast workgroup order of the input transform;
+ *   "split":    0 = whole tiles + split remainder, 1 = all tiles split evenly (contraction).  For tuning and tests; results are the same up to fp32 rounding.
  * The workspace size depends on the contraction variant: choose it BEFORE asking
  * dwm_plan_workspace_bytes.  DWM_ERR_INVALID_ARG for an unknown stage or a variant that does
  * not apply to this plan; DWM_ERR_WORKSPACE (variant unchanged) if a workspace was already

@@ -184,14 +184,19 @@ __device__ __forceinline__ void input_rows4(const DevPlan& P, const DevClass& q,
 
 __global__ __launch_bounds__(256) void input_transform_kernel(DevPlan P, const float* __restrict__ x,
                                                               float* __restrict__ V, int* __restrict__ counters,
-                                                              int n_counters)
+                                                              int n_counters, int rows_fast)
 {
     // The contraction that follows counts partial-tile arrivals in `counters`; they start at zero.
     if (blockIdx.x == 0 && blockIdx.y == 0)
         for (int i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
 
-    const int t = blockIdx.x * 64 + (threadIdx.x & 63);  // < Tpad by construction of the grid
-    const int row = blockIdx.y * 16 + (threadIdx.x >> 6) * 4;  // 4 rows, never across a class (Lpad % 16 == 0)
+    // Workgroup order.  rows_fast: consecutive workgroups take consecutive row groups of the SAME
+    // 64-tile block, so every part and channel of those tiles is in flight together and x is
+    // fetched from HBM once (it matters when x outgrows the L2).  Otherwise consecutive
+    // workgroups take consecutive blocks of the same rows (measured faster while x stays cached).
+    const int bt = rows_fast ? blockIdx.y : blockIdx.x, br = rows_fast ? blockIdx.x : blockIdx.y;
+    const int t = bt * 64 + (threadIdx.x & 63);          // < Tpad by construction of the grid
+    const int row = br * 16 + (threadIdx.x >> 6) * 4;    // 4 rows, never across a class (Lpad % 16 == 0)
     const int qi = find_class(P, row);
     const DevClass q = P.cls[qi];
     const int l0 = row - q.row0;
@@ -236,10 +241,14 @@ dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream)
 {
     const DevPlan& d = p.d;
-    if (d.rows_total / 16 > 65535) return DWM_ERR_UNSUPPORTED;
-    dim3 grid(d.Tpad / 64, d.rows_total / 16), block(256);
+    const int nb = d.Tpad / 64, nr = d.rows_total / 16;
+    int rows_fast = (size_t)d.N * d.C * d.H * d.W * sizeof(float) > ((size_t)64 << 20);
+    if (p.variant_input == 0 || p.variant_input == 1) rows_fast = p.variant_input;
+    if ((rows_fast ? nb : nr) > 65535) rows_fast = !rows_fast;
+    if ((rows_fast ? nb : nr) > 65535) return DWM_ERR_UNSUPPORTED;
+    dim3 grid(rows_fast ? nr : nb, rows_fast ? nb : nr), block(256);
     hipLaunchKernelGGL(input_transform_kernel, grid, block, 0, (hipStream_t)stream, d, x, V, p.sk_counters(),
-                       p.geo.n_sk_tiles);
+                       p.geo.n_sk_tiles, rows_fast);
     return check_launch();
 }
 
