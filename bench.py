@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--contract-variant", type=int, default=-1)
     ap.add_argument("--input-variant", type=int, default=-1)
     ap.add_argument("--split-mode", type=int, default=-1)
+    ap.add_argument("--input-cg", type=int, default=-1)
     ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -114,6 +115,8 @@ def main():
         dwm.dwm_plan_set_variant(plan, "contract", args.contract_variant)
     if args.input_variant >= 0:
         dwm.dwm_plan_set_variant(plan, "input", args.input_variant)
+    if args.input_cg >= 0:
+        dwm.dwm_plan_set_variant(plan, "input_cg", args.input_cg)
     if args.split_mode >= 0:
         dwm.dwm_plan_set_variant(plan, "split", args.split_mode)
     if args.forward_variant >= 0:

@@ -127,7 +127,10 @@ DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size
 /* Pick a kernel variant for a stage; variant < 0 restores the planner's own choice.
  *   "contract": tile shape / chunk depth of the contraction kernel (ids in csrc/plan.hpp);
  *   "forward":  0 = input transform + contraction, 1 = single kernel (few input channels only);
- *   "input":    0 = blocks-fast, 1 = rows-fast workgroup order of the input transform;
+ *   "input":    0, 1 = gather form of the input transform (blocks-fast / rows-fast workgroup order),
+ *               2, 3 = LDS-staged form (channel groups fastest / blocks fastest; refused when the
+ *               rows one block of 64 tiles needs do not fit in LDS);
+ *   "input_cg": channels per workgroup of the LDS-staged form (0 = planner's choice);
  *   "split":    0 = whole tiles + split remainder, 1 = all tiles split evenly (contraction).  For tuning and tests; results are the same up to fp32 rounding.
  * The workspace size depends on the contraction variant: choose it BEFORE asking
  * dwm_plan_workspace_bytes.  DWM_ERR_INVALID_ARG for an unknown stage or a variant that does

@@ -233,6 +233,7 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     in.Kpad = d.Kpad; in.Tpad = d.Tpad;
     in.Vblock = (long long)d.vblock_rows * 64;
     p->fused_ok = dwm::fused_setup(*p, &p->fused);
+    p->inlds_ok = dwm::input_lds_setup(*p, &p->inlds, 0);
     if (p->fused_ok) {
         // the single-kernel path reads U transposed (filters fastest): a second copy after the first
         long long ut = (long long)p->filter_floats;
@@ -302,7 +303,15 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
 {
     if (!plan || !stage) return DWM_ERR_INVALID_ARG;
     if (!std::strcmp(stage, "input")) {
+        if (variant > 3 || (variant >= 2 && !plan->inlds_ok)) return DWM_ERR_INVALID_ARG;
         plan->variant_input = variant;
+        return DWM_OK;
+    }
+    if (!std::strcmp(stage, "input_cg")) {  // channels per workgroup of the LDS-staged input transform
+        dwm::InLdsArgs a;
+        if (!dwm::input_lds_setup(*plan, &a, variant) || (variant > 0 && a.cg != variant)) return DWM_ERR_INVALID_ARG;
+        plan->inlds = a;
+        plan->inlds_ok = true;
         return DWM_OK;
     }
     if (!std::strcmp(stage, "forward")) {

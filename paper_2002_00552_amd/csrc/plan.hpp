@@ -136,6 +136,20 @@ struct FusedArgs {
     size_t lds_bytes;
 };
 
+// Geometry of the LDS-staged input transform (transforms.hip): a workgroup stages the input
+// rows that one 64-tile block needs, for `cg` channels, and builds every part's V from LDS.
+struct InLdsArgs {
+    int cg, ncg;                     // channels per workgroup, workgroups along C
+    int nphase, lwp, lw_in;          // 2*stride phases, floats per (row, phase) (odd), staged columns
+    int row_floats, chan_floats;     // LDS floats per staged row / per channel
+    int max_rows;                    // most rows any block stages
+    int foot_h;                      // rows one tile row needs: 2*stride*(ntr-1) + foot_h for ntr tile rows
+    int rows_full;                   // rows of a whole image's tile rows
+    FastDiv div_tw, div_th, div_lw, div_nphase, div_rows_full;
+    int roff[kMaxPieces][4], coff[kMaxPieces][4];  // LDS offset of patch row a / column b of a piece
+    size_t lds_bytes;
+};
+
 }  // namespace dwm
 
 // The opaque plan of the C ABI.
@@ -155,6 +169,8 @@ struct dwm_plan {
     bool fused_ok;      // the single-kernel path applies to this layer
     int variant_forward;  // < 0: planner's choice (fused when it applies), 0: staged, 1: fused
     dwm::FusedArgs fused;
+    bool inlds_ok;      // the LDS-staged input transform applies (its staged rows fit in LDS)
+    dwm::InLdsArgs inlds;
     bool use_fused() const { return fused_ok && variant_forward != 0; }
 
     // workspace layout: [ V | partial outputs | arrival counters ]
@@ -171,6 +187,7 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out);
 dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U, void* stream);
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream);
 dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const float* V, float* y, void* stream);
+bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish);
 // fused.hip
 bool fused_setup(const dwm_plan& p, FusedArgs* out);
 dwm_status_t launch_fused_forward(const dwm_plan& p, const float* x, const float* U, float* y, void* stream);

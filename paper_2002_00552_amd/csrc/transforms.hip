@@ -5,6 +5,8 @@
 // two-multiplication forms for 2-tap and 1-tap pieces.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "plan.hpp"
 
 namespace dwm {
@@ -213,6 +215,197 @@ __global__ __launch_bounds__(256) void input_transform_kernel(DevPlan P, const f
     }
 }
 
+
+// ---------------------------------------------------------------------------------
+// Input transform, LDS-staged form.
+//
+// A workgroup owns one 64-tile block of V (lane = tile) and `cg` input channels.  Each of
+// its four waves stages the input rows that the block's tiles touch, for ITS channels
+// (c = c0 + wave, c0 + wave + 4, ...), once, with coalesced loads: zero padding is written
+// explicitly and columns are de-interleaved modulo 2*stride, so that the same patch element
+// of adjacent tiles sits in adjacent LDS words.  The wave then walks every part of every
+// class for those channels: a patch element is one LDS read at (lane's tile base) + (an
+// offset that is the same for the whole wave).  x is read from HBM about once and every
+// load instruction is fully used; the global-memory gathers of the other form (one 4-byte
+// load per patch element, lanes 2*stride floats apart) are gone.  Waves never wait for each
+// other: a wave reads only what it staged itself.
+// The 64 tiles of a block span a few tile rows, possibly of several images: the staged rows
+// are the union per image ("segments"), stored one after the other.
+// ---------------------------------------------------------------------------------
+constexpr int kInLdsBatch = 16;  // input rows a wave loads before it writes them to LDS
+
+// UN consecutive image rows, one float per lane each, into consecutive staged rows.
+// xrow: address of the first row's column 0 (the same for the whole wave); voff: the lane's
+// byte offset inside a row.
+template <int UN>
+__device__ __forceinline__ void stage_rows(const char* __restrict__ xrow, unsigned voff, size_t row_bytes,
+                                           float* __restrict__ xd, int row_floats, bool iw_ok)
+{
+    float v[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) v[u] = *reinterpret_cast<const float*>(xrow + u * row_bytes + voff);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) xd[u * row_floats] = iw_ok ? v[u] : 0.f;
+}
+
+template <int LH, int LW>
+__device__ __forceinline__ void lds_class_rows(const DevPlan& P, const InLdsArgs& A, const DevClass& q,
+                                               const float* __restrict__ xl, float* __restrict__ vb, int c0,
+                                               int cn, int wave, bool valid)
+{
+    constexpr int TH_ = LH + 1, TW_ = LW + 1;
+    const size_t plane = (size_t)q.Lpad * 64;
+    for (int a = 0; a < q.hn; ++a)
+        for (int b = 0; b < q.wn; ++b) {
+            int ro[TH_], co[TW_];
+#pragma unroll
+            for (int i = 0; i < TH_; ++i) ro[i] = A.roff[q.h0 + a][i];
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) co[j] = A.coff[q.w0 + b][j];
+            const int lbase = (a * q.wn + b) * P.C + c0;
+            for (int cl = wave; cl < cn; cl += 4) {
+                const float* xc = xl + cl * A.chan_floats;
+                float d[TH_][TW_];
+#pragma unroll
+                for (int i = 0; i < TH_; ++i)
+#pragma unroll
+                    for (int j = 0; j < TW_; ++j) d[i][j] = xc[ro[i] + co[j]];
+                float* vp = vb + (size_t)(q.v_row0 + lbase + cl) * 64;
+                // columns first (B^T d), then rows ((B^T d) B)
+                float tmp[4][4];
+#pragma unroll
+                for (int j = 0; j < TW_; ++j) {
+                    float col[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+#pragma unroll
+                    for (int i = 0; i < TH_; ++i) col[i] = d[i][j];
+                    bt_apply<LH>(col, o);
+#pragma unroll
+                    for (int i = 0; i < TH_; ++i) tmp[i][j] = o[i];
+                }
+#pragma unroll
+                for (int i = 0; i < TH_; ++i) {
+                    float rowv[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+#pragma unroll
+                    for (int j = 0; j < TW_; ++j) rowv[j] = tmp[i][j];
+                    bt_apply<LW>(rowv, o);
+                    if (valid) {
+#pragma unroll
+                        for (int j = 0; j < TW_; ++j) vp[(size_t)(i * TW_ + j) * plane] = o[j];
+                    }
+                }
+            }
+        }
+}
+
+__global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InLdsArgs A,
+                                                                  const float* __restrict__ x,
+                                                                  float* __restrict__ V, int* __restrict__ counters,
+                                                                  int n_counters, int chan_fast)
+{
+    extern __shared__ __attribute__((aligned(16))) float xs[];  // [cg][max_rows][nphase][lwp]
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int nbt = P.Tpad / 64;
+    const int b = blockIdx.x;
+    const int bt = chan_fast ? b / A.ncg : b % nbt, bc = chan_fast ? b % A.ncg : b / nbt;
+    const int c0 = bc * A.cg, cn = min(A.cg, P.C - c0);
+    const int t0 = bt * 64;
+    if (t0 >= P.T) return;  // a block of padding only (Tpad is rounded up to 256)
+    const int t1 = min(t0 + 63, P.T - 1);
+    const int s2 = 2 * P.s;
+    const int g0 = A.div_tw.div(t0), g1 = A.div_tw.div(t1);
+    const int n0 = A.div_th.div(g0), n1 = A.div_th.div(g1);
+    const int ty_a0 = g0 - n0 * P.TH, ty_b1 = g1 - n1 * P.TH;
+    const int rows0 = s2 * ((n1 == n0 ? ty_b1 : P.TH - 1) - ty_a0) + A.foot_h;
+
+    // ---- 1. this wave stages its channels: lanes along a row, rows in batches of up to
+    // kInLdsBatch loads, segment by segment.  Rows above or below the image are written as
+    // zeros; columns left or right of it are loaded from a clamped (legal) address and
+    // replaced by zero on the way to LDS.
+    const size_t img = (size_t)P.C * P.H * P.W;
+    const size_t row_bytes = (size_t)P.W * sizeof(float);
+    for (int cl = wave; cl < cn; cl += 4) {
+        const float* xc = x + ((size_t)n0 * P.C + c0 + cl) * P.H * P.W;
+        float* xsc = xs + cl * A.chan_floats;
+        for (int cb = 0; cb < A.lw_in; cb += 64) {
+            const int col = cb + lane, iw = col - P.P;
+            const bool iw_ok = iw >= 0 && iw < P.W;
+            const unsigned voff = (unsigned)min(max(iw, 0), P.W - 1) * 4u;
+            const int idx = A.div_nphase.div(col);
+            float* xd = xsc + (col - idx * A.nphase) * A.lwp + idx;
+            if (col < A.lw_in) {
+                for (int k = 0; k <= n1 - n0; ++k) {
+                    const int ty_a = k == 0 ? ty_a0 : 0, ty_b = n0 + k == n1 ? ty_b1 : P.TH - 1;
+                    const int nrows = s2 * (ty_b - ty_a) + A.foot_h, ih0 = s2 * ty_a - P.P;
+                    const int r_lo = min(max(-ih0, 0), nrows), r_hi = max(min(P.H - ih0, nrows), r_lo);
+                    for (int r = 0; r < r_lo; ++r) xd[r * A.row_floats] = 0.f;
+                    for (int r = r_hi; r < nrows; ++r) xd[r * A.row_floats] = 0.f;
+                    const char* xrow = reinterpret_cast<const char*>(xc + (size_t)k * img) + (size_t)(ih0 + r_lo) * row_bytes;
+                    float* xdr = xd + r_lo * A.row_floats;
+                    int left = r_hi - r_lo;
+                    for (; left >= kInLdsBatch; left -= kInLdsBatch) {
+                        stage_rows<kInLdsBatch>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                        xrow += kInLdsBatch * row_bytes;
+                        xdr += kInLdsBatch * A.row_floats;
+                    }
+                    if (left & 8) {
+                        stage_rows<8>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                        xrow += 8 * row_bytes;
+                        xdr += 8 * A.row_floats;
+                    }
+                    if (left & 4) {
+                        stage_rows<4>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                        xrow += 4 * row_bytes;
+                        xdr += 4 * A.row_floats;
+                    }
+                    if (left & 2) {
+                        stage_rows<2>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                        xrow += 2 * row_bytes;
+                        xdr += 2 * A.row_floats;
+                    }
+                    if (left & 1) stage_rows<1>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                    xd += nrows * A.row_floats;
+                }
+            }
+        }
+    }
+
+    // ---- 2. every part of every class for those channels ----
+    const int t = t0 + lane;
+    const bool valid = t < P.T;
+    int lane_base = 0;
+    if (valid) {
+        const int g = A.div_tw.div(t), tx = t - g * P.TW;
+        const int n = A.div_th.div(g), ty = g - n * P.TH;
+        const int base_row = n == n0 ? s2 * (ty - ty_a0) : rows0 + (n - n0 - 1) * A.rows_full + s2 * ty;
+        lane_base = base_row * A.row_floats + tx;
+    }
+    const float* xl = xs + lane_base;
+    float* vb = V + (size_t)bt * P.vblock_rows * 64 + lane;
+    for (int qi = 0; qi < P.ncls; ++qi) {
+        const DevClass q = P.cls[qi];
+        switch (q.lh * 4 + q.lw) {
+            case 3 * 4 + 3: lds_class_rows<3, 3>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 3 * 4 + 2: lds_class_rows<3, 2>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 3 * 4 + 1: lds_class_rows<3, 1>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 2 * 4 + 3: lds_class_rows<2, 3>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 2 * 4 + 2: lds_class_rows<2, 2>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 2 * 4 + 1: lds_class_rows<2, 1>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 1 * 4 + 3: lds_class_rows<1, 3>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            case 1 * 4 + 2: lds_class_rows<1, 2>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+            default: lds_class_rows<1, 1>(P, A, q, xl, vb, c0, cn, wave, valid); break;
+        }
+        // rows past the class's reduction length are zeros (the contraction multiplies them)
+        if (bc == 0 && valid) {
+            const int planes = (q.lh + 1) * (q.lw + 1);
+            for (int l = q.L + wave; l < q.Lpad; l += 4)
+                for (int pl = 0; pl < planes; ++pl) vb[((size_t)q.v_row0 + (size_t)pl * q.Lpad + l) * 64] = 0.f;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------
@@ -238,15 +431,93 @@ dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U
     return check_launch();
 }
 
+// Does the LDS-staged form apply, and with how many channels per workgroup: the rows a block
+// stages must fit in LDS.  The row count depends on where a block of 64 tiles starts; the
+// pattern repeats after at most TH*TW blocks, so the maximum is found by walking them.
+bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish)
+{
+    const DevPlan& d = p.d;
+    InLdsArgs a{};
+    int max_oh = 0, max_ow = 0;
+    for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
+    for (int i = 0; i < d.nw; ++i) max_ow = std::max(max_ow, d.s * (d.pw[i].j + d.pw[i].l) + d.pw[i].p);
+    if (d.s > 4096 || max_oh > (1 << 20) || max_ow > (1 << 20)) return false;
+    a.nphase = 2 * d.s;
+    a.foot_h = max_oh + 1;
+    const long long lw_in = 2LL * d.s * (d.TW - 1) + max_ow + 1;
+    const long long rows_full = 2LL * d.s * (d.TH - 1) + a.foot_h;
+    if (lw_in > (1 << 16) || rows_full > (1 << 24)) return false;
+    a.lw_in = (int)lw_in;
+    a.lwp = ((a.lw_in + a.nphase - 1) / a.nphase) | 1;
+    a.row_floats = a.nphase * a.lwp;
+    a.rows_full = (int)rows_full;
+    const long long per = (long long)d.TH * d.TW;
+    const long long nb = (d.T + 63) / 64, scan = std::min(nb, per);
+    long long max_rows = 0;
+    const int s2 = 2 * d.s;
+    for (long long bt = 0; bt < scan; ++bt) {
+        const long long t0 = bt * 64, t1 = std::min<long long>(t0 + 63, d.T - 1);
+        const long long g0 = t0 / d.TW, g1 = t1 / d.TW, n0 = g0 / d.TH, n1 = g1 / d.TH;
+        const long long ty_a0 = g0 - n0 * d.TH, ty_b1 = g1 - n1 * d.TH;
+        const long long rows0 = s2 * ((n1 == n0 ? ty_b1 : d.TH - 1) - ty_a0) + a.foot_h;
+        const long long total = n1 == n0 ? rows0 : rows0 + (n1 - n0 - 1) * rows_full + s2 * ty_b1 + a.foot_h;
+        max_rows = std::max(max_rows, total);
+        if (max_rows * a.row_floats * 4 > 64 * 1024) return false;
+    }
+    a.max_rows = (int)max_rows;
+    a.chan_floats = a.max_rows * a.row_floats;
+    const size_t chan_bytes = (size_t)a.chan_floats * sizeof(float);
+    if (chan_bytes > 64 * 1024) return false;
+    // channels per workgroup: one per wave (measured best: many small workgroups keep more loads
+    // and stores in flight than fewer large ones)
+    int cg = d.C < 4 ? d.C : 4;
+    if (cg_wish > 0 && cg_wish <= d.C && cg_wish * chan_bytes <= 150 * 1024) cg = cg_wish;
+    a.cg = cg;
+    a.ncg = (d.C + cg - 1) / cg;
+    if ((long long)a.ncg * (d.Tpad / 64) > 0x7fffffffLL) return false;
+    a.div_tw.init((unsigned)d.TW);
+    a.div_th.init((unsigned)d.TH);
+    a.div_lw.init((unsigned)a.lw_in);
+    a.div_nphase.init((unsigned)a.nphase);
+    a.div_rows_full.init((unsigned)a.rows_full);
+    for (int i = 0; i < kMaxPieces; ++i)
+        for (int k = 0; k < 4; ++k) {
+            const int oh = i < d.nh ? d.s * (d.ph[i].j + k) + d.ph[i].p : 0;
+            const int ow = i < d.nw ? d.s * (d.pw[i].j + k) + d.pw[i].p : 0;
+            a.roff[i][k] = oh * a.row_floats;
+            a.coff[i][k] = (ow % a.nphase) * a.lwp + ow / a.nphase;
+        }
+    a.lds_bytes = (size_t)cg * chan_bytes;
+    *out = a;
+    return true;
+}
+
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream)
 {
     const DevPlan& d = p.d;
     const int nb = d.Tpad / 64, nr = d.rows_total / 16;
-    int rows_fast = (size_t)d.N * d.C * d.H * d.W * sizeof(float) > ((size_t)64 << 20);
-    if (p.variant_input == 0 || p.variant_input == 1) rows_fast = p.variant_input;
+    dim3 block(256);
+    // variants: 0/1 = gather form (blocks-fast / rows-fast), 2/3 = LDS-staged form (channel groups
+    // fastest / blocks fastest); planner's choice: LDS-staged where it applies
+    int variant = p.variant_input;
+    if (variant < 0) variant = p.inlds_ok ? 2 : ((size_t)d.N * d.C * d.H * d.W * sizeof(float) > ((size_t)64 << 20));
+    if (variant >= 2) {
+        if (!p.inlds_ok) return DWM_ERR_INVALID_ARG;
+        const InLdsArgs& a = p.inlds;
+        auto kernel = input_transform_lds_kernel;
+        if (a.lds_bytes > 64 * 1024) {
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (attr != hipSuccess) return DWM_ERR_HIP;
+        }
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(nb * a.ncg)), block, a.lds_bytes, (hipStream_t)stream, d, a, x, V,
+                           p.sk_counters(), p.geo.n_sk_tiles, variant == 2);
+        return check_launch();
+    }
+    int rows_fast = variant;
     if ((rows_fast ? nb : nr) > 65535) rows_fast = !rows_fast;
     if ((rows_fast ? nb : nr) > 65535) return DWM_ERR_UNSUPPORTED;
-    dim3 grid(rows_fast ? nr : nb, rows_fast ? nb : nr), block(256);
+    dim3 grid(rows_fast ? nr : nb, rows_fast ? nb : nr);
     hipLaunchKernelGGL(input_transform_kernel, grid, block, 0, (hipStream_t)stream, d, x, V, p.sk_counters(),
                        p.geo.n_sk_tiles, rows_fast);
     return check_launch();

@@ -104,6 +104,64 @@ def test_input_transform_matches_oracle(shape):
     r.close()
 
 
+def _v_rows(r):
+    """The transformed input as [row][t], t < T, from the plan's workspace (blocked by 64 tiles)."""
+    info = r.info
+    rows = info.Vblock // 64
+    V = r.ws.cpu().numpy()[:(info.Tpad // 64) * info.Vblock].reshape(info.Tpad // 64, rows, 64)
+    return V.transpose(1, 0, 2).reshape(rows, info.Tpad)[:, :info.T]
+
+
+FORM_SHAPES = [
+    (2, 3, 23, 22, 4, 7, 7, 2, 3),
+    (3, 9, 14, 14, 5, 7, 7, 1, 3),       # a block of 64 tiles spans three images
+    (70, 5, 6, 6, 3, 3, 3, 1, 1),        # ... and here eight
+    (1, 6, 31, 29, 3, 11, 11, 4, 0),
+    (2, 10, 19, 21, 7, 3, 3, 2, 1),
+    (1, 4, 9, 300, 4, 3, 5, 1, 2),       # rows wider than one wave
+    (1, 2, 150, 700, 3, 5, 5, 2, 2),
+    (2, 7, 12, 12, 9, 1, 1, 2, 0),       # kernel shorter than the stride
+]
+
+
+@pytest.mark.parametrize("shape", FORM_SHAPES)
+def test_input_transform_forms_agree(shape):
+    """The gather form (variants 0, 1) and the LDS-staged form (2, 3; any channel group size)
+    apply the same additions in the same order: V must be bit-identical."""
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand(*shape[:7], seed=21)
+    xd = torch.from_numpy(x).cuda()
+    ref = None
+    for variant, cg in [(0, 0), (1, 0), (2, 0), (3, 0), (2, 1), (2, min(C, 3)), (3, min(C, 8))]:
+        r = Runner(*shape)
+        if cg:
+            dwm.dwm_plan_set_variant(r.plan, "input_cg", cg)
+        dwm.dwm_plan_set_variant(r.plan, "input", variant)
+        dwm.dwm_input_transform(r.plan, xd.data_ptr(), r.stream())
+        torch.cuda.synchronize()
+        V = _v_rows(r).copy()
+        r.close()
+        assert np.all(np.isfinite(V)), (variant, cg)
+        if ref is None:
+            ref = V
+        else:
+            assert np.array_equal(V, ref), (variant, cg)
+
+
+def test_input_transform_falls_back_when_rows_do_not_fit_in_lds():
+    """A very wide image: the staged rows of one block exceed LDS, so only the gather form
+    applies; the planner must choose it and refuse the other."""
+    shape = (1, 2, 12, 6000, 3, 3, 3, 1, 1)
+    x, w = _rand(*shape[:7], seed=22)
+    ref = oracle.direct_f64(x, w, 1, 1)
+    p = dwm.dwm_plan_create(*shape)
+    with pytest.raises(dwm.DwmError):
+        dwm.dwm_plan_set_variant(p, "input", 2)
+    dwm.dwm_plan_destroy(p)
+    y = conv(x, w, 1, 1, variants={"forward": 0})
+    assert _relerr(y, ref) <= TOL
+
+
 # ---- end-to-end parity on small shapes that span several tiles and ragged tails ----
 
 E2E_SHAPES = [
