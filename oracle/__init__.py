@@ -12,6 +12,7 @@ compiles it with gcc on first use and exposes thin numpy wrappers:
 * ``split_1d / split_2d``   the paper's kernel splitting (Sec. 4.1, eq. 8 and eq. 12)
 * ``mults_per_tile``        the multiplication-count model behind Table 3
 * ``winograd_matrices``     B^T, G, A^T of F(2,l), l = 1..3 (Sec. 3.2 for l = 3)
+* ``set_f22_form``          which of the two F(2,2) forms the 2-tap pieces use
 * ``winograd_1d``           Y = A^T[(G g) .* (B^T d)] (Sec. 3.1)
 * ``part_filter_transform`` U = G g G^T of one part
 * ``part_input_transform``  V = B^T d B of one part, one image
@@ -140,6 +141,14 @@ def split_2d(R, S, s):
 
 def mults_per_tile(R, S, s):
     return int(_load().oracle_mults_per_tile(R, S, s))
+
+
+def set_f22_form(form):
+    """Which three-multiplication F(2,2) every function below uses for 2-tap pieces:
+    0 = the form with entries 0/+-1 (default), 1 = the printed F(2,3) without its point at
+    infinity (points 0, 1, -1).  The paper prints neither; both are exact."""
+    if _load().oracle_set_f22_form(int(form)):
+        raise ValueError("form must be 0 or 1")
 
 
 def winograd_matrices(l):

@@ -112,22 +112,36 @@ int oracle_direct_f64_at(const float* x, const float* w, const long long* idx, l
  * 2-tap piece costs 3 multiplications, a 1-tap piece costs 2):
  *   F(2,2): m1=(d0-d1)g0, m2=d1(g0+g1), m3=(d2-d1)g1; y0=m1+m2, y1=m2+m3
  *   F(2,1): m1=d0 g0, m2=d1 g0 (no transform at all)
+ * A second F(2,2) with three multiplications is kept beside it (slot 0 of the tables,
+ * chosen with oracle_set_f22_form(1)): the one that evaluates at the points 0, 1, -1 --
+ * the printed F(2,3) of Sec. 3.2 without its point at infinity, i.e. a 3-tap piece whose
+ * third tap is zero, fourth product dropped because it vanishes:
+ *   m1=(d0-d2)g0, m2=(d1+d2)(g0+g1)/2, m3=(d2-d1)(g0-g1)/2; y0=m1+m2+m3, y1=m2-m3
+ * The paper fixes neither; both are exact, both cost what Table 3 counts.
  * Stored in 4x4 / 4x3 / 2x4 arrays, upper-left corner used: tile length l+1.
  */
+static int f22_form_ = 0;
+#define LIDX(l) (((l) == 2 && f22_form_) ? 0 : (l))
+int oracle_set_f22_form(int form)
+{
+    if (form != 0 && form != 1) return 1;
+    f22_form_ = form;
+    return 0;
+}
 static const double BT_[4][4][4] = {
-    {{0}},
+    /* l=2, points 0,1,-1 */ {{1, 0, -1, 0}, {0, 1, 1, 0}, {0, -1, 1, 0}, {0, 0, 0, 0}},
     /* l=1 */ {{1, 0, 0, 0}, {0, 1, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}},
     /* l=2 */ {{1, -1, 0, 0}, {0, 1, 0, 0}, {0, -1, 1, 0}, {0, 0, 0, 0}},
     /* l=3 */ {{1, 0, -1, 0}, {0, 1, 1, 0}, {0, -1, 1, 0}, {0, 1, 0, -1}},
 };
 static const double G_[4][4][3] = {
-    {{0}},
+    /* l=2, points 0,1,-1 */ {{1, 0, 0}, {0.5, 0.5, 0}, {0.5, -0.5, 0}, {0, 0, 0}},
     /* l=1 */ {{1, 0, 0}, {1, 0, 0}, {0, 0, 0}, {0, 0, 0}},
     /* l=2 */ {{1, 0, 0}, {1, 1, 0}, {0, 1, 0}, {0, 0, 0}},
     /* l=3 */ {{1, 0, 0}, {0.5, 0.5, 0.5}, {0.5, -0.5, 0.5}, {0, 0, 1}},
 };
 static const double AT_[4][2][4] = {
-    {{0}},
+    /* l=2, points 0,1,-1 */ {{1, 1, 1, 0}, {0, 1, -1, 0}},
     /* l=1 */ {{1, 0, 0, 0}, {0, 1, 0, 0}},
     /* l=2 */ {{1, 1, 0, 0}, {0, 1, 1, 0}},
     /* l=3 */ {{1, 1, 1, 0}, {0, 1, -1, -1}},
@@ -139,11 +153,11 @@ int oracle_winograd_matrices(int l, double* BT, double* G, double* AT)
     if (l < 1 || l > 3) return 1;
     const int t = l + 1;
     for (int i = 0; i < t; ++i)
-        for (int j = 0; j < t; ++j) BT[i * t + j] = BT_[l][i][j];
+        for (int j = 0; j < t; ++j) BT[i * t + j] = BT_[LIDX(l)][i][j];
     for (int i = 0; i < t; ++i)
-        for (int j = 0; j < l; ++j) G[i * l + j] = G_[l][i][j];
+        for (int j = 0; j < l; ++j) G[i * l + j] = G_[LIDX(l)][i][j];
     for (int i = 0; i < 2; ++i)
-        for (int j = 0; j < t; ++j) AT[i * t + j] = AT_[l][i][j];
+        for (int j = 0; j < t; ++j) AT[i * t + j] = AT_[LIDX(l)][i][j];
     return 0;
 }
 
@@ -155,13 +169,13 @@ int oracle_winograd_1d(int l, const double* g, const double* d, double* y2)
     double u[4], v[4];
     for (int i = 0; i < t; ++i) {
         u[i] = 0.0;
-        for (int j = 0; j < l; ++j) u[i] += G_[l][i][j] * g[j];
+        for (int j = 0; j < l; ++j) u[i] += G_[LIDX(l)][i][j] * g[j];
         v[i] = 0.0;
-        for (int j = 0; j < t; ++j) v[i] += BT_[l][i][j] * d[j];
+        for (int j = 0; j < t; ++j) v[i] += BT_[LIDX(l)][i][j] * d[j];
     }
     for (int o = 0; o < 2; ++o) {
         y2[o] = 0.0;
-        for (int i = 0; i < t; ++i) y2[o] += AT_[l][o][i] * (u[i] * v[i]);
+        for (int i = 0; i < t; ++i) y2[o] += AT_[LIDX(l)][o][i] * (u[i] * v[i]);
     }
     return 0;
 }
@@ -249,13 +263,13 @@ int oracle_part_filter_transform(const float* w, int K, int C, int R, int S, int
             for (int i = 0; i < th; ++i)
                 for (int b = 0; b < lw; ++b) {
                     Gg[i][b] = 0.0;
-                    for (int a = 0; a < lh; ++a) Gg[i][b] += G_[lh][i][a] * g[a][b];
+                    for (int a = 0; a < lh; ++a) Gg[i][b] += G_[LIDX(lh)][i][a] * g[a][b];
                 }
             double* u = U + ((size_t)k * C + c) * th * tw;
             for (int i = 0; i < th; ++i)
                 for (int j = 0; j < tw; ++j) {
                     double acc = 0.0;
-                    for (int b = 0; b < lw; ++b) acc += Gg[i][b] * G_[lw][j][b];
+                    for (int b = 0; b < lw; ++b) acc += Gg[i][b] * G_[LIDX(lw)][j][b];
                     u[i * tw + j] = acc;
                 }
         }
@@ -287,13 +301,13 @@ int oracle_part_input_transform(const float* x, int C, int H, int W, int s, int 
                 for (int i = 0; i < th; ++i)
                     for (int b = 0; b < tw; ++b) {
                         Bd[i][b] = 0.0;
-                        for (int a = 0; a < th; ++a) Bd[i][b] += BT_[lh][i][a] * d[a][b];
+                        for (int a = 0; a < th; ++a) Bd[i][b] += BT_[LIDX(lh)][i][a] * d[a][b];
                     }
                 double* v = V + (((size_t)c * TH + ty) * TW + tx) * th * tw;
                 for (int i = 0; i < th; ++i)
                     for (int j = 0; j < tw; ++j) {
                         double acc = 0.0;
-                        for (int b = 0; b < tw; ++b) acc += Bd[i][b] * BT_[lw][j][b];
+                        for (int b = 0; b < tw; ++b) acc += Bd[i][b] * BT_[LIDX(lw)][j][b];
                         v[i * tw + j] = acc;
                     }
             }
@@ -351,7 +365,7 @@ int oracle_dwm_f64(const float* x, const float* w, double* y,
                         for (int a = 0; a < 2; ++a)
                             for (int j = 0; j < tw; ++j) {
                                 AM[a][j] = 0.0;
-                                for (int i = 0; i < th; ++i) AM[a][j] += AT_[pt->lh][a][i] * M[i][j];
+                                for (int i = 0; i < th; ++i) AM[a][j] += AT_[LIDX(pt->lh)][a][i] * M[i][j];
                             }
                         /* Aggregation: add this part's 2x2 block into the output. */
                         for (int a = 0; a < 2; ++a)
@@ -359,7 +373,7 @@ int oracle_dwm_f64(const float* x, const float* w, double* y,
                                 int oh = 2 * ty + a, ow = 2 * tx + b;
                                 if (oh >= OH || ow >= OW) continue;
                                 double acc = 0.0;
-                                for (int j = 0; j < tw; ++j) acc += AM[a][j] * AT_[pt->lw][b][j];
+                                for (int j = 0; j < tw; ++j) acc += AM[a][j] * AT_[LIDX(pt->lw)][b][j];
                                 y[(((size_t)n * K + k) * OH + oh) * OW + ow] += acc;
                             }
                     }

@@ -111,9 +111,18 @@ _SWEEP = [(R, S, s, P) for R in (1, 2, 3, 4, 5, 6, 7, 9, 11) for S in (1, 3, 5, 
           for s in (1, 2, 3, 4) for P in (0, 1, 3, 5)]
 
 
-def test_dwm_equals_direct_sweep():
+@pytest.fixture
+def f22_form(request):
+    oracle.set_f22_form(request.param)
+    yield request.param
+    oracle.set_f22_form(0)
+
+
+@pytest.mark.parametrize("f22_form", [0, 1], indirect=True)
+def test_dwm_equals_direct_sweep(f22_form):
     """FP64 DWM == direct conv to 1e-12 relative over kernel sizes 1..11 (R != S too),
-    strides 1..4, paddings 0..5 (also not multiples of the stride), odd H/W, odd OH/OW."""
+    strides 1..4, paddings 0..5 (also not multiples of the stride), odd H/W, odd OH/OW;
+    with either of the two F(2,2) forms on the 2-tap pieces."""
     worst = 0.0
     for i, (R, S, s, P) in enumerate(_SWEEP):
         H, W = 9 + (i % 5), 8 + (i % 7)
@@ -138,7 +147,8 @@ def test_dwm_equals_direct_on_scaled_down_stem_shapes(R, s, P, H):
     assert _relerr(oracle.dwm_f64(x, w, s, P), oracle.direct_f64(x, w, s, P)) < 1e-12
 
 
-def test_part_stage_functions_compose_to_the_full_result():
+@pytest.mark.parametrize("f22_form", [0, 1], indirect=True)
+def test_part_stage_functions_compose_to_the_full_result(f22_form):
     """Sum over parts of A^T[(U .* V summed over c)]A, assembled here from the staged
     U and V the oracle exposes, equals O1: pins the stage outputs that the GPU's
     filter- and input-transform kernels are compared against."""

@@ -42,11 +42,21 @@ def test_f23_matrices_are_the_printed_ones(golden_dir):
         assert np.array_equal(got, want), name
 
 
+@pytest.fixture
+def f22_form(request):
+    """Select one of the oracle's two F(2,2) forms for a test, restoring the default after."""
+    oracle.set_f22_form(request.param)
+    yield request.param
+    oracle.set_f22_form(0)
+
+
+@pytest.mark.parametrize("f22_form", [0, 1], indirect=True)
 @pytest.mark.parametrize("l", [1, 2, 3])
-def test_f2l_matrices_reproduce_correlation_exactly(l):
+def test_f2l_matrices_reproduce_correlation_exactly(l, f22_form):
     """A^T[(G g) .* (B^T d)] == [sum_k d[k] g[k], sum_k d[k+1] g[k]] as an identity
     over the rationals (Sec. 3.1 formula; correlation form of the printed matrices).
-    The map is bilinear in (g, d), so exactness on all basis pairs proves it."""
+    The map is bilinear in (g, d), so exactness on all basis pairs proves it.
+    Both F(2,2) forms (the paper prints neither) must pass."""
     BT, G, AT = oracle.winograd_matrices(l)
     fr = lambda M: [[Fraction(v).limit_denominator(8) for v in row] for row in M]
     BTf, Gf, ATf = fr(BT), fr(G), fr(AT)
@@ -70,8 +80,29 @@ def test_multiplication_count_of_f2l(l):
     assert BT.shape == (l + 1, l + 1) and G.shape == (l + 1, l) and AT.shape == (2, l + 1)
 
 
+def test_second_f22_form_is_the_printed_f23_without_its_last_point(golden_dir):
+    """Form 1 of F(2,2): rows/columns 0..2 of the printed F(2,3) matrices (Sec. 3.2), i.e. a
+    3-tap piece whose third tap is zero with the vanishing fourth product dropped."""
+    gold = _read_matrices(os.path.join(golden_dir, "f23_matrices.txt"))
+    want = {k: np.array([[float(v) for v in row] for row in gold[k]]) for k in ("BT", "G", "AT")}
+    oracle.set_f22_form(1)
+    try:
+        BT, G, AT = oracle.winograd_matrices(2)
+    finally:
+        oracle.set_f22_form(0)
+    assert np.array_equal(BT, want["BT"][:3, :3])
+    assert np.array_equal(G, want["G"][:3, :2])
+    assert np.array_equal(AT, want["AT"][:, :3])
+    # the dropped parts really vanish or are unused: G's last row only sees the third tap,
+    # B^T's first three rows do not read the fourth sample
+    assert np.all(want["G"][3, :2] == 0) and np.all(want["BT"][:3, 3] == 0)
+    BT0, G0, AT0 = oracle.winograd_matrices(2)
+    assert not np.array_equal(G0, G)  # the default form is a different algorithm
+
+
+@pytest.mark.parametrize("f22_form", [0, 1], indirect=True)
 @pytest.mark.parametrize("l", [1, 2, 3])
-def test_winograd_1d_function_matches_numpy_correlate(l):
+def test_winograd_1d_function_matches_numpy_correlate(l, f22_form):
     rng = np.random.default_rng(7 + l)
     for _ in range(20):
         g, d = rng.standard_normal(l), rng.standard_normal(l + 1)
