@@ -35,18 +35,6 @@ TRAFFIC = {
 }
 
 
-def _uses_single_kernel(dwm, plan, args):
-    """True if dwm_conv_forward runs the single-kernel path for this plan (few input channels)."""
-    if args.forward_variant == 0:
-        return False
-    try:
-        dwm.dwm_plan_set_variant(plan, "forward", 1)  # refused where the path does not apply
-    except dwm.DwmError:
-        return False
-    dwm.dwm_plan_set_variant(plan, "forward", args.forward_variant)
-    return True
-
-
 def cpu_baseline(x, w, L, target_s=12.0):
     """The FP64 direct-convolution oracle, as it stands, on a bounded sample of this
     workload's outputs: direct-equivalent TFLOP/s on the host cores."""
@@ -84,7 +72,7 @@ def main():
     ap.add_argument("--input-variant", type=int, default=-1)
     ap.add_argument("--split-mode", type=int, default=-1)
     ap.add_argument("--input-cg", type=int, default=-1)
-    ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
+    ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 / 2 single kernels, -1 planner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -149,7 +137,9 @@ def main():
 
     # Per-kernel durations: the same K steps again, each kernel bracketed by HIP events on the
     # stream the kernels run on (torch's current stream is the one handed to the library).
-    fused = _uses_single_kernel(dwm, plan, args)
+    path = dwm.dwm_plan_info(plan).forward_path
+    fused = path != 0
+    kname = {1: "fused_forward_kernel", 2: "f2_forward_kernel"}.get(path)
     v_bytes = 4.0 * info.mults_per_tile * L.C * info.T
     x_bytes, y_bytes = 4.0 * x.size, 4.0 * y.numel()
     e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -168,10 +158,10 @@ def main():
                               "frac_of_hbm_peak": (x_bytes + y_bytes) / f_ms / 1e6 / PEAK_HBM},
             "filter_transform_once": {"ms": filter_ms},
         }
-        roofline = {"kernel": "fused_forward_kernel", "bound": "mfma",
+        roofline = {"kernel": kname, "bound": "mfma",
                     "achieved": info.winograd_flops / f_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
                     "frac": info.winograd_flops / f_ms / 1e9 / PEAK_MFMA_F32,
-                    "traffic": TRAFFIC.get((L.name, "fused_forward_kernel"))}
+                    "traffic": TRAFFIC.get((L.name, kname))}
     else:
         for i in range(args.steps):
             e[i][0].record()
@@ -212,7 +202,8 @@ def main():
                    "mults_per_tile": info.mults_per_tile, "direct_GFLOP": info.direct_flops / 1e9,
                    "winograd_GFLOP": info.winograd_flops / 1e9},
         "roofline": roofline, "stages": stages,
-        "path": "single kernel (input staged in LDS)" if fused else "input transform + contraction",
+        "path": ["input transform + contraction", "single kernel (V staged in LDS)",
+                 "single kernel (V in registers)"][path],
     }
 
     if not args.no_check:

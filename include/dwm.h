@@ -66,6 +66,8 @@ typedef struct {
     int Kpad;                 /* rows per plane of the transformed filter (K rounded up) */
     long long Tpad;           /* tiles covered by the transformed input (T rounded up to 256) */
     long long Vblock;         /* floats of one block of the transformed input: all planes' rows for 64 tiles */
+    int forward_path;         /* what dwm_conv_forward runs now: 0 = input transform + contraction,
+                                 1 = single kernel (layers with few input channels) */
 } dwm_plan_info_t;
 
 /* One sub-kernel.  Its taps are w[.,.,stride*(off_h+a)+phase_h, stride*(off_w+b)+phase_w],
@@ -92,15 +94,37 @@ typedef struct {
     int n_parts;
     int L, Lpad;
     long long u_offset, v_offset;
-    long long ut_offset; /* -1 unless the layer uses the single-kernel forward path (few input
-                            channels); then Ugw also holds the class transposed, filters fastest:
-                            Ugw[ut_offset + ((fh*(len_w+1)+fw)*Lt + l)*Kpad + k], zero for l >= L, k >= K */
-    int Lt;              /* L rounded up to even (0 if ut_offset is -1) */
 } dwm_class_t;
+
+/* The single-kernel forward path (layers with few input channels) reads its own copy of the
+ * transformed filter, kept in Ugw after the per-class layout above.  There, pieces of two and
+ * three taps of a dimension form one family that shares the four frequencies of F(2,3)
+ * (Sec. 3.2): a 2-tap piece is run as a 3-tap piece whose third tap is zero, so its fourth
+ * product vanishes and is dropped -- a three-multiplication F(2,2), as Table 3 counts it.
+ * One-tap pieces (two products, no transform) form the other family.  A "fused class" is a
+ * pair of families; its rows are (part, channel) pairs, grouped by (len_h, len_w) and padded
+ * to a multiple of four with rows of zeros.  Layout, filter k = 32*slice + 16*half + i:
+ *   Ugw[uf_offset + (((slice*n_freq_h*n_freq_w + fh*n_freq_w + fw)*rows + row)*16 + i)*2 + half]
+ * zero for k >= K, padding rows and frequencies a part does not have. */
+typedef struct {
+    int wide_h, wide_w;     /* 1: the family of 2- and 3-tap pieces, 0: one-tap pieces */
+    int n_freq_h, n_freq_w; /* 4 or 2 */
+    int first_row, rows;    /* rows of this class in the row numbering of dwm_plan_fused_row */
+    long long uf_offset;    /* floats from the start of Ugw */
+} dwm_fused_class_t;
+
+typedef struct {
+    int part;    /* index for dwm_plan_part */
+    int channel; /* input channel */
+    int real;    /* 0: padding row (zeros) */
+} dwm_fused_row_t;
 
 /*
  * Splitting, kernel side (Sec. 4.1: eq. 12 for the stride, eq. 8 for the size; the two
- * combined as its last paragraph says).  Host only; no GPU call is made.
+ * combined as its last paragraph says).  Where the single-kernel path applies, a phase's
+ * taps are cut 3,...,3,2,2 instead of 3,...,3,3,1 (the same number of multiplications), so
+ * that one-tap pieces only come from phases that hold a single tap.
+ * Host only; no GPU call is made.
  * Limits: at most 16 one-dimensional pieces per dimension (e.g. R <= 48 at stride 1),
  * N*TH*TW and every buffer's element count below 2^31.  Returns DWM_ERR_INVALID_ARG for
  * non-positive sizes, negative pad or an empty output, DWM_ERR_UNSUPPORTED beyond the limits.
@@ -114,6 +138,10 @@ DWM_API dwm_status_t dwm_plan_destroy(dwm_plan_t* plan);
 DWM_API dwm_status_t dwm_plan_info(const dwm_plan_t* plan, dwm_plan_info_t* info);
 DWM_API dwm_status_t dwm_plan_part(const dwm_plan_t* plan, int i, dwm_part_t* part);     /* i < n_parts   */
 DWM_API dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls);   /* i < n_classes */
+/* The single-kernel path's filter copy: counts (all 0 where the path does not apply), classes, rows. */
+DWM_API dwm_status_t dwm_plan_fused_info(const dwm_plan_t* plan, int* n_classes, int* n_rows, int* n_slices);
+DWM_API dwm_status_t dwm_plan_fused_class(const dwm_plan_t* plan, int i, dwm_fused_class_t* cls);
+DWM_API dwm_status_t dwm_plan_fused_row(const dwm_plan_t* plan, int row, dwm_fused_row_t* out);
 
 /* Bytes of the transformed filter Ugw and of the workspace (the transformed input V, plus
  * partial output tiles and arrival counters of the contraction's split tiles). */
@@ -126,7 +154,8 @@ DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size
 
 /* Pick a kernel variant for a stage; variant < 0 restores the planner's own choice.
  *   "contract": tile shape / chunk depth of the contraction kernel (ids in csrc/plan.hpp);
- *   "forward":  0 = input transform + contraction, 1 = single kernel (few input channels only);
+ *   "forward":  0 = input transform + contraction, 1 = single kernel (layers with few input channels
+ *               only; the planner's choice where it applies);
  *   "input":    0, 1 = gather form of the input transform (blocks-fast / rows-fast workgroup order),
  *               2, 3 = LDS-staged form (channel groups fastest / blocks fastest; refused when the
  *               rows one block of 64 tiles needs do not fit in LDS);

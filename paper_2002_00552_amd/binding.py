@@ -26,7 +26,8 @@ class dwm_plan_info_t(ctypes.Structure):
         ("T", ctypes.c_longlong), ("n_parts", ctypes.c_int), ("n_classes", ctypes.c_int),
         ("n_planes", ctypes.c_int), ("mults_per_tile", ctypes.c_longlong),
         ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double),
-        ("Kpad", ctypes.c_int), ("Tpad", ctypes.c_longlong), ("Vblock", ctypes.c_longlong)]
+        ("Kpad", ctypes.c_int), ("Tpad", ctypes.c_longlong), ("Vblock", ctypes.c_longlong),
+        ("forward_path", ctypes.c_int)]
 
 
 class dwm_part_t(ctypes.Structure):
@@ -36,8 +37,16 @@ class dwm_part_t(ctypes.Structure):
 
 class dwm_class_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("len_h", "len_w", "n_parts", "L", "Lpad")] + [
-        ("u_offset", ctypes.c_longlong), ("v_offset", ctypes.c_longlong), ("ut_offset", ctypes.c_longlong),
-        ("Lt", ctypes.c_int)]
+        ("u_offset", ctypes.c_longlong), ("v_offset", ctypes.c_longlong)]
+
+
+class dwm_fused_class_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("wide_h", "wide_w", "n_freq_h", "n_freq_w", "first_row", "rows")] + [
+        ("uf_offset", ctypes.c_longlong)]
+
+
+class dwm_fused_row_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("part", "channel", "real")]
 
 
 _P = ctypes.c_void_p
@@ -48,6 +57,9 @@ _SIGNATURES = {
     "dwm_plan_info": (_I, [_P, ctypes.POINTER(dwm_plan_info_t)]),
     "dwm_plan_part": (_I, [_P, _I, ctypes.POINTER(dwm_part_t)]),
     "dwm_plan_class": (_I, [_P, _I, ctypes.POINTER(dwm_class_t)]),
+    "dwm_plan_fused_info": (_I, [_P] + [ctypes.POINTER(_I)] * 3),
+    "dwm_plan_fused_class": (_I, [_P, _I, ctypes.POINTER(dwm_fused_class_t)]),
+    "dwm_plan_fused_row": (_I, [_P, _I, ctypes.POINTER(dwm_fused_row_t)]),
     "dwm_plan_filter_bytes": (ctypes.c_size_t, [_P]),
     "dwm_plan_workspace_bytes": (ctypes.c_size_t, [_P]),
     "dwm_plan_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
@@ -112,6 +124,25 @@ def dwm_plan_class(plan, i):
     cls = dwm_class_t()
     _check(lib().dwm_plan_class(plan, i, ctypes.byref(cls)), "dwm_plan_class")
     return cls
+
+
+def dwm_plan_fused_info(plan):
+    """(n_classes, n_rows, n_slices) of the single-kernel path's filter copy; zeros where it does not apply."""
+    a, b, c = _I(), _I(), _I()
+    _check(lib().dwm_plan_fused_info(plan, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "dwm_plan_fused_info")
+    return a.value, b.value, c.value
+
+
+def dwm_plan_fused_class(plan, i):
+    cls = dwm_fused_class_t()
+    _check(lib().dwm_plan_fused_class(plan, i, ctypes.byref(cls)), "dwm_plan_fused_class")
+    return cls
+
+
+def dwm_plan_fused_row(plan, row):
+    out = dwm_fused_row_t()
+    _check(lib().dwm_plan_fused_row(plan, row, ctypes.byref(out)), "dwm_plan_fused_row")
+    return out
 
 
 def dwm_plan_filter_bytes(plan):

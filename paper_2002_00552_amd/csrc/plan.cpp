@@ -17,17 +17,24 @@ long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
 // Split one kernel dimension of r taps at stride s into pieces, longest class first.
 // Within a phase the taps are cut 3,3,...,remainder from the low end (eq. 8; the number
 // of cuts is ceil(n/3)).  Returns the piece count or -1 if it exceeds kMaxPieces.
-int split_dimension(int r, int s, DevPiece* out, int start[4], int count[4])
+// `even_tail`: a remainder of one tap is avoided where the phase has more than one tap --
+// 3+1 becomes 2+2, which costs the same number of multiplications (4+2 = 3+3) -- so that
+// one-tap pieces, which cannot share frequencies with the others, only arise from phases
+// that hold a single tap.
+int split_dimension(int r, int s, bool even_tail, DevPiece* out, int start[4], int count[4])
 {
     DevPiece tmp[kMaxPieces];
     int n = 0;
     const int phases = s < r ? s : r;  // phases beyond the kernel length hold no tap
     for (int p = 0; p < phases; ++p) {
         const int taps = (r - p + s - 1) / s;
-        for (int j = 0; j < taps; j += 3) {
+        for (int j = 0; j < taps;) {
             if (n == kMaxPieces) return -1;
             const int rest = taps - j;
-            tmp[n++] = DevPiece{p, j, rest < 3 ? rest : 3};
+            int len = rest < 3 ? rest : 3;
+            if (even_tail && rest == 4) len = 2;
+            tmp[n++] = DevPiece{p, j, len};
+            j += len;
         }
     }
     int m = 0;
@@ -112,10 +119,10 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
 
 extern "C" {
 
-dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
-                             int stride, int pad)
+// One planning pass with the given splitting policy; *out is set on DWM_OK only.
+static dwm_status_t plan_build(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S, int stride,
+                               int pad, bool even_tail)
 {
-    if (!out) return DWM_ERR_INVALID_ARG;
     if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || pad < 0)
         return DWM_ERR_INVALID_ARG;
     if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return DWM_ERR_INVALID_ARG;
@@ -136,8 +143,8 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     const long long lim = (1LL << 31) - 1;
 
     int sh[4], ch[4], sw[4], cw[4];
-    d.nh = split_dimension(R, stride, d.ph, sh, ch);
-    d.nw = split_dimension(S, stride, d.pw, sw, cw);
+    d.nh = split_dimension(R, stride, even_tail, d.ph, sh, ch);
+    d.nw = split_dimension(S, stride, even_tail, d.pw, sw, cw);
     bool ok = d.nh > 0 && d.nw > 0 && Tpad < lim && (long long)N * K * d.OH * d.OW < lim &&
               (long long)N * C * H * W < lim && (long long)K * C * R * S < lim;
 
@@ -232,28 +239,42 @@ dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K
     in.winograd_flops = 2.0 * (double)mults * C * K * (double)T;
     in.Kpad = d.Kpad; in.Tpad = d.Tpad;
     in.Vblock = (long long)d.vblock_rows * 64;
-    p->fused_ok = dwm::fused_setup(*p, &p->fused);
+    // (the single-kernel path goes with the even-tail splitting only)
+    p->fused_ok = even_tail && dwm::fused_setup(*p, &p->fused);
     p->inlds_ok = dwm::input_lds_setup(*p, &p->inlds, 0);
     if (p->fused_ok) {
-        // the single-kernel path reads U transposed (filters fastest): a second copy after the first
-        long long ut = (long long)p->filter_floats;
-        d.has_ut = 1;
-        for (int i = 0; i < d.ncls; ++i) {
-            dwm::DevClass& q = d.cls[i];
-            q.Lt = (q.L + 1) & ~1;
-            q.ut_off = ut;
-            const int planes = (q.lh + 1) * (q.lw + 1);
-            for (int pl = 0; pl < planes; ++pl)
-                p->planes.e[q.plane0 + pl].ut_off64 = (uint32_t)((ut + (long long)pl * q.Lt * d.Kpad) / 64);
-            ut += (long long)planes * q.Lt * d.Kpad;
+        // the single-kernel path reads its own copy of the transformed filter (see FusedClass)
+        size_t uf = (p->filter_floats + 63) / 64 * 64;
+        p->uf_gap = p->filter_floats;
+        p->uf_begin = uf;
+        for (int i = 0; i < p->fused.nfc; ++i) {
+            dwm::FusedClass& fc = p->fused.fc[i];
+            fc.uf_off = (long long)uf;
+            uf += (size_t)p->fused.nslices * fc.nfh * fc.nfw * fc.rows * 32;
         }
-        // every plane is read a fixed number of rows deep: 32 rows of slack after the last one
-        p->ut_begin = p->filter_floats;
-        p->filter_floats = (size_t)ut + (size_t)32 * d.Kpad;
+        p->filter_floats = uf;
     }
     *out = p;
     return DWM_OK;
 }
+
+dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad)
+{
+    if (!out) return DWM_ERR_INVALID_ARG;
+    // The single-kernel path for layers with few input channels wants the splitting without
+    // one-tap remainders; every other layer is split three taps at a time as eq. 8 writes it.
+    dwm_plan_t* p = nullptr;
+    dwm_status_t st = plan_build(&p, N, C, H, W, K, R, S, stride, pad, true);
+    if (st == DWM_OK && !p->fused_ok) {
+        delete p;
+        p = nullptr;
+        st = plan_build(&p, N, C, H, W, K, R, S, stride, pad, false);
+    }
+    if (st == DWM_OK) *out = p;
+    return st;
+}
+
 
 dwm_status_t dwm_plan_destroy(dwm_plan_t* plan)
 {
@@ -266,6 +287,7 @@ dwm_status_t dwm_plan_info(const dwm_plan_t* plan, dwm_plan_info_t* info)
 {
     if (!plan || !info) return DWM_ERR_INVALID_ARG;
     *info = plan->info;
+    info->forward_path = plan->use_fused() ? 1 : 0;
     return DWM_OK;
 }
 
@@ -282,9 +304,44 @@ dwm_status_t dwm_plan_class(const dwm_plan_t* plan, int i, dwm_class_t* cls)
     const dwm::DevClass& q = plan->d.cls[i];
     cls->len_h = q.lh; cls->len_w = q.lw; cls->n_parts = q.hn * q.wn;
     cls->L = q.L; cls->Lpad = q.Lpad; cls->u_offset = q.u_off; cls->v_offset = (long long)q.v_row0 * 64;
-    cls->ut_offset = plan->d.has_ut ? q.ut_off : -1;
-    cls->Lt = plan->d.has_ut ? q.Lt : 0;
     return DWM_OK;
+}
+
+dwm_status_t dwm_plan_fused_info(const dwm_plan_t* plan, int* n_classes, int* n_rows, int* n_slices)
+{
+    if (!plan || !n_classes || !n_rows || !n_slices) return DWM_ERR_INVALID_ARG;
+    *n_classes = plan->fused_ok ? plan->fused.nfc : 0;
+    *n_rows = plan->fused_ok ? plan->fused.rows_total : 0;
+    *n_slices = plan->fused_ok ? plan->fused.nslices : 0;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_fused_class(const dwm_plan_t* plan, int i, dwm_fused_class_t* cls)
+{
+    if (!plan || !cls || !plan->fused_ok || i < 0 || i >= plan->fused.nfc) return DWM_ERR_INVALID_ARG;
+    const dwm::FusedClass& fc = plan->fused.fc[i];
+    cls->wide_h = fc.wide_h; cls->wide_w = fc.wide_w;
+    cls->n_freq_h = fc.nfh; cls->n_freq_w = fc.nfw;
+    cls->first_row = fc.row0; cls->rows = fc.rows;
+    cls->uf_offset = fc.uf_off;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_plan_fused_row(const dwm_plan_t* plan, int row, dwm_fused_row_t* out)
+{
+    if (!plan || !out || !plan->fused_ok || row < 0 || row >= plan->fused.rows_total) return DWM_ERR_INVALID_ARG;
+    const unsigned desc = plan->fused.rowdesc[row];
+    const dwm::DevPiece hp = plan->d.ph[desc & 15], wp = plan->d.pw[(desc >> 4) & 15];
+    out->channel = (int)((desc >> 8) & 127);
+    out->real = (int)(desc >> 15);
+    out->part = -1;
+    for (int i = 0; i < plan->info.n_parts; ++i) {
+        const dwm_part_t& pt = plan->parts[i];
+        if (pt.phase_h == hp.p && pt.off_h == hp.j && pt.len_h == hp.l && pt.phase_w == wp.p &&
+            pt.off_w == wp.j && pt.len_w == wp.l)
+            out->part = i;
+    }
+    return out->part >= 0 ? DWM_OK : DWM_ERR_INVALID_ARG;
 }
 
 size_t dwm_plan_filter_bytes(const dwm_plan_t* plan) { return plan ? plan->filter_floats * sizeof(float) : 0; }
@@ -342,7 +399,9 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
 dwm_status_t dwm_filter_transform(const dwm_plan_t* plan, const float* w_dev, float* Ugw_dev, void* stream)
 {
     if (!plan || !w_dev || !Ugw_dev) return DWM_ERR_INVALID_ARG;
-    return dwm::launch_filter_transform(*plan, w_dev, Ugw_dev, stream);
+    const dwm_status_t st = dwm::launch_filter_transform(*plan, w_dev, Ugw_dev, stream);
+    if (st != DWM_OK || !plan->fused_ok) return st;
+    return dwm::launch_fused_filter(*plan, w_dev, Ugw_dev, stream);
 }
 
 dwm_status_t dwm_input_transform(const dwm_plan_t* plan, const float* x_dev, void* stream)

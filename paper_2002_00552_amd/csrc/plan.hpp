@@ -33,9 +33,6 @@ struct DevClass {
     long long u_off;         // floats
     int v_row0;              // first row of the class inside a V block (a row = 64 tiles)
     int pad2_;
-    long long ut_off;        // floats; transposed copy UT[plane][Lt][Kpad] (only if DevPlan::has_ut)
-    int Lt;                  // L rounded up to even
-    int pad_;
 };
 
 struct DevPlan {
@@ -46,7 +43,6 @@ struct DevPlan {
     int ncls;
     int rows_total;  // sum over classes of Lpad
     int vblock_rows; // rows of one V block = sum over planes of Lpad
-    int has_ut;      // the filter transform also writes the transposed copy (single-kernel path)
     DevPiece ph[kMaxPieces];
     DevPiece pw[kMaxPieces];
     DevClass cls[kMaxClasses];
@@ -58,7 +54,6 @@ struct DevPlan {
 struct DevPlaneEntry {
     uint32_t u_off64;  // offset into Ugw in units of 64 floats
     uint32_t v_off64;  // first row of the plane inside a V block (= offset in units of 64 floats)
-    uint32_t ut_off64; // offset of the transposed copy UT_p[Lt][Kpad] in units of 64 floats
     int32_t Lpad;
     int32_t coef;      // bits [2q+1:2q] of output q=2a+b: 0 -> 0, 1 -> +1, 3 -> -1
 };
@@ -119,20 +114,34 @@ struct FastDiv {
 #endif
 };
 
-// Geometry of the single-kernel forward path for layers whose whole input footprint of a
-// block of output tiles, all channels, fits in LDS (small C): see fused.hip.
+// Geometry of the single-kernel forward path (fused.hip).  A wave owns 16
+// tiles and 32 filters at a time; the pieces of 2 and 3 taps of a dimension form one family
+// that shares the four F(2,3) frequencies (a 2-tap piece is a 3-tap piece whose last tap is
+// zero: its fourth frequency vanishes and is skipped), one-tap pieces form the other.  A
+// "class" here is a pair of families; its parts are ordered by (len_h, len_w) in groups whose
+// rows (part, channel) are padded to a multiple of four, the reduction depth of one MFMA step.
+constexpr int kFusedMaxSteps = 64;
+constexpr int kFusedMaxRows = 4 * kFusedMaxSteps;
+struct FusedClass {
+    int wide_h, wide_w;  // 1: pieces of 2 or 3 taps (four frequencies), 0: one-tap pieces (two)
+    int nfh, nfw;        // frequencies per dimension: 4 or 2
+    int step0, nsteps;   // steps of four rows
+    int row0, rows;      // first row, rows (a multiple of 4)
+    long long uf_off;    // floats from the start of Ugw: UF[slice][plane][row][16 filters][2 halves]
+};
 struct FusedArgs {
-    int BH, BW, nbh, nbw;  // block of tiles owned by a workgroup (BH*BW <= 64), blocks per image
-    int wgm;               // K blocks of 32 per workgroup (1..4)
-    int nkt;               // workgroups along K
+    int BH, BW, nbh, nbw;           // block of tiles owned by a workgroup (BH*BW <= 64), blocks per image
     int nphase, lwp, lw_in, nrows;  // staged input region: 2*stride phases, floats per (row, phase), columns, rows
     int row_floats, chan_floats;    // LDS floats per staged row / per channel
     int tile_row_step;              // LDS floats between vertically adjacent tiles' patches
-    int vrows;                      // rows of one V plane buffer in LDS (even, >= every class's L)
-    int rows_all;                   // sum over classes of Lt; row0[i] = first row of class i
-    int row0[kMaxClasses];
-    FastDiv div_bw, div_nphase, div_c;
+    int nslices;                    // ceil(K / 32)
+    int slices_per_wg, nkw;         // K slices per workgroup, workgroups along K
+    int nfc, rows_total;
+    FusedClass fc[4];
+    FastDiv div_bw, div_nphase;
     int roff[kMaxPieces][4], coff[kMaxPieces][4];  // LDS offset of patch row a / column b of a piece
+    int step_type[kFusedMaxSteps];                    // len_h * 4 + len_w of the step's four rows
+    unsigned short rowdesc[kFusedMaxRows];            // h piece | w piece << 4 | channel << 8 | real row << 15
     size_t lds_bytes;
 };
 
@@ -159,16 +168,16 @@ struct dwm_plan {
     dwm_plan_info_t info;
     dwm_part_t parts[dwm::kMaxPieces * dwm::kMaxPieces];
     size_t filter_floats, v_floats;
-    size_t ut_begin;  // first float of the transposed copy in Ugw (single-kernel path only)
     dwm::ContractGeometry geo;
     float* ws;
     size_t ws_bytes;
     int lgran;  // every class's Lpad is a multiple of this (16, 32 or 64)
     int variant_input;  // < 0: planner's choice
     int sk_mode;        // how leftover tiles are split (see contract_geometry)
-    bool fused_ok;      // the single-kernel path applies to this layer
-    int variant_forward;  // < 0: planner's choice (fused when it applies), 0: staged, 1: fused
+    int variant_forward;  // < 0: planner's choice (single kernel where it applies), 0: staged, 1: single kernel
+    bool fused_ok;        // the single-kernel path applies to this layer
     dwm::FusedArgs fused;
+    size_t uf_gap, uf_begin;  // end of what precedes its filter copy in Ugw, first float of the copy
     bool inlds_ok;      // the LDS-staged input transform applies (its staged rows fit in LDS)
     dwm::InLdsArgs inlds;
     bool use_fused() const { return fused_ok && variant_forward != 0; }
@@ -190,5 +199,6 @@ dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const flo
 bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish);
 // fused.hip
 bool fused_setup(const dwm_plan& p, FusedArgs* out);
+dwm_status_t launch_fused_filter(const dwm_plan& p, const float* w, float* U, void* stream);
 dwm_status_t launch_fused_forward(const dwm_plan& p, const float* x, const float* U, float* y, void* stream);
 }  // namespace dwm

@@ -110,8 +110,6 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(DevPlan P, const 
         for (int j = 0; j < 4; ++j)
             if (i < th && j < tw) {
                 U[(size_t)q.u_off + ((size_t)(i * tw + j) * P.Kpad + k) * q.Lpad + l] = u[i][j];
-                if (P.has_ut && l < q.Lt)
-                    U[(size_t)q.ut_off + ((size_t)(i * tw + j) * q.Lt + l) * P.Kpad + k] = u[i][j];
             }
 }
 
@@ -414,20 +412,10 @@ static dwm_status_t check_launch()
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }
 
-__global__ __launch_bounds__(256) void zero_fill_kernel(float* __restrict__ p, size_t n)
-{
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.f;
-}
-
 dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U, void* stream)
 {
     dim3 grid((p.d.rows_total + 255) / 256, p.d.Kpad), block(256);
     hipLaunchKernelGGL(filter_transform_kernel, grid, block, 0, (hipStream_t)stream, p.d, w, U);
-    if (p.d.has_ut) {  // the slack rows after the transposed copy (read, never used)
-        const size_t slack = (size_t)32 * p.d.Kpad;
-        hipLaunchKernelGGL(zero_fill_kernel, dim3(32), block, 0, (hipStream_t)stream,
-                           U + p.filter_floats - slack, slack);
-    }
     return check_launch();
 }
 

@@ -68,11 +68,31 @@ def test_filter_transform_matches_oracle(shape):
         assert np.max(np.abs(got - ref)) <= 1e-6 * max(np.max(np.abs(ref)), 1e-30)
         # padding rows/columns are zero
         assert np.all(Ug[:, :, K:, :] == 0) and np.all(Ug[:, :, :, q.L:] == 0)
-        if q.ut_offset >= 0:  # the transposed copy the single-kernel path reads
-            UT = U[q.ut_offset:q.ut_offset + th * tw * q.Lt * Kpad].reshape(th, tw, q.Lt, Kpad)
-            got_t = UT[:, :, pt.slot * C:(pt.slot + 1) * C, :K].transpose(3, 2, 0, 1)
-            assert np.array_equal(got_t, got)
-            assert np.all(UT[:, :, q.L:, :] == 0) and np.all(UT[:, :, :, K:] == 0)
+    # the single-kernel path's copy: (part, channel) rows with the F(2,2) form that shares the
+    # frequencies of F(2,3) (the oracle's form 1)
+    nfc, nrows, nslices = dwm.dwm_plan_fused_info(r.plan)
+    if nfc:
+        oracle.set_f22_form(1)
+        try:
+            parts = r.parts()
+            refs = [oracle.part_filter_transform(w, s, _part_tuple(pt)) for pt in parts]  # [K][C][th][tw]
+        finally:
+            oracle.set_f22_form(0)
+        scale = max(np.max(np.abs(u)) for u in refs)
+        for i in range(nfc):
+            fq = dwm.dwm_plan_fused_class(r.plan, i)
+            n = nslices * fq.n_freq_h * fq.n_freq_w * fq.rows * 32
+            UF = U[fq.uf_offset:fq.uf_offset + n].reshape(nslices, fq.n_freq_h, fq.n_freq_w, fq.rows, 16, 2)
+            # filter index = 32*slice + 16*half + i  ->  [fh][fw][row][filter]
+            UF = UF.transpose(1, 2, 3, 0, 5, 4).reshape(fq.n_freq_h, fq.n_freq_w, fq.rows, nslices * 32)
+            assert np.all(UF[:, :, :, K:] == 0)
+            for j in range(fq.rows):
+                row = dwm.dwm_plan_fused_row(r.plan, fq.first_row + j)
+                pt = parts[row.part]
+                want = np.zeros((fq.n_freq_h, fq.n_freq_w, K))
+                if row.real:
+                    want[:pt.len_h + 1, :pt.len_w + 1, :] = refs[row.part][:, row.channel].transpose(1, 2, 0)
+                assert np.max(np.abs(UF[:, :, j, :K] - want)) <= 1e-6 * scale, (i, j)
     r.close()
 
 

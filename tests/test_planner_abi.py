@@ -86,14 +86,36 @@ def test_taps_partition_and_layout(R, S, s):
     # V comes first in the workspace; partial tiles and counters of the contraction follow
     assert info.Vblock == v_end and info.Tpad % 64 == 0
     assert dwm.dwm_plan_workspace_bytes(p) >= 4 * info.Vblock * (info.Tpad // 64)
-    if classes[0].ut_offset < 0:
+    # the single-kernel path's filter copy follows (few input channels: it applies here)
+    nfc, nrows, nslices = dwm.dwm_plan_fused_info(p)
+    if nfc == 0:
         assert dwm.dwm_plan_filter_bytes(p) == 4 * u_end
-    else:  # few input channels: a transposed copy of every class follows, then slack rows
-        ut_end = u_end
-        for q in classes:
-            assert q.ut_offset == ut_end and q.Lt == q.L + (q.L & 1)
-            ut_end += (q.len_h + 1) * (q.len_w + 1) * q.Lt * info.Kpad
-        assert dwm.dwm_plan_filter_bytes(p) >= 4 * ut_end
+    else:
+        assert nslices == (K + 31) // 32
+        uf_end, row_end, seen = u_end, 0, set()
+        for i in range(nfc):
+            fq = dwm.dwm_plan_fused_class(p, i)
+            assert fq.uf_offset >= uf_end and fq.uf_offset % 2 == 0 and fq.rows % 4 == 0
+            assert fq.first_row == row_end and (fq.n_freq_h, fq.n_freq_w) == (4 if fq.wide_h else 2, 4 if fq.wide_w else 2)
+            for r in range(fq.first_row, fq.first_row + fq.rows):
+                row = dwm.dwm_plan_fused_row(p, r)
+                pt = dwm.dwm_plan_part(p, row.part)
+                assert (pt.len_h >= 2) == bool(fq.wide_h) and (pt.len_w >= 2) == bool(fq.wide_w)
+                assert 0 <= row.channel < C
+                if row.real:
+                    assert (row.part, row.channel) not in seen
+                    seen.add((row.part, row.channel))
+            row_end += fq.rows
+            uf_end = fq.uf_offset + nslices * fq.n_freq_h * fq.n_freq_w * fq.rows * 32
+        assert row_end == nrows and len(seen) == info.n_parts * C  # every (part, channel) exactly once
+        assert dwm.dwm_plan_filter_bytes(p) == 4 * uf_end
+        # with this path, one-tap pieces only come from phases that hold a single tap
+        for i in range(info.n_parts):
+            pt = dwm.dwm_plan_part(p, i)
+            if pt.len_h == 1:
+                assert pt.off_h == 0 and s * 1 + pt.phase_h >= R
+            if pt.len_w == 1:
+                assert pt.off_w == 0 and s * 1 + pt.phase_w >= S
     assert info.Kpad >= K and info.Tpad >= info.T == 2 * info.TH * info.TW
     dwm.dwm_plan_destroy(p)
 
