@@ -31,7 +31,11 @@ PEAK_HBM = 8000.0      # GB/s
 # counter reads for the copy probe of known size (factors 2.00 and 1.00); see profiles/.
 TRAFFIC = {
     ("cfg2_3x3s2_c128k256_56", "contract_kernel"): 332.9e6,
-    ("cfg2_3x3s2_c128k256_56", "input_transform_kernel"): 232.5e6,
+    ("cfg2_3x3s2_c128k256_56", "input_transform_kernel"): 132.3e6,
+    ("cfg3_7x7s1_c256k256_28", "contract_kernel"): 2.473e9,
+    ("cfg3_7x7s1_c256k256_28", "input_transform_kernel"): 672.2e6,
+    ("cfg4_7x7s2_c3k64_224", "fused_forward_kernel"): 326.9e6,
+    ("cfg5_11x11s4_c3k96_227", "fused_forward_kernel"): 328.4e6,
 }
 
 
@@ -72,7 +76,7 @@ def main():
     ap.add_argument("--input-variant", type=int, default=-1)
     ap.add_argument("--split-mode", type=int, default=-1)
     ap.add_argument("--input-cg", type=int, default=-1)
-    ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 / 2 single kernels, -1 planner")
+    ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -139,7 +143,7 @@ def main():
     # stream the kernels run on (torch's current stream is the one handed to the library).
     path = dwm.dwm_plan_info(plan).forward_path
     fused = path != 0
-    kname = {1: "fused_forward_kernel", 2: "f2_forward_kernel"}.get(path)
+    kname = {1: "fused_forward_kernel"}.get(path)
     v_bytes = 4.0 * info.mults_per_tile * L.C * info.T
     x_bytes, y_bytes = 4.0 * x.size, 4.0 * y.numel()
     e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -202,8 +206,7 @@ def main():
                    "mults_per_tile": info.mults_per_tile, "direct_GFLOP": info.direct_flops / 1e9,
                    "winograd_GFLOP": info.winograd_flops / 1e9},
         "roofline": roofline, "stages": stages,
-        "path": ["input transform + contraction", "single kernel (V staged in LDS)",
-                 "single kernel (V in registers)"][path],
+        "path": ["input transform + contraction", "single kernel (V in registers)"][path],
     }
 
     if not args.no_check:

@@ -33,6 +33,7 @@ struct ContractArgs {
     int OH, OW, TH, TW;
     int vblock;  // floats of one 64-tile block of V
     ContractGeometry g;
+    OutMap om;   // used by the MAPPED instantiation only
 };
 
 // XOR pattern of U-tile row i: which 16-byte column group sits in which slot, chosen so
@@ -45,7 +46,9 @@ __device__ __forceinline__ int a_swizzle(int i)
     return i & 15;  // LC == 64
 }
 
-template <int WGM, int WGN, int WM, int WN, int LC, int NS>
+// MAPPED: outputs go through ContractArgs::om (strided / offset destination, used by the data
+// gradient); otherwise y is the dense [N][K][OH][OW] of the forward convolution.
+template <int WGM, int WGN, int WM, int WN, int LC, int NS, bool MAPPED>
 __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kernel(
     ContractArgs A, PlaneTable PT, const float* __restrict__ U, const float* __restrict__ V,
     float* __restrict__ y, float* __restrict__ partial, int* __restrict__ counters)
@@ -256,9 +259,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                 for (int e = 0; e < 16; ++e) {
                     const int k = kt * KT + wave_m * 32 * WM + mi * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
                     if (k >= A.K) continue;
-                    float* yp = y + (((size_t)n * A.K + k) * A.OH + oh) * A.OW + ow;
                     const float y00 = Y[mi][nj][0][e], y01 = Y[mi][nj][1][e];
                     const float y10 = Y[mi][nj][2][e], y11 = Y[mi][nj][3][e];
+                    if (MAPPED) {
+                        store_tile(y, A.om, A.OH, A.OW, (size_t)n * A.K + k, oh, ow, y00, y01, y10, y11);
+                        continue;
+                    }
+                    float* yp = y + (((size_t)n * A.K + k) * A.OH + oh) * A.OW + ow;
                     if (pair_ok) {
                         *reinterpret_cast<float2*>(yp) = make_float2(y00, y01);
                         if (oh + 1 < A.OH) *reinterpret_cast<float2*>(yp + A.OW) = make_float2(y10, y11);
@@ -375,14 +382,20 @@ static dwm_status_t launch_variant(const dwm_plan& p, const float* U, const floa
         return DWM_ERR_INVALID_ARG;
     const long long blocks = (long long)a.g.n_full + a.g.sk_wgs;
     constexpr int lds_bytes = NS * (KT + TT) * LC * 4;
-    auto kernel = contract_kernel<WGM, WGN, WM, WN, LC, NS>;
+    const OutMap& m = p.d.om;
+    a.om = m;
+    const bool dense = m.sy == 1 && m.sx == 1 && m.oy == 0 && m.ox == 0 && m.YH == p.d.OH && m.YW == p.d.OW;
+    auto kd = contract_kernel<WGM, WGN, WM, WN, LC, NS, false>;
+    auto km = contract_kernel<WGM, WGN, WM, WN, LC, NS, true>;
     if (lds_bytes > 64 * 1024) {
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (attr != hipSuccess) return DWM_ERR_HIP;
+        static const hipError_t attr_d = hipFuncSetAttribute(reinterpret_cast<const void*>(kd),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        static const hipError_t attr_m = hipFuncSetAttribute(reinterpret_cast<const void*>(km),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (attr_d != hipSuccess || attr_m != hipSuccess) return DWM_ERR_HIP;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * WGM * WGN), lds_bytes, (hipStream_t)stream, a,
-                       p.planes, U, V, y, p.sk_partial(), p.sk_counters());
+    hipLaunchKernelGGL(dense ? kd : km, dim3((unsigned)blocks), dim3(64 * WGM * WGN), lds_bytes, (hipStream_t)stream,
+                       a, p.planes, U, V, y, p.sk_partial(), p.sk_counters());
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }
 

@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void fused_forward_kernel(DevPlan P, FusedA
     // ---- 1. stage the block's input region (padded coordinates).  A unit is (channel, 8 rows);
     // a wave issues the loads of up to four units before it writes any of them to LDS. ----
     {
-        const int prow0 = 2 * ty0 * P.s - P.P, pcol0 = 2 * tx0 * P.s - P.P;
+        const int prow0 = 2 * ty0 * P.s - P.Ph, pcol0 = 2 * tx0 * P.s - P.Pw;
         const float* xn = x + (size_t)n * P.C * P.H * P.W;
         const int nb8 = (F.nrows + 7) >> 3, units = P.C * nb8;
         for (int cb = 0; cb < F.lw_in; cb += 64) {
@@ -395,27 +395,14 @@ __global__ __launch_bounds__(256, 2) void fused_forward_kernel(DevPlan P, FusedA
         // ---- scatter: lane (ln, lq) holds tile ln and filters 32*ks + 16*half + 4*lq + r ----
         if (tile_ok) {
             const int oh = 2 * ty, ow = 2 * tx;
-            const bool pair_ok = (P.OW & 1) == 0;
 #pragma unroll
             for (int half = 0; half < 2; ++half)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int k = ks * 32 + half * 16 + lq * 4 + r;
                     if (k >= P.K) continue;
-                    float* yp = y + (((size_t)n * P.K + k) * P.OH + oh) * P.OW + ow;
-                    const float y00 = Y[0][0][half][r], y01 = Y[0][1][half][r];
-                    const float y10 = Y[1][0][half][r], y11 = Y[1][1][half][r];
-                    if (pair_ok) {
-                        *reinterpret_cast<float2*>(yp) = make_float2(y00, y01);
-                        if (oh + 1 < P.OH) *reinterpret_cast<float2*>(yp + P.OW) = make_float2(y10, y11);
-                    } else {
-                        yp[0] = y00;
-                        if (ow + 1 < P.OW) yp[1] = y01;
-                        if (oh + 1 < P.OH) {
-                            yp[P.OW] = y10;
-                            if (ow + 1 < P.OW) yp[P.OW + 1] = y11;
-                        }
-                    }
+                    store_tile(y, P.om, P.OH, P.OW, (size_t)n * P.K + k, oh, ow, Y[0][0][half][r], Y[0][1][half][r],
+                               Y[1][0][half][r], Y[1][1][half][r]);
                 }
         }
     }

@@ -120,21 +120,24 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
 extern "C" {
 
 // One planning pass with the given splitting policy; *out is set on DWM_OK only.
-static dwm_status_t plan_build(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S, int stride,
-                               int pad, bool even_tail)
+static dwm_status_t plan_build(dwm_plan_t** out, const dwm::PlanSpec& sp, bool even_tail)
 {
-    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || pad < 0)
+    const int N = sp.N, C = sp.C, H = sp.H, W = sp.W, K = sp.K, R = sp.R, S = sp.S, stride = sp.stride;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || sp.OH < 1 || sp.OW < 1)
         return DWM_ERR_INVALID_ARG;
-    if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return DWM_ERR_INVALID_ARG;
-    if (pad > (1 << 20) || H > (1 << 20) || W > (1 << 20)) return DWM_ERR_UNSUPPORTED;
+    const int lim20 = 1 << 20;
+    if (sp.pad_h > lim20 || sp.pad_h < -lim20 || sp.pad_w > lim20 || sp.pad_w < -lim20 || H > lim20 || W > lim20 ||
+        sp.OH > lim20 || sp.OW > lim20 || stride > lim20 || R > lim20 || S > lim20)
+        return DWM_ERR_UNSUPPORTED;
 
     dwm_plan* p = new (std::nothrow) dwm_plan;
     if (!p) return DWM_ERR_ALLOC;
     std::memset(p, 0, sizeof(*p));
     DevPlan& d = p->d;
-    d.N = N; d.C = C; d.H = H; d.W = W; d.K = K; d.R = R; d.S = S; d.s = stride; d.P = pad;
-    d.OH = (H + 2 * pad - R) / stride + 1;
-    d.OW = (W + 2 * pad - S) / stride + 1;
+    d.N = N; d.C = C; d.H = H; d.W = W; d.K = K; d.R = R; d.S = S; d.s = stride;
+    d.Ph = sp.pad_h; d.Pw = sp.pad_w;
+    d.OH = sp.OH; d.OW = sp.OW;
+    d.om = sp.om;
     d.TH = (d.OH + 1) / 2;
     d.TW = (d.OW + 1) / 2;
     const long long T = (long long)N * d.TH * d.TW;
@@ -145,7 +148,7 @@ static dwm_status_t plan_build(dwm_plan_t** out, int N, int C, int H, int W, int
     int sh[4], ch[4], sw[4], cw[4];
     d.nh = split_dimension(R, stride, even_tail, d.ph, sh, ch);
     d.nw = split_dimension(S, stride, even_tail, d.pw, sw, cw);
-    bool ok = d.nh > 0 && d.nw > 0 && Tpad < lim && (long long)N * K * d.OH * d.OW < lim &&
+    bool ok = d.nh > 0 && d.nw > 0 && Tpad < lim && (long long)N * K * d.om.YH * d.om.YW < lim && (long long)N * K * d.OH * d.OW < lim &&
               (long long)N * C * H * W < lim && (long long)K * C * R * S < lim;
 
     // Reduction granularity: the largest of 64/32/16 that costs at most 5 % more padded
@@ -231,7 +234,7 @@ static dwm_status_t plan_build(dwm_plan_t** out, int N, int C, int H, int W, int
     }
 
     dwm_plan_info_t& in = p->info;
-    in.N = N; in.C = C; in.H = H; in.W = W; in.K = K; in.R = R; in.S = S; in.stride = stride; in.pad = pad;
+    in.N = N; in.C = C; in.H = H; in.W = W; in.K = K; in.R = R; in.S = S; in.stride = stride; in.pad = sp.pad_h;
     in.OH = d.OH; in.OW = d.OW; in.TH = d.TH; in.TW = d.TW; in.T = T;
     in.n_parts = n_parts; in.n_classes = d.ncls; in.n_planes = p->planes.n;
     in.mults_per_tile = mults;
@@ -258,23 +261,43 @@ static dwm_status_t plan_build(dwm_plan_t** out, int N, int C, int H, int W, int
     return DWM_OK;
 }
 
-dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
-                             int stride, int pad)
+}  // extern "C"
+
+namespace dwm {
+// The single-kernel path for layers with few input channels wants the splitting without
+// one-tap remainders; every other layer is split three taps at a time as eq. 8 writes it.
+dwm_status_t plan_from_spec(dwm_plan_t** out, const PlanSpec& sp)
 {
-    if (!out) return DWM_ERR_INVALID_ARG;
-    // The single-kernel path for layers with few input channels wants the splitting without
-    // one-tap remainders; every other layer is split three taps at a time as eq. 8 writes it.
     dwm_plan_t* p = nullptr;
-    dwm_status_t st = plan_build(&p, N, C, H, W, K, R, S, stride, pad, true);
+    dwm_status_t st = plan_build(&p, sp, true);
     if (st == DWM_OK && !p->fused_ok) {
         delete p;
         p = nullptr;
-        st = plan_build(&p, N, C, H, W, K, R, S, stride, pad, false);
+        st = plan_build(&p, sp, false);
     }
     if (st == DWM_OK) *out = p;
     return st;
 }
+}  // namespace dwm
 
+extern "C" {
+
+dwm_status_t dwm_plan_create(dwm_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                             int stride, int pad)
+{
+    if (!out) return DWM_ERR_INVALID_ARG;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return DWM_ERR_INVALID_ARG;
+    if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return DWM_ERR_INVALID_ARG;
+    if (pad > (1 << 20) || H > (1 << 20) || W > (1 << 20)) return DWM_ERR_UNSUPPORTED;
+    dwm::PlanSpec sp{};
+    sp.N = N; sp.C = C; sp.H = H; sp.W = W; sp.K = K; sp.R = R; sp.S = S; sp.stride = stride;
+    sp.pad_h = sp.pad_w = pad;
+    sp.OH = (H + 2 * pad - R) / stride + 1;
+    sp.OW = (W + 2 * pad - S) / stride + 1;
+    sp.om = dwm::OutMap{sp.OH, sp.OW, 1, 0, 1, 0};
+    return dwm::plan_from_spec(out, sp);
+}
 
 dwm_status_t dwm_plan_destroy(dwm_plan_t* plan)
 {

@@ -35,9 +35,20 @@ struct DevClass {
     int pad2_;
 };
 
+// Where output pixel (oh, ow) of image n and filter k is written: element
+// ((n*K + k)*YH + sy*oh + oy)*YW + sx*ow + ox of the destination.  The forward convolution
+// writes densely (YH = OH, YW = OW, steps 1, offsets 0); the data gradient interleaves the
+// outputs of its stride-1 sub-convolutions (one per input phase) into the gradient image.
+struct OutMap {
+    int YH, YW;
+    int sy, oy, sx, ox;
+};
+
 struct DevPlan {
-    int N, C, H, W, K, R, S, s, P;
+    int N, C, H, W, K, R, S, s;
+    int Ph, Pw;  // the padded input starts Ph rows above and Pw columns left of the image (may be negative)
     int OH, OW, TH, TW;
+    OutMap om;
     int T, Tpad, Kpad;
     int nh, nw;
     int ncls;
@@ -96,6 +107,28 @@ struct ContractGeometry {
     int sk_maxc;     // partial-output slots per shared tile
     size_t partial_floats;
 };
+
+#ifdef __HIPCC__
+// One 2x2 output tile through the output map; rows/columns past the output extent are dropped.
+__device__ __forceinline__ void store_tile(float* __restrict__ y, const OutMap& M, int OH, int OW, size_t plane,
+                                           int oh, int ow, float y00, float y01, float y10, float y11)
+{
+    float* yp = y + (plane * M.YH + (size_t)(M.sy * oh + M.oy)) * M.YW + (M.sx * ow + M.ox);
+    const bool pair_ok = M.sx == 1 && ((M.YW | M.ox | OW) & 1) == 0;
+    const size_t row = (size_t)M.sy * M.YW;
+    if (pair_ok) {
+        *reinterpret_cast<float2*>(yp) = make_float2(y00, y01);
+        if (oh + 1 < OH) *reinterpret_cast<float2*>(yp + row) = make_float2(y10, y11);
+    } else {
+        yp[0] = y00;
+        if (ow + 1 < OW) yp[M.sx] = y01;
+        if (oh + 1 < OH) {
+            yp[row] = y10;
+            if (ow + 1 < OW) yp[row + M.sx] = y11;
+        }
+    }
+}
+#endif
 
 // exact floor(n / d) for 0 <= n < 2^31, d >= 1, without a division
 struct FastDiv {
@@ -190,6 +223,15 @@ struct dwm_plan {
 };
 
 namespace dwm {
+// What a plan is made from: the layer, where the padded input starts relative to the image,
+// the output extent to compute and where the outputs go.
+struct PlanSpec {
+    int N, C, H, W, K, R, S, stride;
+    int pad_h, pad_w;
+    int OH, OW;
+    OutMap om;
+};
+dwm_status_t plan_from_spec(dwm_plan_t** out, const PlanSpec& sp);
 // plan.cpp: geometry of a contraction variant for this plan; false if the variant does not apply
 bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out);
 // transforms.hip, contract.hip

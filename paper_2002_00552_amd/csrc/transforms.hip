@@ -146,10 +146,10 @@ __device__ __forceinline__ void input_rows4(const DevPlan& P, const DevClass& q,
         const float* xc = x + ((size_t)n * P.C + c) * P.H * P.W;
 #pragma unroll
         for (int i = 0; i < TH_; ++i) {
-            const int ih = P.s * (2 * ty + hp.j + i) + hp.p - P.P;
+            const int ih = P.s * (2 * ty + hp.j + i) + hp.p - P.Ph;
 #pragma unroll
             for (int j = 0; j < TW_; ++j) {
-                const int iw = P.s * (2 * tx + wp.j + j) + wp.p - P.P;
+                const int iw = P.s * (2 * tx + wp.j + j) + wp.p - P.Pw;
                 d[r][i][j] = (ok && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W) ? xc[(size_t)ih * P.W + iw] : 0.f;
             }
         }
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InL
         const float* xc = x + ((size_t)n0 * P.C + c0 + cl) * P.H * P.W;
         float* xsc = xs + cl * A.chan_floats;
         for (int cb = 0; cb < A.lw_in; cb += 64) {
-            const int col = cb + lane, iw = col - P.P;
+            const int col = cb + lane, iw = col - P.Pw;
             const bool iw_ok = iw >= 0 && iw < P.W;
             const unsigned voff = (unsigned)min(max(iw, 0), P.W - 1) * 4u;
             const int idx = A.div_nphase.div(col);
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InL
             if (col < A.lw_in) {
                 for (int k = 0; k <= n1 - n0; ++k) {
                     const int ty_a = k == 0 ? ty_a0 : 0, ty_b = n0 + k == n1 ? ty_b1 : P.TH - 1;
-                    const int nrows = s2 * (ty_b - ty_a) + A.foot_h, ih0 = s2 * ty_a - P.P;
+                    const int nrows = s2 * (ty_b - ty_a) + A.foot_h, ih0 = s2 * ty_a - P.Ph;
                     const int r_lo = min(max(-ih0, 0), nrows), r_hi = max(min(P.H - ih0, nrows), r_lo);
                     for (int r = 0; r < r_lo; ++r) xd[r * A.row_floats] = 0.f;
                     for (int r = r_hi; r < nrows; ++r) xd[r * A.row_floats] = 0.f;
