@@ -9,6 +9,8 @@ compiles it with gcc on first use and exposes thin numpy wrappers:
 * ``direct_f64``            O1, the definition of the convolution (ground truth)
 * ``direct_f64_at``         O1 at sampled output positions
 * ``dwm_f64``               O2, the paper's five steps in FP64
+* ``backward_data_f64``     O1', the gradient with respect to the input, by definition
+* ``dwm_backward_data_f64`` O2', the same by the paper's backward formulas
 * ``split_1d / split_2d``   the paper's kernel splitting (Sec. 4.1, eq. 8 and eq. 12)
 * ``mults_per_tile``        the multiplication-count model behind Table 3
 * ``winograd_matrices``     B^T, G, A^T of F(2,l), l = 1..3 (Sec. 3.2 for l = 3)
@@ -119,6 +121,29 @@ def dwm_f64(x, w, stride, pad):
     if rc:
         raise ValueError("oracle_dwm_f64: bad shape (rc=%d)" % rc)
     return y
+
+
+def _bwd(fn, dy, w, x_shape, stride, pad):
+    dy, w = _f32(dy), _f32(w)
+    N, C, H, W = x_shape
+    K, C2, R, S = w.shape
+    assert C == C2 and dy.shape == (N, K, out_size(H, R, stride, pad), out_size(W, S, stride, pad))
+    dx = np.empty((N, C, H, W), np.float64)
+    rc = fn(_fp(dy), _fp(w), _dp(dx), N, C, H, W, K, R, S, stride, pad)
+    if rc:
+        raise ValueError("backward data: bad shape (rc=%d)" % rc)
+    return dx
+
+
+def backward_data_f64(dy, w, x_shape, stride, pad):
+    """O1': dL/dx for L = <dy, conv(x, w)>, by its definition (the paper's backward pass,
+    Sec. 3.1 eq. 5 / Sec. 4.2 eq. 16-17, computes this quantity)."""
+    return _bwd(_load().oracle_backward_data_f64, dy, w, x_shape, stride, pad)
+
+
+def dwm_backward_data_f64(dy, w, x_shape, stride, pad):
+    """O2': the same gradient by the paper's formulas, part by part."""
+    return _bwd(_load().oracle_dwm_backward_data_f64, dy, w, x_shape, stride, pad)
 
 
 def split_1d(r, s):

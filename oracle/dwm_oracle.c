@@ -19,6 +19,12 @@
  *                              size by the consecutive 3-tap cut of Sec. 4.1 "Large
  *                              kernel size" (eq. 8-11).
  *
+ * and, for the gradient with respect to the input (the paper's backward pass, Sec. 3.1
+ * eq. 5 and Sec. 4.2 eq. 16-17):
+ *
+ *   O1' oracle_backward_data_f64      the definition of dL/dx
+ *   O2' oracle_dwm_backward_data_f64  the paper's formulas, part by part
+ *
  * All arithmetic is double precision; inputs are the float32 arrays the GPU sees,
  * widened on load.  Layouts: x[N][C][H][W], w[K][C][R][S], y[N][K][OH][OW], dense.
  * Cross-correlation semantics (the printed F(2,3) matrices of Sec. 3.2 compute
@@ -380,6 +386,131 @@ int oracle_dwm_f64(const float* x, const float* w, double* y,
         }
     }
     free(parts); free(U); free(V);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gradient with respect to the input                                         */
+/* ------------------------------------------------------------------------- */
+/*
+ * O1': the definition.  With L = sum_{n,k,oh,ow} dy[n,k,oh,ow] * y[n,k,oh,ow] and y the
+ * convolution above, dL/dx[n,c,ih,iw] = sum over every (k, r, q, oh, ow) whose window
+ * touches that pixel (oh*s + r - P == ih, ow*s + q - P == iw) of dy[n,k,oh,ow] * w[k,c,r,q].
+ * The paper's backward pass (Sec. 3.1 eq. 5 for one Winograd unit, Sec. 4.2 eq. 16-17 for
+ * the decomposition: dY^(j) = dY for every part, the parts' input gradients are added up)
+ * computes exactly this quantity.
+ */
+int oracle_backward_data_f64(const float* dy, const float* w, double* dx,
+                             int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = (H + 2 * P - R) / s + 1, OW = (W + 2 * P - S) / s + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int ih = 0; ih < H; ++ih)
+                for (int iw = 0; iw < W; ++iw) {
+                    double acc = 0.0;
+                    for (int k = 0; k < K; ++k)
+                        for (int r = 0; r < R; ++r) {
+                            int a = ih + P - r;
+                            if (a < 0 || a % s != 0 || a / s >= OH) continue;
+                            for (int q = 0; q < S; ++q) {
+                                int b = iw + P - q;
+                                if (b < 0 || b % s != 0 || b / s >= OW) continue;
+                                acc += (double)dy[(((size_t)n * K + k) * OH + a / s) * OW + b / s] *
+                                       (double)w[(((size_t)k * C + c) * R + r) * S + q];
+                            }
+                        }
+                    dx[(((size_t)n * C + c) * H + ih) * W + iw] = acc;
+                }
+    return 0;
+}
+
+/*
+ * O2': the paper's backward pass step by step.  For every part (splitting as in the
+ * forward pass) and every 2x2 output tile: dM = A dY A^T (the transposed
+ * detransformation), dV = sum_k U .* dM (Sec. 3.1 eq. 5: dd = B[(A dY A^T) .* U]B^T, with
+ * the sum over filters that the channel-wise forward sum turns into), dd = B dV B^T, and
+ * dd is added into the padded input gradient at the positions the part's patch was read
+ * from (Sec. 4.2 eq. 17: the parts' gradients are summed).  The padding is cropped last.
+ */
+int oracle_dwm_backward_data_f64(const float* dy, const float* w, double* dx,
+                                 int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = (H + 2 * P - R) / s + 1, OW = (W + 2 * P - S) / s + 1;
+    const int TH = (OH + 1) / 2, TW = (OW + 1) / 2;
+    /* padded gradient image, large enough for the overhang of the last (partial) tile */
+    const int HP = s * (2 * TH + (R + s - 1) / s + 2) + s, WP = s * (2 * TW + (S + s - 1) / s + 2) + s;
+    oracle_part* parts = (oracle_part*)malloc(sizeof(oracle_part) * ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (!parts) return 2;
+    const int n_parts = oracle_split_2d(R, S, s, parts, ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (n_parts < 0) { free(parts); return 1; }
+    double* U = (double*)malloc(sizeof(double) * (size_t)K * C * 16);
+    double* gp = (double*)malloc(sizeof(double) * (size_t)C * HP * WP);
+    if (!U || !gp) { free(parts); free(U); free(gp); return 2; }
+    int rc = 0;
+    for (int n = 0; n < N && !rc; ++n) {
+        memset(gp, 0, sizeof(double) * (size_t)C * HP * WP);
+        for (int ip = 0; ip < n_parts && !rc; ++ip) {
+            const oracle_part* pt = &parts[ip];
+            const int th = pt->lh + 1, tw = pt->lw + 1;
+            rc = oracle_part_filter_transform(w, K, C, R, S, s, pt, U);
+            if (rc) break;
+#pragma omp parallel for schedule(static)
+            for (int c = 0; c < C; ++c)
+                for (int ty = 0; ty < TH; ++ty)
+                    for (int tx = 0; tx < TW; ++tx) {
+                        double dV[4][4];
+                        for (int i = 0; i < th; ++i)
+                            for (int j = 0; j < tw; ++j) dV[i][j] = 0.0;
+                        for (int k = 0; k < K; ++k) {
+                            /* dM = A dY A^T, dY the tile's 2x2 block (zero past the output) */
+                            double g2[2][2], Ag[4][2];
+                            for (int a = 0; a < 2; ++a)
+                                for (int b = 0; b < 2; ++b) {
+                                    int oh = 2 * ty + a, ow = 2 * tx + b;
+                                    g2[a][b] = (oh < OH && ow < OW)
+                                                   ? (double)dy[(((size_t)n * K + k) * OH + oh) * OW + ow] : 0.0;
+                                }
+                            for (int i = 0; i < th; ++i)
+                                for (int b = 0; b < 2; ++b) {
+                                    Ag[i][b] = 0.0;
+                                    for (int a = 0; a < 2; ++a) Ag[i][b] += AT_[LIDX(pt->lh)][a][i] * g2[a][b];
+                                }
+                            const double* u = U + ((size_t)k * C + c) * th * tw;
+                            for (int i = 0; i < th; ++i)
+                                for (int j = 0; j < tw; ++j) {
+                                    double dM = 0.0;
+                                    for (int b = 0; b < 2; ++b) dM += Ag[i][b] * AT_[LIDX(pt->lw)][b][j];
+                                    dV[i][j] += u[i * tw + j] * dM;
+                                }
+                        }
+                        /* dd = B dV B^T, added where the patch was read */
+                        double BdV[4][4];
+                        for (int a = 0; a < th; ++a)
+                            for (int j = 0; j < tw; ++j) {
+                                BdV[a][j] = 0.0;
+                                for (int i = 0; i < th; ++i) BdV[a][j] += BT_[LIDX(pt->lh)][i][a] * dV[i][j];
+                            }
+                        for (int a = 0; a < th; ++a)
+                            for (int b = 0; b < tw; ++b) {
+                                double acc = 0.0;
+                                for (int j = 0; j < tw; ++j) acc += BdV[a][j] * BT_[LIDX(pt->lw)][j][b];
+                                int ph = s * (2 * ty + pt->jh + a) + pt->ph, pw = s * (2 * tx + pt->jw + b) + pt->pw;
+                                gp[((size_t)c * HP + ph) * WP + pw] += acc;
+                            }
+                    }
+        }
+        for (int c = 0; c < C; ++c)
+            for (int ih = 0; ih < H; ++ih)
+                for (int iw = 0; iw < W; ++iw)
+                    dx[(((size_t)n * C + c) * H + ih) * W + iw] = gp[((size_t)c * HP + ih + P) * WP + iw + P];
+    }
+    free(parts); free(U); free(gp);
     return rc;
 }
 
