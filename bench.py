@@ -65,6 +65,59 @@ def cpu_baseline(x, w, L, target_s=12.0):
             "sample": "%d of %d outputs of %s drawn uniformly, FP64 direct convolution" % (n, total, L.name)}
 
 
+def bench_backward_data(args, L, x, w):
+    """A step = one dwm_conv_backward_data (stride^2 stride-1 sub-convolutions of dy) on resident
+    buffers; the filter transform of the flipped, phase-split weights runs once before."""
+    import numpy as np
+    import torch
+
+    import dwm_workloads as wl
+    import paper_2002_00552_amd as dwm
+
+    OH, OW = wl.out_hw(L)
+    dy = np.random.default_rng(3100).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
+    plan = dwm.dwm_bwd_data_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    info = dwm.dwm_bwd_data_plan_info(plan)
+    dyd, wd = torch.from_numpy(dy).cuda(), torch.from_numpy(w).cuda()
+    U = torch.empty(dwm.dwm_bwd_data_filter_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(dwm.dwm_bwd_data_workspace_bytes(plan) // 4, 64), dtype=torch.float32, device="cuda")
+    dx = torch.empty((L.N, L.C, L.H, L.W), dtype=torch.float32, device="cuda")
+    dwm.dwm_bwd_data_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+    st = torch.cuda.current_stream().cuda_stream
+    dwm.dwm_bwd_data_filter_transform(plan, wd.data_ptr(), U.data_ptr(), st)
+    for _ in range(args.warmup):
+        dwm.dwm_conv_backward_data(plan, dyd.data_ptr(), U.data_ptr(), dx.data_ptr(), st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dwm.dwm_conv_backward_data(plan, dyd.data_ptr(), U.data_ptr(), dx.data_ptr(), st)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    out = {
+        "metric": "direct-conv-equivalent TFLOP/s of the DWM data gradient (fp32, 1 GPU); MSE vs FP64 definition",
+        "value": info.direct_flops / dt / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": L.name + "_backward_data", "phases": info.n_phases, "subconvs": info.n_subconvs,
+                   "direct_GFLOP": info.direct_flops / 1e9, "winograd_GFLOP": info.winograd_flops / 1e9},
+        "roofline": {"kernel": "all sub-convolutions", "bound": "mfma", "achieved": info.winograd_flops / dt / 1e12,
+                     "peak": PEAK_MFMA_F32, "unit": "TFLOP/s", "frac": info.winograd_flops / dt / 1e12 / PEAK_MFMA_F32,
+                     "traffic": None},
+    }
+    if not args.no_check:
+        import oracle
+        got = dx.cpu().numpy()
+        idx = np.random.default_rng(98).choice(got.size, min(got.size, 20000), replace=False)
+        ref = oracle.backward_data_f64_at(dy, w, (L.N, L.C, L.H, L.W), L.stride, L.pad, idx)
+        g = got.ravel()[idx].astype(np.float64)
+        mse = float(np.mean((g - ref) ** 2))
+        out["accuracy"] = {"max_rel_err": float(np.max(np.abs(g - ref)) / np.max(np.abs(ref))),
+                           "mse_vs_fp64": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
+                           "sampled_outputs": int(idx.size)}
+    dwm.dwm_bwd_data_plan_destroy(plan)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +130,8 @@ def main():
     ap.add_argument("--split-mode", type=int, default=-1)
     ap.add_argument("--input-cg", type=int, default=-1)
     ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
+    ap.add_argument("--backward-data", action="store_true",
+                    help="time the gradient with respect to the input of the same layer instead of the forward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -100,6 +155,9 @@ def main():
     else:
         L = wl.CONFIGS[args.config]
         x, w = wl.make_layer_tensors(L, args.config)
+
+    if args.backward_data:
+        return bench_backward_data(args, L, x, w)
 
     plan = dwm.dwm_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     info = dwm.dwm_plan_info(plan)

@@ -195,6 +195,57 @@ DWM_API dwm_status_t dwm_conv_forward(const dwm_plan_t* plan, const float* x_dev
 DWM_API dwm_status_t dwm_input_transform(const dwm_plan_t* plan, const float* x_dev, void* stream);
 DWM_API dwm_status_t dwm_contract_output(const dwm_plan_t* plan, const float* Ugw_dev, float* y_dev, void* stream);
 
+/*
+ * Gradient with respect to the input (the paper's backward pass: Sec. 3.1 eq. 5 for one
+ * Winograd unit, Sec. 4.2 eq. 16-17 for the decomposition -- every part receives the whole
+ * output gradient and the parts' input gradients are summed, which is the gradient of the
+ * ordinary convolution):
+ *     dx[n,c,ih,iw] = sum over (k,r,q,oh,ow) with oh*stride+r-pad == ih, ow*stride+q-pad == iw
+ *                     of dy[n,k,oh,ow] * w[k,c,r,q]
+ * It is computed as stride^2 stride-1 convolutions of dy, one per phase of the input
+ * position modulo the stride (the phase grouping of Sec. 4.1, eq. 12-14, in mirror image),
+ * each run through the forward machinery above and written to its own pixels of dx; phases
+ * no tap reaches are written as zeros.  dx is fully overwritten, nothing is accumulated in
+ * memory, results do not vary from run to run.
+ * The plan takes the FORWARD layer's shape.  Limits: stride <= 8 and those of dwm_plan_create.
+ * Memory, stream and error conventions are the same as for the forward calls; the workspace
+ * (>= dwm_bwd_data_workspace_bytes, 256-byte aligned, non-null) is shared by the
+ * sub-convolutions, which run one after the other on the stream.
+ */
+typedef struct dwm_bwd_data_plan dwm_bwd_data_plan_t;
+
+typedef struct {
+    int n_phases;                    /* stride^2 */
+    int n_subconvs;                  /* phases that hold taps and pixels */
+    long long mults_per_input_block; /* sum over sub-convolutions of their multiplications per 2x2 tile */
+    double direct_flops;             /* 2*N*K*C*R*S*OH*OW, the same as the forward pass */
+    double winograd_flops;           /* sum over sub-convolutions */
+} dwm_bwd_data_info_t;
+
+typedef struct {
+    int phase_h, phase_w; /* padded input position modulo the stride */
+    int taps_h, taps_w;   /* taps of the kernel in that phase: ceil((R - phase_h)/stride), 0 if none */
+    int first_h, first_w; /* first pixel of dx in the phase */
+    int count_h, count_w; /* pixels of dx in the phase, per dimension */
+    int has_subconv;      /* 1: a stride-1 convolution of taps_h x taps_w taps computes them; 0: zeros */
+} dwm_bwd_phase_t;
+
+DWM_API dwm_status_t dwm_bwd_data_plan_create(dwm_bwd_data_plan_t** out, int N, int C, int H, int W, int K, int R,
+                                              int S, int stride, int pad);
+DWM_API dwm_status_t dwm_bwd_data_plan_destroy(dwm_bwd_data_plan_t* plan);
+DWM_API dwm_status_t dwm_bwd_data_plan_info(const dwm_bwd_data_plan_t* plan, dwm_bwd_data_info_t* info);
+DWM_API dwm_status_t dwm_bwd_data_plan_phase(const dwm_bwd_data_plan_t* plan, int i, dwm_bwd_phase_t* out);
+DWM_API size_t dwm_bwd_data_filter_bytes(const dwm_bwd_data_plan_t* plan);
+DWM_API size_t dwm_bwd_data_workspace_bytes(const dwm_bwd_data_plan_t* plan);
+DWM_API dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void* ws_dev, size_t bytes);
+/* w_dev is the forward layer's [K][C][R][S]; Ugw_dev (dwm_bwd_data_filter_bytes long) receives, per
+ * phase, the transformed filter of that phase's flipped taps with filters and channels swapped. */
+DWM_API dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, const float* w_dev, float* Ugw_dev,
+                                                   void* stream);
+/* dy_dev [N][K][OH][OW], dx_dev [N][C][H][W] (fully overwritten). */
+DWM_API dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float* dy_dev,
+                                            const float* Ugw_dev, float* dx_dev, void* stream);
+
 DWM_API const char* dwm_status_string(dwm_status_t status);
 
 #ifdef __cplusplus

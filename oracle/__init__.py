@@ -141,6 +141,22 @@ def backward_data_f64(dy, w, x_shape, stride, pad):
     return _bwd(_load().oracle_backward_data_f64, dy, w, x_shape, stride, pad)
 
 
+def backward_data_f64_at(dy, w, x_shape, stride, pad, flat_idx):
+    """O1' at sampled positions (flat indices into dx[N][C][H][W])."""
+    dy, w = _f32(dy), _f32(w)
+    N, C, H, W = x_shape
+    K, C2, R, S = w.shape
+    assert C == C2 and dy.shape == (N, K, out_size(H, R, stride, pad), out_size(W, S, stride, pad))
+    idx = np.ascontiguousarray(flat_idx, dtype=np.int64)
+    out = np.empty(idx.shape, np.float64)
+    rc = _load().oracle_backward_data_f64_at(
+        _fp(dy), _fp(w), idx.ctypes.data_as(ctypes.POINTER(ctypes.c_longlong)), ctypes.c_longlong(idx.size),
+        _dp(out), N, C, H, W, K, R, S, stride, pad)
+    if rc:
+        raise ValueError("oracle_backward_data_f64_at: bad shape or index (rc=%d)" % rc)
+    return out
+
+
 def dwm_backward_data_f64(dy, w, x_shape, stride, pad):
     """O2': the same gradient by the paper's formulas, part by part."""
     return _bwd(_load().oracle_dwm_backward_data_f64, dy, w, x_shape, stride, pad)

@@ -428,6 +428,40 @@ int oracle_backward_data_f64(const float* dy, const float* w, double* dx,
     return 0;
 }
 
+/* O1' at sampled positions of dx (flat indices into [N][C][H][W]). */
+int oracle_backward_data_f64_at(const float* dy, const float* w, const long long* idx, long long n_idx, double* out,
+                                int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = (H + 2 * P - R) / s + 1, OW = (W + 2 * P - S) / s + 1;
+    const long long total = (long long)N * C * H * W;
+    for (long long i = 0; i < n_idx; ++i)
+        if (idx[i] < 0 || idx[i] >= total) return 1;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (long long i = 0; i < n_idx; ++i) {
+        long long e = idx[i];
+        const int iw = (int)(e % W); e /= W;
+        const int ih = (int)(e % H); e /= H;
+        const int c = (int)(e % C);
+        const int n = (int)(e / C);
+        double acc = 0.0;
+        for (int k = 0; k < K; ++k)
+            for (int r = 0; r < R; ++r) {
+                int a = ih + P - r;
+                if (a < 0 || a % s != 0 || a / s >= OH) continue;
+                for (int q = 0; q < S; ++q) {
+                    int b = iw + P - q;
+                    if (b < 0 || b % s != 0 || b / s >= OW) continue;
+                    acc += (double)dy[(((size_t)n * K + k) * OH + a / s) * OW + b / s] *
+                           (double)w[(((size_t)k * C + c) * R + r) * S + q];
+                }
+            }
+        out[i] = acc;
+    }
+    return 0;
+}
+
 /*
  * O2': the paper's backward pass step by step.  For every part (splitting as in the
  * forward pass) and every 2x2 output tile: dM = A dY A^T (the transposed

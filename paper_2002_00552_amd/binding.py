@@ -49,6 +49,16 @@ class dwm_fused_row_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("part", "channel", "real")]
 
 
+class dwm_bwd_data_info_t(ctypes.Structure):
+    _fields_ = [("n_phases", ctypes.c_int), ("n_subconvs", ctypes.c_int), ("mults_per_input_block", ctypes.c_longlong),
+                ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double)]
+
+
+class dwm_bwd_phase_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("phase_h", "phase_w", "taps_h", "taps_w", "first_h", "first_w",
+                                            "count_h", "count_w", "has_subconv")]
+
+
 _P = ctypes.c_void_p
 _I = ctypes.c_int
 _SIGNATURES = {
@@ -69,6 +79,15 @@ _SIGNATURES = {
     "dwm_input_transform": (_I, [_P, _P, _P]),
     "dwm_contract_output": (_I, [_P, _P, _P, _P]),
     "dwm_status_string": (ctypes.c_char_p, [_I]),
+    "dwm_bwd_data_plan_create": (_I, [ctypes.POINTER(_P)] + [_I] * 9),
+    "dwm_bwd_data_plan_destroy": (_I, [_P]),
+    "dwm_bwd_data_plan_info": (_I, [_P, ctypes.POINTER(dwm_bwd_data_info_t)]),
+    "dwm_bwd_data_plan_phase": (_I, [_P, _I, ctypes.POINTER(dwm_bwd_phase_t)]),
+    "dwm_bwd_data_filter_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_bwd_data_workspace_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_bwd_data_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
+    "dwm_bwd_data_filter_transform": (_I, [_P, _P, _P, _P]),
+    "dwm_conv_backward_data": (_I, [_P, _P, _P, _P, _P]),
 }
 EXPORTS = sorted(_SIGNATURES)
 
@@ -175,3 +194,45 @@ def dwm_input_transform(plan, x_dev, stream=None):
 
 def dwm_contract_output(plan, Ugw_dev, y_dev, stream=None):
     _check(lib().dwm_contract_output(plan, Ugw_dev, y_dev, stream), "dwm_contract_output")
+
+
+def dwm_bwd_data_plan_create(N, C, H, W, K, R, S, stride, pad):
+    h = _P()
+    _check(lib().dwm_bwd_data_plan_create(ctypes.byref(h), N, C, H, W, K, R, S, stride, pad), "dwm_bwd_data_plan_create")
+    return h
+
+
+def dwm_bwd_data_plan_destroy(plan):
+    _check(lib().dwm_bwd_data_plan_destroy(plan), "dwm_bwd_data_plan_destroy")
+
+
+def dwm_bwd_data_plan_info(plan):
+    info = dwm_bwd_data_info_t()
+    _check(lib().dwm_bwd_data_plan_info(plan, ctypes.byref(info)), "dwm_bwd_data_plan_info")
+    return info
+
+
+def dwm_bwd_data_plan_phase(plan, i):
+    out = dwm_bwd_phase_t()
+    _check(lib().dwm_bwd_data_plan_phase(plan, i, ctypes.byref(out)), "dwm_bwd_data_plan_phase")
+    return out
+
+
+def dwm_bwd_data_filter_bytes(plan):
+    return int(lib().dwm_bwd_data_filter_bytes(plan))
+
+
+def dwm_bwd_data_workspace_bytes(plan):
+    return int(lib().dwm_bwd_data_workspace_bytes(plan))
+
+
+def dwm_bwd_data_set_workspace(plan, ws_dev, nbytes):
+    _check(lib().dwm_bwd_data_set_workspace(plan, ws_dev, nbytes), "dwm_bwd_data_set_workspace")
+
+
+def dwm_bwd_data_filter_transform(plan, w_dev, Ugw_dev, stream=None):
+    _check(lib().dwm_bwd_data_filter_transform(plan, w_dev, Ugw_dev, stream), "dwm_bwd_data_filter_transform")
+
+
+def dwm_conv_backward_data(plan, dy_dev, Ugw_dev, dx_dev, stream=None):
+    _check(lib().dwm_conv_backward_data(plan, dy_dev, Ugw_dev, dx_dev, stream), "dwm_conv_backward_data")

@@ -1,0 +1,233 @@
+// Gradient of the DWM convolution with respect to its input (paper Sec. 3.1 eq. 5 and
+// Sec. 4.2 eq. 16-17 state what is computed: every part receives the whole output gradient
+// and the parts' input gradients add up -- the sum is the gradient of the ordinary
+// convolution).
+//
+// How it is organised here.  The gradient image is itself a convolution of dy, and the
+// stride splitting of Sec. 4.1 (eq. 12-14) applies to it in mirror image: an input pixel at
+// padded position u belongs to phase a = u mod stride, only taps r = stride*i + a reach it,
+// and with u = stride*u' + a
+//     dx_a[u'] = sum_k sum_i dy[k][u' - i] * w[k][c][stride*i + a]
+// is a STRIDE-1 convolution of dy with the taps of phase a, flipped, filters and channels
+// swapped.  So the gradient is stride^2 independent stride-1 convolutions -- one per phase
+// pair (a, b) -- each run through the forward DWM machinery of this library (splitting into
+// pieces of at most three taps, F(2,l), the same kernels), whose outputs interleave: the
+// sub-convolution of phase (a, b) writes the pixels (stride*o + oy, stride*o' + ox) of dx.
+// Every pixel of dx is written exactly once, nothing is accumulated in memory, results are
+// bit-identical from run to run.  Phases that hold no tap (stride > kernel) get zeros.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "plan.hpp"
+
+struct dwm_bwd_data_plan {
+    int N, C, H, W, K, R, S, s, P, OH, OW;
+    struct Phase {
+        int a, b, na, nb;    // phase pair, taps per dimension (0: no tap)
+        int oy, ox, UH, UW;  // first pixel of the phase in dx, pixels per dimension
+        dwm_plan_t* sub;     // stride-1 sub-convolution (null if the phase has no tap or no pixel)
+        size_t u_off;        // its transformed filter inside Ugw (floats)
+    };
+    std::vector<Phase> phases;
+    size_t wtmp_floats;      // start of Ugw: scratch for one phase's gathered, flipped weights
+    size_t filter_floats, ws_bytes;
+    double direct_flops;
+};
+
+namespace dwm {
+
+// wt[c][k][i][j] = w[k][c][s*(na-1-i) + a][s*(nb-1-j) + b]
+__global__ __launch_bounds__(256) void bwd_gather_weights_kernel(const float* __restrict__ w, float* __restrict__ wt,
+                                                                 int K, int C, int R, int S, int s, int a, int b,
+                                                                 int na, int nb)
+{
+    const size_t total = (size_t)C * K * na * nb;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const int j = (int)(e % nb);
+        const int i = (int)((e / nb) % na);
+        const int k = (int)((e / ((size_t)nb * na)) % K);
+        const int c = (int)(e / ((size_t)nb * na * K));
+        wt[e] = w[(((size_t)k * C + c) * R + (s * (na - 1 - i) + a)) * S + (s * (nb - 1 - j) + b)];
+    }
+}
+
+// dx[n][c][sy*o + oy][sx*o' + ox] = 0 for o < UH, o' < UW
+__global__ __launch_bounds__(256) void bwd_zero_phase_kernel(float* __restrict__ dx, int planes, int H, int W, int s,
+                                                             int oy, int ox, int UH, int UW)
+{
+    const size_t total = (size_t)planes * UH * UW;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const int v = (int)(e % UW);
+        const int u = (int)((e / UW) % UH);
+        const size_t pl = e / ((size_t)UW * UH);
+        dx[(pl * H + (size_t)(s * u + oy)) * W + (s * v + ox)] = 0.f;
+    }
+}
+
+static int ceil_div(int x, int d) { return x >= 0 ? (x + d - 1) / d : -((-x) / d); }
+
+}  // namespace dwm
+
+extern "C" {
+
+dwm_status_t dwm_bwd_data_plan_create(dwm_bwd_data_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                                      int stride, int pad)
+{
+    using namespace dwm;
+    if (!out) return DWM_ERR_INVALID_ARG;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || pad < 0)
+        return DWM_ERR_INVALID_ARG;
+    if ((long long)H + 2LL * pad < R || (long long)W + 2LL * pad < S) return DWM_ERR_INVALID_ARG;
+    if (pad > (1 << 20) || H > (1 << 20) || W > (1 << 20) || stride > 8) return DWM_ERR_UNSUPPORTED;
+    dwm_bwd_data_plan* bp = new (std::nothrow) dwm_bwd_data_plan;
+    if (!bp) return DWM_ERR_ALLOC;
+    bp->N = N; bp->C = C; bp->H = H; bp->W = W; bp->K = K; bp->R = R; bp->S = S; bp->s = stride; bp->P = pad;
+    bp->OH = (H + 2 * pad - R) / stride + 1;
+    bp->OW = (W + 2 * pad - S) / stride + 1;
+    bp->direct_flops = 2.0 * N * K * C * R * S * bp->OH * bp->OW;
+    bp->wtmp_floats = 0;
+    bp->ws_bytes = 256;
+    const int s = stride;
+    dwm_status_t st = DWM_OK;
+    for (int a = 0; a < s && st == DWM_OK; ++a)
+        for (int b = 0; b < s && st == DWM_OK; ++b) {
+            dwm_bwd_data_plan::Phase ph{};
+            ph.a = a; ph.b = b;
+            ph.na = a < R ? (R - a + s - 1) / s : 0;
+            ph.nb = b < S ? (S - b + s - 1) / s : 0;
+            // pixels of this phase: padded position u = s*u' + a with pad <= u < H + pad
+            const int u0 = ceil_div(pad - a, s), v0 = ceil_div(pad - b, s);
+            const int u1 = H + pad - 1 - a >= 0 ? (H + pad - 1 - a) / s : -1;
+            const int v1 = W + pad - 1 - b >= 0 ? (W + pad - 1 - b) / s : -1;
+            ph.UH = u1 - u0 + 1; ph.UW = v1 - v0 + 1;
+            ph.oy = s * u0 + a - pad; ph.ox = s * v0 + b - pad;
+            ph.sub = nullptr;
+            if (ph.UH > 0 && ph.UW > 0 && ph.na > 0 && ph.nb > 0) {
+                // the stride-1 sub-convolution: dy is its input (K channels), C filters of na x nb
+                // taps; output o stands for u' = o + u0, whose window starts at dy row u' - (na-1)
+                PlanSpec sp{};
+                sp.N = N; sp.C = K; sp.H = bp->OH; sp.W = bp->OW; sp.K = C; sp.R = ph.na; sp.S = ph.nb; sp.stride = 1;
+                sp.pad_h = ph.na - 1 - u0; sp.pad_w = ph.nb - 1 - v0;
+                sp.OH = ph.UH; sp.OW = ph.UW;
+                sp.om = OutMap{H, W, s, ph.oy, s, ph.ox};
+                st = plan_from_spec(&ph.sub, sp);
+                if (st == DWM_OK) {
+                    bp->wtmp_floats = std::max(bp->wtmp_floats, (size_t)C * K * ph.na * ph.nb);
+                    bp->ws_bytes = std::max(bp->ws_bytes, dwm_plan_workspace_bytes(ph.sub));
+                }
+            }
+            bp->phases.push_back(ph);
+        }
+    if (st != DWM_OK) {
+        for (auto& ph : bp->phases)
+            if (ph.sub) dwm_plan_destroy(ph.sub);
+        delete bp;
+        return st;
+    }
+    size_t off = (bp->wtmp_floats + 63) / 64 * 64;
+    bp->wtmp_floats = off;
+    for (auto& ph : bp->phases)
+        if (ph.sub) {
+            ph.u_off = off;
+            off += (dwm_plan_filter_bytes(ph.sub) / sizeof(float) + 63) / 64 * 64;
+        }
+    bp->filter_floats = off;
+    *out = bp;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_bwd_data_plan_destroy(dwm_bwd_data_plan_t* plan)
+{
+    if (!plan) return DWM_ERR_INVALID_ARG;
+    for (auto& ph : plan->phases)
+        if (ph.sub) dwm_plan_destroy(ph.sub);
+    delete plan;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_bwd_data_plan_info(const dwm_bwd_data_plan_t* plan, dwm_bwd_data_info_t* info)
+{
+    if (!plan || !info) return DWM_ERR_INVALID_ARG;
+    info->n_phases = (int)plan->phases.size();
+    info->n_subconvs = 0;
+    info->winograd_flops = 0.0;
+    info->mults_per_input_block = 0;
+    for (const auto& ph : plan->phases)
+        if (ph.sub) {
+            dwm_plan_info_t si;
+            dwm_plan_info(ph.sub, &si);
+            ++info->n_subconvs;
+            info->winograd_flops += si.winograd_flops;
+            info->mults_per_input_block += si.mults_per_tile;
+        }
+    info->direct_flops = plan->direct_flops;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_bwd_data_plan_phase(const dwm_bwd_data_plan_t* plan, int i, dwm_bwd_phase_t* out)
+{
+    if (!plan || !out || i < 0 || i >= (int)plan->phases.size()) return DWM_ERR_INVALID_ARG;
+    const auto& ph = plan->phases[i];
+    out->phase_h = ph.a; out->phase_w = ph.b; out->taps_h = ph.na; out->taps_w = ph.nb;
+    out->first_h = ph.oy; out->first_w = ph.ox; out->count_h = ph.UH; out->count_w = ph.UW;
+    out->has_subconv = ph.sub != nullptr;
+    return DWM_OK;
+}
+
+size_t dwm_bwd_data_filter_bytes(const dwm_bwd_data_plan_t* plan) { return plan ? plan->filter_floats * sizeof(float) : 0; }
+size_t dwm_bwd_data_workspace_bytes(const dwm_bwd_data_plan_t* plan) { return plan ? plan->ws_bytes : 0; }
+
+dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void* ws_dev, size_t bytes)
+{
+    if (!plan) return DWM_ERR_INVALID_ARG;
+    if (bytes < plan->ws_bytes) return DWM_ERR_WORKSPACE;
+    for (auto& ph : plan->phases)
+        if (ph.sub) {
+            const dwm_status_t st = dwm_plan_set_workspace(ph.sub, ws_dev, bytes);
+            if (st != DWM_OK) return st;
+        }
+    return DWM_OK;
+}
+
+dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, const float* w_dev, float* Ugw_dev,
+                                           void* stream)
+{
+    if (!plan || !w_dev || !Ugw_dev) return DWM_ERR_INVALID_ARG;
+    for (const auto& ph : plan->phases) {
+        if (!ph.sub) continue;
+        const size_t total = (size_t)plan->C * plan->K * ph.na * ph.nb;
+        const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 4096);
+        // the scratch at the start of Ugw is reused phase after phase: stream order keeps it safe
+        hipLaunchKernelGGL(dwm::bwd_gather_weights_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, w_dev,
+                           Ugw_dev, plan->K, plan->C, plan->R, plan->S, plan->s, ph.a, ph.b, ph.na, ph.nb);
+        if (hipGetLastError() != hipSuccess) return DWM_ERR_HIP;
+        const dwm_status_t st = dwm_filter_transform(ph.sub, Ugw_dev, Ugw_dev + ph.u_off, stream);
+        if (st != DWM_OK) return st;
+    }
+    return DWM_OK;
+}
+
+dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float* dy_dev, const float* Ugw_dev,
+                                    float* dx_dev, void* stream)
+{
+    if (!plan || !dy_dev || !Ugw_dev || !dx_dev) return DWM_ERR_INVALID_ARG;
+    for (const auto& ph : plan->phases) {
+        if (ph.UH <= 0 || ph.UW <= 0) continue;
+        if (!ph.sub) {  // no tap reaches these pixels
+            const size_t total = (size_t)plan->N * plan->C * ph.UH * ph.UW;
+            const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 8192);
+            hipLaunchKernelGGL(dwm::bwd_zero_phase_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, dx_dev,
+                               plan->N * plan->C, plan->H, plan->W, plan->s, ph.oy, ph.ox, ph.UH, ph.UW);
+            if (hipGetLastError() != hipSuccess) return DWM_ERR_HIP;
+            continue;
+        }
+        const dwm_status_t st = dwm_conv_forward(ph.sub, dy_dev, Ugw_dev + ph.u_off, dx_dev, stream);
+        if (st != DWM_OK) return st;
+    }
+    return DWM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+"""GPU parity tests of the data gradient: dwm_conv_backward_data, called through the C ABI,
+against the FP64 definition of dL/dx (oracle.backward_data_f64).
+
+Bar: max |dx_gpu - dx_ref| / max |dx_ref| <= 1e-4, the forward path's bar (the gradient is a
+sum of K*R*S/stride^2 products per pixel in the same fp32 arithmetic).
+"""
+import numpy as np
+import pytest
+import torch
+
+import dwm_workloads as wl
+import oracle
+import paper_2002_00552_amd as dwm
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+class BwdRunner:
+    def __init__(self, N, C, H, W, K, R, S, stride, pad):
+        self.plan = dwm.dwm_bwd_data_plan_create(N, C, H, W, K, R, S, stride, pad)
+        dev = torch.device("cuda:0")
+        self.Ugw = torch.full((dwm.dwm_bwd_data_filter_bytes(self.plan) // 4,), float("nan"), dtype=torch.float32, device=dev)
+        self.ws = torch.full((max(dwm.dwm_bwd_data_workspace_bytes(self.plan) // 4, 64),), float("nan"),
+                             dtype=torch.float32, device=dev)
+        dwm.dwm_bwd_data_set_workspace(self.plan, self.ws.data_ptr(), self.ws.numel() * 4)
+        self.dx = torch.full((N, C, H, W), float("nan"), dtype=torch.float32, device=dev)
+
+    def run(self, dy, w):
+        st = torch.cuda.current_stream().cuda_stream
+        self.w = torch.from_numpy(np.ascontiguousarray(w)).cuda()
+        self.dy = torch.from_numpy(np.ascontiguousarray(dy)).cuda()
+        dwm.dwm_bwd_data_filter_transform(self.plan, self.w.data_ptr(), self.Ugw.data_ptr(), st)
+        dwm.dwm_conv_backward_data(self.plan, self.dy.data_ptr(), self.Ugw.data_ptr(), self.dx.data_ptr(), st)
+        torch.cuda.synchronize()
+        return self.dx.cpu().numpy()
+
+    def close(self):
+        dwm.dwm_bwd_data_plan_destroy(self.plan)
+
+
+def _rand(N, C, H, W, K, R, S, s, P, seed):
+    rng = np.random.default_rng(seed)
+    OH, OW = (H + 2 * P - R) // s + 1, (W + 2 * P - S) // s + 1
+    w = (rng.standard_normal((K, C, R, S)) * np.sqrt(2.0 / (C * R * S))).astype(np.float32)
+    dy = rng.uniform(-1, 1, (N, K, OH, OW)).astype(np.float32)
+    return w, dy
+
+
+def _relerr(a, ref):
+    return float(np.max(np.abs(a.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+SHAPES = [  # N, C, H, W, K, R, S, stride, pad
+    (1, 16, 32, 32, 16, 5, 5, 1, 2),     # benchmark config 1
+    (2, 3, 13, 15, 5, 5, 5, 1, 2),
+    (3, 8, 19, 21, 70, 3, 3, 2, 1),      # the stride-2 downsampling pattern, odd sizes
+    (2, 24, 14, 14, 40, 7, 7, 1, 3),
+    (2, 3, 37, 35, 33, 7, 7, 2, 3),      # stem pattern: phases of 4 and 3 taps
+    (2, 3, 43, 47, 20, 11, 11, 4, 0),    # 16 phases, pixels at the end no window touches
+    (1, 5, 9, 10, 2, 1, 7, 1, 3),        # R != S
+    (2, 17, 12, 12, 9, 1, 1, 1, 0),      # 1x1
+    (1, 7, 11, 11, 4, 1, 1, 2, 0),       # stride beyond the kernel: three of four phases are zeros
+    (1, 4, 16, 16, 8, 2, 2, 2, 0),
+    (1, 3, 20, 18, 5, 4, 6, 3, 2),       # pad not a multiple of the stride
+    (1, 2, 12, 12, 3, 12, 12, 1, 0),     # a single output pixel spread over the whole image
+    (5, 130, 7, 7, 129, 3, 3, 1, 1),     # many channels on both sides: staged sub-convolutions
+    (2, 70, 21, 19, 130, 3, 3, 2, 1),
+    (1, 3, 9, 300, 4, 3, 5, 1, 2),       # one long row
+    (2, 6, 40, 33, 5, 5, 5, 2, 5),       # pad larger than the kernel reach: windows wholly in the padding
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_backward_data_matches_fp64_definition(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    w, dy = _rand(*shape, seed=300 + R * 7 + S)
+    ref = oracle.backward_data_f64(dy, w, (N, C, H, W), s, P)
+    r = BwdRunner(*shape)
+    dx = r.run(dy, w)
+    r.close()
+    assert np.all(np.isfinite(dx))  # every pixel written, the untouched ones as zeros
+    assert _relerr(dx, ref) <= TOL, shape
+
+
+def test_backward_data_is_deterministic_and_plan_reusable():
+    shape = (2, 8, 21, 20, 9, 5, 5, 2, 2)
+    w, dy = _rand(*shape, seed=5)
+    r = BwdRunner(*shape)
+    a = r.run(dy, w).copy()
+    r.dx.fill_(float("nan"))
+    b = r.run(dy, w).copy()
+    assert np.array_equal(a, b)
+    dy2 = (dy * 0.5).astype(np.float32)
+    c = r.run(dy2, w)
+    assert _relerr(c, oracle.backward_data_f64(dy2, w, shape[:4], 2, 2)) <= TOL
+    r.close()
+
+
+def test_backward_data_phases_cover_the_image_once():
+    for shape in [(1, 2, 17, 19, 3, 7, 7, 2, 3), (1, 2, 23, 22, 3, 11, 11, 4, 0), (1, 2, 9, 9, 3, 1, 1, 3, 0),
+                  (1, 2, 10, 13, 3, 4, 6, 3, 2)]:
+        N, C, H, W, K, R, S, s, P = shape
+        p = dwm.dwm_bwd_data_plan_create(*shape)
+        info = dwm.dwm_bwd_data_plan_info(p)
+        assert info.n_phases == s * s
+        cover = np.zeros((H, W), int)
+        for i in range(info.n_phases):
+            ph = dwm.dwm_bwd_data_plan_phase(p, i)
+            assert ph.taps_h == len(range(ph.phase_h, R, s)) and ph.taps_w == len(range(ph.phase_w, S, s))
+            if ph.count_h > 0 and ph.count_w > 0:
+                cover[ph.first_h:ph.first_h + s * ph.count_h:s, ph.first_w:ph.first_w + s * ph.count_w:s] += 1
+                assert (ph.first_h + P) % s == ph.phase_h and (ph.first_w + P) % s == ph.phase_w
+                assert bool(ph.has_subconv) == (ph.taps_h > 0 and ph.taps_w > 0)
+        assert np.all(cover == 1)
+        dwm.dwm_bwd_data_plan_destroy(p)
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
+def test_backward_data_benchmark_layers_full_size(index):
+    """Whole layer on the GPU; the oracle computes 20 000 sampled pixels of dx one by one plus the
+    image border, where the padding and the ragged ends of every phase live."""
+    L = wl.CONFIGS[index]
+    _, w = wl.make_layer_tensors(L, index)
+    OH, OW = wl.out_hw(L)
+    dy = np.random.default_rng(3100 + index).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
+    r = BwdRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    dx = r.run(dy, w)
+    r.close()
+    assert dx.shape == (L.N, L.C, L.H, L.W) and np.all(np.isfinite(dx))
+    rng = np.random.default_rng(5200 + index)
+    if dx.size <= 100000:
+        idx = np.arange(dx.size)
+    else:
+        idx = rng.choice(dx.size, 20000, replace=False)
+        n, c = L.N - 1, L.C - 1
+        edge = [((n * L.C + c) * L.H + L.H - 1) * L.W + j for j in range(L.W)]
+        edge += [((n * L.C + c) * L.H + i) * L.W + L.W - 1 for i in range(L.H)]
+        edge += list(range(L.W))
+        idx = np.unique(np.concatenate([idx, np.array(edge)]))
+    ref = oracle.backward_data_f64_at(dy, w, (L.N, L.C, L.H, L.W), L.stride, L.pad, idx)
+    got = dx.ravel()[idx].astype(np.float64)
+    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= TOL, L.name

@@ -96,6 +96,15 @@ def test_backward_data_of_a_delta_kernel_is_a_strided_placement():
     assert np.array_equal(dx[0, 0], want)
 
 
+def test_backward_data_at_matches_full():
+    x, w, dy = _rand(2, 3, 11, 12, 4, 5, 3, 2, 2, seed=21)
+    full = oracle.backward_data_f64(dy, w, x.shape, 2, 2)
+    idx = np.random.default_rng(0).choice(full.size, 200, replace=False)
+    assert np.array_equal(oracle.backward_data_f64_at(dy, w, x.shape, 2, 2, idx), full.ravel()[idx])
+    with pytest.raises(ValueError):
+        oracle.backward_data_f64_at(dy, w, x.shape, 2, 2, np.array([full.size]))
+
+
 @pytest.fixture
 def f22_form(request):
     oracle.set_f22_form(request.param)
