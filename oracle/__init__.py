@@ -11,6 +11,8 @@ compiles it with gcc on first use and exposes thin numpy wrappers:
 * ``dwm_f64``               O2, the paper's five steps in FP64
 * ``backward_data_f64``     O1', the gradient with respect to the input, by definition
 * ``dwm_backward_data_f64`` O2', the same by the paper's backward formulas
+* ``backward_filter_f64``   O1'', the gradient with respect to the filter, by definition
+* ``dwm_backward_filter_f64`` O2'', the same by the paper's formula
 * ``split_1d / split_2d``   the paper's kernel splitting (Sec. 4.1, eq. 8 and eq. 12)
 * ``mults_per_tile``        the multiplication-count model behind Table 3
 * ``winograd_matrices``     B^T, G, A^T of F(2,l), l = 1..3 (Sec. 3.2 for l = 3)
@@ -160,6 +162,29 @@ def backward_data_f64_at(dy, w, x_shape, stride, pad, flat_idx):
 def dwm_backward_data_f64(dy, w, x_shape, stride, pad):
     """O2': the same gradient by the paper's formulas, part by part."""
     return _bwd(_load().oracle_dwm_backward_data_f64, dy, w, x_shape, stride, pad)
+
+
+def _bwd_w(fn, x, dy, w_shape, stride, pad):
+    x, dy = _f32(x), _f32(dy)
+    N, C, H, W = x.shape
+    K, C2, R, S = w_shape
+    assert C == C2 and dy.shape == (N, K, out_size(H, R, stride, pad), out_size(W, S, stride, pad))
+    dw = np.empty((K, C, R, S), np.float64)
+    rc = fn(_fp(x), _fp(dy), _dp(dw), N, C, H, W, K, R, S, stride, pad)
+    if rc:
+        raise ValueError("backward filter: bad shape (rc=%d)" % rc)
+    return dw
+
+
+def backward_filter_f64(x, dy, w_shape, stride, pad):
+    """O1'': dL/dw for L = <dy, conv(x, w)>, by its definition (Sec. 3.1 eq. 5 / Sec. 4.2 eq. 18
+    compute this quantity)."""
+    return _bwd_w(_load().oracle_backward_filter_f64, x, dy, w_shape, stride, pad)
+
+
+def dwm_backward_filter_f64(x, dy, w_shape, stride, pad):
+    """O2'': the same gradient by the paper's formula, part by part."""
+    return _bwd_w(_load().oracle_dwm_backward_filter_f64, x, dy, w_shape, stride, pad)
 
 
 def split_1d(r, s):

@@ -24,6 +24,8 @@
  *
  *   O1' oracle_backward_data_f64      the definition of dL/dx
  *   O2' oracle_dwm_backward_data_f64  the paper's formulas, part by part
+ * and for the gradient with respect to the filter (Sec. 3.1 eq. 5, Sec. 4.2 eq. 18):
+ *   O1'' oracle_backward_filter_f64, O2'' oracle_dwm_backward_filter_f64
  *
  * All arithmetic is double precision; inputs are the float32 arrays the GPU sees,
  * widened on load.  Layouts: x[N][C][H][W], w[K][C][R][S], y[N][K][OH][OW], dense.
@@ -545,6 +547,119 @@ int oracle_dwm_backward_data_f64(const float* dy, const float* w, double* dx,
                     dx[(((size_t)n * C + c) * H + ih) * W + iw] = gp[((size_t)c * HP + ih + P) * WP + iw + P];
     }
     free(parts); free(U); free(gp);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gradient with respect to the filter                                        */
+/* ------------------------------------------------------------------------- */
+/*
+ * O1'': the definition.  y is linear in w, so for L = sum dy * y
+ *   dL/dw[k,c,r,q] = sum_{n,oh,ow} dy[n,k,oh,ow] * xp[n,c,oh*s+r,ow*s+q]   (xp = padded x).
+ * The paper's backward pass (Sec. 3.1 eq. 5, second formula; Sec. 4.2 eq. 18: every part's
+ * kernel gradient is computed from the whole output gradient) computes this quantity.
+ */
+int oracle_backward_filter_f64(const float* x, const float* dy, double* dw,
+                               int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = (H + 2 * P - R) / s + 1, OW = (W + 2 * P - S) / s + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c)
+            for (int r = 0; r < R; ++r)
+                for (int q = 0; q < S; ++q) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n)
+                        for (int oh = 0; oh < OH; ++oh) {
+                            int ih = oh * s + r - P;
+                            if (ih < 0 || ih >= H) continue;
+                            for (int ow = 0; ow < OW; ++ow) {
+                                int iw = ow * s + q - P;
+                                if (iw < 0 || iw >= W) continue;
+                                acc += (double)dy[(((size_t)n * K + k) * OH + oh) * OW + ow] *
+                                       (double)x[(((size_t)n * C + c) * H + ih) * W + iw];
+                            }
+                        }
+                    dw[(((size_t)k * C + c) * R + r) * S + q] = acc;
+                }
+    return 0;
+}
+
+/*
+ * O2'': the paper's formula part by part: dg = G^T [ sum over tiles and images of
+ * (A dY A^T) .* V ] G (Sec. 3.1 eq. 5), V = B^T d B the part's transformed input patch;
+ * a part's dg lands on the taps the part was cut from (Sec. 4.2 eq. 18).
+ */
+int oracle_dwm_backward_filter_f64(const float* x, const float* dy, double* dw,
+                                   int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
+    if (H + 2 * P < R || W + 2 * P < S) return 1;
+    const int OH = (H + 2 * P - R) / s + 1, OW = (W + 2 * P - S) / s + 1;
+    const int TH = (OH + 1) / 2, TW = (OW + 1) / 2;
+    oracle_part* parts = (oracle_part*)malloc(sizeof(oracle_part) * ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (!parts) return 2;
+    const int n_parts = oracle_split_2d(R, S, s, parts, ORACLE_MAX_PIECES * ORACLE_MAX_PIECES);
+    if (n_parts < 0) { free(parts); return 1; }
+    double* V = (double*)malloc(sizeof(double) * (size_t)C * TH * TW * 16);
+    double* dU = (double*)malloc(sizeof(double) * (size_t)K * C * 16);
+    if (!V || !dU) { free(parts); free(V); free(dU); return 2; }
+    memset(dw, 0, sizeof(double) * (size_t)K * C * R * S);
+    int rc = 0;
+    for (int ip = 0; ip < n_parts && !rc; ++ip) {
+        const oracle_part* pt = &parts[ip];
+        const int lh = pt->lh, lw = pt->lw, th = lh + 1, tw = lw + 1;
+        memset(dU, 0, sizeof(double) * (size_t)K * C * 16);
+        for (int n = 0; n < N && !rc; ++n) {
+            rc = oracle_part_input_transform(x, C, H, W, s, P, TH, TW, n, pt, V);
+            if (rc) break;
+#pragma omp parallel for schedule(static)
+            for (int k = 0; k < K; ++k)
+                for (int ty = 0; ty < TH; ++ty)
+                    for (int tx = 0; tx < TW; ++tx) {
+                        double g2[2][2], Ag[4][2], dM[4][4];
+                        for (int a = 0; a < 2; ++a)
+                            for (int b = 0; b < 2; ++b) {
+                                int oh = 2 * ty + a, ow = 2 * tx + b;
+                                g2[a][b] = (oh < OH && ow < OW)
+                                               ? (double)dy[(((size_t)n * K + k) * OH + oh) * OW + ow] : 0.0;
+                            }
+                        for (int i = 0; i < th; ++i)
+                            for (int b = 0; b < 2; ++b) {
+                                Ag[i][b] = 0.0;
+                                for (int a = 0; a < 2; ++a) Ag[i][b] += AT_[LIDX(lh)][a][i] * g2[a][b];
+                            }
+                        for (int i = 0; i < th; ++i)
+                            for (int j = 0; j < tw; ++j) {
+                                dM[i][j] = 0.0;
+                                for (int b = 0; b < 2; ++b) dM[i][j] += Ag[i][b] * AT_[LIDX(lw)][b][j];
+                            }
+                        for (int c = 0; c < C; ++c) {
+                            const double* v = V + (((size_t)c * TH + ty) * TW + tx) * th * tw;
+                            double* du = dU + ((size_t)k * C + c) * 16;
+                            for (int i = 0; i < th; ++i)
+                                for (int j = 0; j < tw; ++j) du[i * 4 + j] += dM[i][j] * v[i * tw + j];
+                        }
+                    }
+        }
+        /* dg = G^T dU G onto the part's taps */
+        for (int k = 0; k < K && !rc; ++k)
+            for (int c = 0; c < C; ++c) {
+                const double* du = dU + ((size_t)k * C + c) * 16;
+                for (int a = 0; a < lh; ++a)
+                    for (int b = 0; b < lw; ++b) {
+                        double acc = 0.0;
+                        for (int i = 0; i < th; ++i)
+                            for (int j = 0; j < tw; ++j)
+                                acc += G_[LIDX(lh)][i][a] * du[i * 4 + j] * G_[LIDX(lw)][j][b];
+                        int r = s * (pt->jh + a) + pt->ph, q = s * (pt->jw + b) + pt->pw;
+                        dw[(((size_t)k * C + c) * R + r) * S + q] += acc;
+                    }
+            }
+    }
+    free(parts); free(V); free(dU);
     return rc;
 }
 

@@ -1,4 +1,4 @@
-"""Pins for the oracle's gradient with respect to the input.
+"""Pins for the oracle's gradients with respect to the input and to the filter.
 
 O1' (the definition of dL/dx) is pinned by the adjoint identity against the pinned forward
 oracle O1, by PyTorch's float64 autograd on CPU (a library routine, used only here), by a
@@ -127,6 +127,54 @@ def test_paper_backward_formulas_equal_the_definition(f22_form):
                     x, w, dy = _rand(1 + i % 2, 2 + i % 3, H, W, 1 + i % 3, R, S, s, P, seed=500 + i)
                     e = _relerr(oracle.dwm_backward_data_f64(dy, w, x.shape, s, P),
                                 oracle.backward_data_f64(dy, w, x.shape, s, P))
+                    worst = max(worst, e)
+                    assert e < 1e-12, (R, S, s, P, H, W, e)
+    assert worst > 0.0
+
+
+# ---- gradient with respect to the filter ----
+
+@pytest.mark.parametrize("R,S,s,P,H,W", SHAPES)
+def test_backward_filter_is_the_adjoint_in_w(R, S, s, P, H, W):
+    """conv is linear in w: <dy, conv(x, w)> == <dL/dw, w>, and tap by tap dL/dw is the
+    response to a one-hot filter."""
+    x, w, dy = _rand(2, 3, H, W, 4, R, S, s, P, seed=40 + R * 100 + S * 10 + s)
+    dw = oracle.backward_filter_f64(x, dy, w.shape, s, P)
+    lhs = float(np.sum(dy.astype(np.float64) * oracle.direct_f64(x, w, s, P)))
+    rhs = float(np.sum(dw * w.astype(np.float64)))
+    assert abs(lhs - rhs) <= 1e-12 * max(abs(lhs), np.sum(np.abs(dw * w)))
+    rng = np.random.default_rng(2)
+    for _ in range(5):
+        k, c, r, q = rng.integers(4), rng.integers(3), rng.integers(R), rng.integers(S)
+        e = np.zeros_like(w)
+        e[k, c, r, q] = 1.0
+        want = float(np.sum(dy.astype(np.float64) * oracle.direct_f64(x, e, s, P)))
+        assert abs(dw[k, c, r, q] - want) <= 1e-12 * max(1.0, abs(want))
+
+
+@pytest.mark.parametrize("R,S,s,P,H,W", SHAPES)
+def test_backward_filter_vs_library_autograd(R, S, s, P, H, W):
+    x, w, dy = _rand(2, 3, H, W, 4, R, S, s, P, seed=77 + R + S + s)
+    wt = torch.from_numpy(w).double().requires_grad_(True)
+    yt = torch.nn.functional.conv2d(torch.from_numpy(x).double(), wt, stride=s, padding=P)
+    yt.backward(torch.from_numpy(dy).double())
+    assert _relerr(oracle.backward_filter_f64(x, dy, w.shape, s, P), wt.grad.numpy()) < 1e-13
+
+
+@pytest.mark.parametrize("f22_form", [0, 1], indirect=True)
+def test_paper_filter_gradient_formula_equals_the_definition(f22_form):
+    worst, i = 0.0, 0
+    for R in (1, 2, 3, 5, 7, 11):
+        for S in (1, 3, 4, 7):
+            for s in (1, 2, 3, 4):
+                for P in (0, 1, 3):
+                    i += 1
+                    H, W = 9 + i % 5, 8 + i % 7
+                    if H + 2 * P < R or W + 2 * P < S:
+                        continue
+                    x, w, dy = _rand(1 + i % 2, 2 + i % 3, H, W, 1 + i % 3, R, S, s, P, seed=900 + i)
+                    e = _relerr(oracle.dwm_backward_filter_f64(x, dy, w.shape, s, P),
+                                oracle.backward_filter_f64(x, dy, w.shape, s, P))
                     worst = max(worst, e)
                     assert e < 1e-12, (R, S, s, P, H, W, e)
     assert worst > 0.0
