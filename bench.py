@@ -118,6 +118,57 @@ def bench_backward_data(args, L, x, w):
     print(json.dumps(out))
 
 
+def bench_backward_filter(args, L, x, w):
+    """A step = one dwm_conv_backward_filter (input transform of x, A dY A^T, the per-plane GEMMs over
+    the tiles, G^T (.) G) on resident buffers."""
+    import numpy as np
+    import torch
+
+    import dwm_workloads as wl
+    import paper_2002_00552_amd as dwm
+
+    OH, OW = wl.out_hw(L)
+    dy = np.random.default_rng(4100).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
+    plan = dwm.dwm_bwd_filter_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    info = dwm.dwm_bwd_filter_plan_info(plan)
+    xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+    ws = torch.empty(dwm.dwm_bwd_filter_workspace_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+    dw = torch.empty((L.K, L.C, L.R, L.S), dtype=torch.float32, device="cuda")
+    dwm.dwm_bwd_filter_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(args.warmup):
+        dwm.dwm_conv_backward_filter(plan, xd.data_ptr(), dyd.data_ptr(), dw.data_ptr(), st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dwm.dwm_conv_backward_filter(plan, xd.data_ptr(), dyd.data_ptr(), dw.data_ptr(), st)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    out = {
+        "metric": "direct-conv-equivalent TFLOP/s of the DWM filter gradient (fp32, 1 GPU); MSE vs FP64 definition",
+        "value": info.direct_flops / dt / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": L.name + "_backward_filter", "planes": info.n_planes, "tiles": info.n_tiles,
+                   "splits": info.splits, "direct_GFLOP": info.direct_flops / 1e9,
+                   "winograd_GFLOP": info.winograd_flops / 1e9, "workspace_MB": ws.numel() * 4 / 1e6},
+        "roofline": {"kernel": "wgrad_gemm_kernel (whole step timed)", "bound": "mfma",
+                     "achieved": info.winograd_flops / dt / 1e12, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
+                     "frac": info.winograd_flops / dt / 1e12 / PEAK_MFMA_F32, "traffic": None},
+    }
+    if not args.no_check:
+        import oracle
+        ks = sorted({0, L.K - 1})
+        ref = oracle.backward_filter_f64(x, np.ascontiguousarray(dy[:, ks]), (len(ks), L.C, L.R, L.S), L.stride, L.pad)
+        g = dw.cpu().numpy()[ks].astype(np.float64)
+        mse = float(np.mean((g - ref) ** 2))
+        out["accuracy"] = {"max_rel_err": float(np.max(np.abs(g - ref)) / np.max(np.abs(ref))),
+                           "mse_vs_fp64": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
+                           "checked_filters": len(ks)}
+    dwm.dwm_bwd_filter_plan_destroy(plan)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -132,6 +183,8 @@ def main():
     ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
     ap.add_argument("--backward-data", action="store_true",
                     help="time the gradient with respect to the input of the same layer instead of the forward pass")
+    ap.add_argument("--backward-filter", action="store_true",
+                    help="time the gradient with respect to the filter of the same layer instead of the forward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -158,6 +211,8 @@ def main():
 
     if args.backward_data:
         return bench_backward_data(args, L, x, w)
+    if args.backward_filter:
+        return bench_backward_filter(args, L, x, w)
 
     plan = dwm.dwm_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     info = dwm.dwm_plan_info(plan)

@@ -246,6 +246,36 @@ DWM_API dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* pl
 DWM_API dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float* dy_dev,
                                             const float* Ugw_dev, float* dx_dev, void* stream);
 
+/*
+ * Gradient with respect to the filter (the paper's backward pass: Sec. 3.1 eq. 5, second
+ * formula, per Winograd unit; Sec. 4.2 eq. 18 for the decomposition):
+ *     dw[k,c,r,q] = sum_{n,oh,ow} dy[n,k,oh,ow] * xp[n,c,oh*stride+r,ow*stride+q]
+ * computed part by part as dg = G^T [ sum over tiles of (A dY A^T) .* V ] G with V = B^T d B the
+ * forward pass's transformed input; the sum over tiles is a GEMM per Winograd-domain plane.
+ * dw [K][C][R][S] is fully overwritten; results do not vary from run to run.
+ * The plan takes the forward layer's shape; the workspace (dwm_bwd_filter_workspace_bytes,
+ * 256-byte aligned) holds V, A dY A^T and the partial sums.  Conventions as for the forward calls.
+ */
+typedef struct dwm_bwd_filter_plan dwm_bwd_filter_plan_t;
+
+typedef struct {
+    int n_planes;          /* Winograd-domain planes = GEMMs */
+    int n_tiles;           /* 64x64 output tiles over all planes */
+    int splits;            /* ranges the tile axis (the reduction) is cut into */
+    double direct_flops;   /* 2*N*K*C*R*S*OH*OW */
+    double winograd_flops; /* 2*mults_per_tile*C*K*T, as in the forward pass */
+} dwm_bwd_filter_info_t;
+
+DWM_API dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int C, int H, int W, int K,
+                                                int R, int S, int stride, int pad);
+DWM_API dwm_status_t dwm_bwd_filter_plan_destroy(dwm_bwd_filter_plan_t* plan);
+DWM_API dwm_status_t dwm_bwd_filter_plan_info(const dwm_bwd_filter_plan_t* plan, dwm_bwd_filter_info_t* info);
+DWM_API size_t dwm_bwd_filter_workspace_bytes(const dwm_bwd_filter_plan_t* plan);
+DWM_API dwm_status_t dwm_bwd_filter_set_workspace(dwm_bwd_filter_plan_t* plan, void* ws_dev, size_t bytes);
+/* x_dev [N][C][H][W], dy_dev [N][K][OH][OW], dw_dev [K][C][R][S]. */
+DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const float* x_dev,
+                                              const float* dy_dev, float* dw_dev, void* stream);
+
 DWM_API const char* dwm_status_string(dwm_status_t status);
 
 #ifdef __cplusplus

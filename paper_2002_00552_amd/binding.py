@@ -59,6 +59,11 @@ class dwm_bwd_phase_t(ctypes.Structure):
                                             "count_h", "count_w", "has_subconv")]
 
 
+class dwm_bwd_filter_info_t(ctypes.Structure):
+    _fields_ = [("n_planes", ctypes.c_int), ("n_tiles", ctypes.c_int), ("splits", ctypes.c_int),
+                ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double)]
+
+
 _P = ctypes.c_void_p
 _I = ctypes.c_int
 _SIGNATURES = {
@@ -88,6 +93,12 @@ _SIGNATURES = {
     "dwm_bwd_data_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
     "dwm_bwd_data_filter_transform": (_I, [_P, _P, _P, _P]),
     "dwm_conv_backward_data": (_I, [_P, _P, _P, _P, _P]),
+    "dwm_bwd_filter_plan_create": (_I, [ctypes.POINTER(_P)] + [_I] * 9),
+    "dwm_bwd_filter_plan_destroy": (_I, [_P]),
+    "dwm_bwd_filter_plan_info": (_I, [_P, ctypes.POINTER(dwm_bwd_filter_info_t)]),
+    "dwm_bwd_filter_workspace_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_bwd_filter_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
+    "dwm_conv_backward_filter": (_I, [_P, _P, _P, _P, _P]),
 }
 EXPORTS = sorted(_SIGNATURES)
 
@@ -236,3 +247,32 @@ def dwm_bwd_data_filter_transform(plan, w_dev, Ugw_dev, stream=None):
 
 def dwm_conv_backward_data(plan, dy_dev, Ugw_dev, dx_dev, stream=None):
     _check(lib().dwm_conv_backward_data(plan, dy_dev, Ugw_dev, dx_dev, stream), "dwm_conv_backward_data")
+
+
+def dwm_bwd_filter_plan_create(N, C, H, W, K, R, S, stride, pad):
+    h = _P()
+    _check(lib().dwm_bwd_filter_plan_create(ctypes.byref(h), N, C, H, W, K, R, S, stride, pad),
+           "dwm_bwd_filter_plan_create")
+    return h
+
+
+def dwm_bwd_filter_plan_destroy(plan):
+    _check(lib().dwm_bwd_filter_plan_destroy(plan), "dwm_bwd_filter_plan_destroy")
+
+
+def dwm_bwd_filter_plan_info(plan):
+    info = dwm_bwd_filter_info_t()
+    _check(lib().dwm_bwd_filter_plan_info(plan, ctypes.byref(info)), "dwm_bwd_filter_plan_info")
+    return info
+
+
+def dwm_bwd_filter_workspace_bytes(plan):
+    return int(lib().dwm_bwd_filter_workspace_bytes(plan))
+
+
+def dwm_bwd_filter_set_workspace(plan, ws_dev, nbytes):
+    _check(lib().dwm_bwd_filter_set_workspace(plan, ws_dev, nbytes), "dwm_bwd_filter_set_workspace")
+
+
+def dwm_conv_backward_filter(plan, x_dev, dy_dev, dw_dev, stream=None):
+    _check(lib().dwm_conv_backward_filter(plan, x_dev, dy_dev, dw_dev, stream), "dwm_conv_backward_filter")

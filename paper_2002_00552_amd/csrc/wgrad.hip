@@ -1,0 +1,369 @@
+// Gradient of the DWM convolution with respect to its filter (paper Sec. 3.1 eq. 5, second
+// formula, and Sec. 4.2 eq. 18): for every part
+//     dg = G^T [ sum over tiles and images of (A dY A^T) .* V ] G,      V = B^T d B,
+// and a part's dg lands on the taps the part was cut from.
+//
+// Steps, all on the caller's stream:
+//   1. V: the forward pass's input transform of x (same kernel, same layout, blocked by 64 tiles).
+//   2. dM = A dY A^T for every plane: the plane's 0/+-1 output pattern applied to the 2x2 block of
+//      dy -- the transpose of the forward pass's fold -- written in V's blocked layout,
+//      dM[block][plane][k][64 tiles].
+//   3. Per plane, dU[k][l] = sum_t dM[k][t] * V[l][t]: a GEMM whose reduction runs over the tiles.
+//      fp32 MFMA (32x32x2), 64x64 output tile per workgroup; both operand tiles are "row x 64
+//      consecutive tiles", 16 KB contiguous each, brought in by global->LDS DMA with the rows'
+//      16-byte groups XOR-swizzled so that the lanes' 16-byte reads do not collide.  The tile
+//      axis is cut into `splits` ranges to fill the chip; every range writes its own partial dU.
+//   4. The partial dU are summed in a fixed order and G^T (.) G is applied: every tap of dw is
+//      written exactly once (the parts partition the taps), nothing is accumulated atomically,
+//      results do not vary from run to run.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <new>
+
+#include "dma.hpp"
+#include "plan.hpp"
+
+namespace dwm {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct WgradArgs {
+    int K, Kp, T, tblocks;       // filters, filters rounded up to 64, tiles, blocks of 64 tiles
+    int dm_rows, vblock_rows;    // rows of one dM block / one V block
+    int n_planes, n_tiles;
+    int splits, chunks_per_split;
+    long long split_floats;      // floats of one split's partial dU
+    int tile0[kMaxPlanes + 1];   // first output tile of each plane
+    int nlt[kMaxPlanes];         // 64-wide l tiles of each plane
+    int vrow[kMaxPlanes];        // first V row of each plane
+    int poff64[kMaxPlanes];      // offset of the plane's dU[Kp][Lp64] inside a split, in units of 64 floats
+};
+
+// ---- step 2: dM[block][plane*Kp + k][t] = sum_q pattern_p[q] * dy[n][k][2ty+a][2tx+b] ----
+struct DyShape {
+    int T, K, Kp, TH, TW, OH, OW, dm_rows;
+};
+__global__ __launch_bounds__(256) void wgrad_dy_transform_kernel(DyShape P, PlaneTable PT,
+                                                                 const float* __restrict__ dy, float* __restrict__ dM)
+{
+    const DyShape& A = P;
+    const int blk = blockIdx.x;
+    const int t = blk * 64 + (threadIdx.x & 63);
+    const int k = blockIdx.y * 4 + (threadIdx.x >> 6);
+    float g[4] = {0.f, 0.f, 0.f, 0.f};
+    if (t < P.T && k < P.K) {
+        const int tiles = P.TH * P.TW;
+        const int n = t / tiles, rem = t - n * tiles;
+        const int ty = rem / P.TW, tx = rem - ty * P.TW;
+        const float* yp = dy + (((size_t)n * P.K + k) * P.OH + 2 * ty) * P.OW + 2 * tx;
+        const bool r1 = 2 * ty + 1 < P.OH, c1 = 2 * tx + 1 < P.OW;
+        g[0] = yp[0];
+        if (c1) g[1] = yp[1];
+        if (r1) g[2] = yp[P.OW];
+        if (r1 && c1) g[3] = yp[P.OW + 1];
+    }
+    // rows k >= K and columns t >= T are written as zeros: the GEMM multiplies them
+    float* out = dM + ((size_t)blk * A.dm_rows + k) * 64 + (threadIdx.x & 63);
+    for (int p = 0; p < PT.n; ++p) {
+        const int coef = PT.e[p].coef;
+        float v = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int cq = (coef >> (2 * q)) & 3;
+            v += cq == 1 ? g[q] : cq == 3 ? -g[q] : 0.f;
+        }
+        out[(size_t)p * A.Kp * 64] = v;
+    }
+}
+
+// columns past the last tile of the last V block: zeros (the forward pass leaves them unwritten)
+__global__ __launch_bounds__(256) void wgrad_zero_tail_kernel(float* __restrict__ V, int rows, int first_col)
+{
+    const int ncol = 64 - first_col;
+    const size_t total = (size_t)rows * ncol;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256)
+        V[(e / ncol) * 64 + first_col + (e % ncol)] = 0.f;
+}
+
+// ---- step 3: partial dU of one 64x64 tile of one plane over one range of tile blocks ----
+template <int NS>
+__global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradArgs A, const float* __restrict__ dM,
+                                                            const float* __restrict__ V, float* __restrict__ partial)
+{
+    constexpr int TILE = 64 * 64, STAGE = 2 * TILE;  // floats: dM tile + V tile
+    constexpr int N_DMA = 8;                         // per wave and chunk: 4 for each tile
+    static_assert(NS >= 2 && (NS - 2) * N_DMA < 64, "ring depth");
+    extern __shared__ __attribute__((aligned(1024))) float smem[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int li = lane & 31, lh = lane >> 5;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+
+    // which tile, which range of blocks
+    const int tile = blockIdx.x % A.n_tiles, split = blockIdx.x / A.n_tiles;
+    int p = 0;
+    while (p + 1 < A.n_planes && tile >= A.tile0[p + 1]) ++p;
+    const int r = tile - A.tile0[p];
+    const int kt = r / A.nlt[p], lt = r - kt * A.nlt[p];
+    const int c0 = split * A.chunks_per_split, c1 = min(c0 + A.chunks_per_split, A.tblocks);
+    const int nit = c1 - c0;
+
+    // this wave's DMA sources: rows of 64 floats, 16-byte group cp of row `row` goes to slot cp,
+    // fetched from group cp ^ (row & 15)
+    const float* pa[4];
+    const float* pb[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int s = (wave * 4 + q) * 64 + lane;
+        const int row = s >> 4, cp = s & 15;
+        const int off = row * 64 + ((cp ^ (row & 15)) << 2);
+        pa[q] = dM + ((size_t)c0 * A.dm_rows + (size_t)p * A.Kp + kt * 64) * 64 + off;
+        pb[q] = V + ((size_t)c0 * A.vblock_rows + A.vrow[p] + lt * 64) * 64 + off;
+    }
+    const size_t stepA = (size_t)A.dm_rows * 64, stepB = (size_t)A.vblock_rows * 64;
+    int istage = 0, ileft = nit;
+    auto issue_chunk = [&]() {
+        const uint32_t sa = lds0 + (uint32_t)(istage * STAGE * 4);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dma16(pa[q], sa + (wave * 4 + q) * 1024);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dma16(pb[q], sa + TILE * 4 + (wave * 4 + q) * 1024);
+        istage = istage + 1 == NS ? 0 : istage + 1;
+        if (--ileft > 0) {  // the last chunk is simply loaded again: the counts stay uniform
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                pa[q] += stepA;
+                pb[q] += stepB;
+            }
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue_chunk();
+
+    floatx16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    const int swz = li & 15;
+    int stage = 0;
+    for (int it = 0; it < nit; ++it) {
+        wait_vmcnt<(NS - 2) * N_DMA>();
+        __syncthreads();
+        // chunk it has landed and every wave is done with the stage chunk it-1 was read from:
+        // that stage is refilled while this chunk is multiplied
+        issue_chunk();
+        const float* as = smem + stage * STAGE + (wave_m * 32 + li) * 64;
+        const float* bs = smem + stage * STAGE + TILE + (wave_n * 32 + li) * 64;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            const float4 a4 = *reinterpret_cast<const float4*>(as + (((2 * g + lh) ^ swz) << 2));
+            const float4 b4 = *reinterpret_cast<const float4*>(bs + (((2 * g + lh) ^ swz) << 2));
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+        }
+        stage = stage + 1 == NS ? 0 : stage + 1;
+    }
+    wait_vmcnt<0>();
+
+    // lane holds column l = li and rows k = 8*(e/4) + 4*lh + e%4 of its 32x32 block
+    const int Lp64 = A.nlt[p] * 64;
+    float* out = partial + (size_t)split * A.split_floats + (size_t)A.poff64[p] * 64 +
+                 (size_t)(kt * 64 + wave_m * 32) * Lp64 + lt * 64 + wave_n * 32 + li;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) out[(size_t)(8 * (e >> 2) + 4 * lh + (e & 3)) * Lp64] = acc[e];
+}
+
+// ---- step 4: dw = G^T (sum of partial dU) G, one thread per (row of a class, filter) ----
+__device__ __forceinline__ float gt_col(int l, int a, const float u[4])
+{
+    if (l == 3) return a == 0 ? u[0] + 0.5f * (u[1] + u[2]) : a == 1 ? 0.5f * (u[1] - u[2]) : 0.5f * (u[1] + u[2]) + u[3];
+    if (l == 2) return a == 0 ? u[0] + u[1] : u[1] + u[2];
+    return u[0] + u[1];
+}
+
+__global__ __launch_bounds__(256) void wgrad_final_kernel(DevPlan P, WgradArgs A, const float* __restrict__ partial,
+                                                          float* __restrict__ dw)
+{
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    const int k = blockIdx.y;
+    if (row >= P.rows_total) return;
+    int qi = 0;
+    while (qi + 1 < P.ncls && row >= P.cls[qi + 1].row0) ++qi;
+    const DevClass q = P.cls[qi];
+    const int l = row - q.row0;
+    if (l >= q.L) return;
+    const int slot = l / P.C, c = l - slot * P.C;
+    const int ai = slot / q.wn, bi = slot - ai * q.wn;
+    const DevPiece hp = P.ph[q.h0 + ai], wp = P.pw[q.w0 + bi];
+    const int tw = q.lw + 1;
+    float u[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v = 0.f;
+            if (i <= q.lh && j <= q.lw) {
+                const int p = q.plane0 + i * tw + j;
+                const float* src = partial + (size_t)A.poff64[p] * 64 + (size_t)k * (A.nlt[p] * 64) + l;
+                for (int s = 0; s < A.splits; ++s) v += src[(size_t)s * A.split_floats];
+            }
+            u[i][j] = v;
+        }
+    // columns (G_h^T u), then rows ((.) G_w)
+    float t[3][4];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float col[4] = {u[0][j], u[1][j], u[2][j], u[3][j]};
+            t[a][j] = a < q.lh ? gt_col(q.lh, a, col) : 0.f;
+        }
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b)
+            if (a < q.lh && b < q.lw) {
+                const int r = P.s * (hp.j + a) + hp.p, s2 = P.s * (wp.j + b) + wp.p;
+                dw[(((size_t)k * P.C + c) * P.R + r) * P.S + s2] = gt_col(q.lw, b, t[a]);
+            }
+}
+
+}  // namespace dwm
+
+struct dwm_bwd_filter_plan {
+    dwm_plan_t* fwd;
+    dwm::WgradArgs a;
+    size_t fwd_ws_bytes, dm_bytes, partial_bytes;
+    float* ws;
+};
+
+extern "C" {
+
+dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                                        int stride, int pad)
+{
+    using namespace dwm;
+    if (!out) return DWM_ERR_INVALID_ARG;
+    dwm_plan_t* fwd = nullptr;
+    const dwm_status_t st = dwm_plan_create(&fwd, N, C, H, W, K, R, S, stride, pad);
+    if (st != DWM_OK) return st;
+    dwm_bwd_filter_plan* bp = new (std::nothrow) dwm_bwd_filter_plan;
+    if (!bp) {
+        dwm_plan_destroy(fwd);
+        return DWM_ERR_ALLOC;
+    }
+    bp->fwd = fwd;
+    bp->ws = nullptr;
+    WgradArgs& a = bp->a;
+    a = WgradArgs{};
+    const DevPlan& d = fwd->d;
+    a.K = K; a.Kp = (K + 63) / 64 * 64; a.T = d.T; a.tblocks = (d.T + 63) / 64;
+    a.n_planes = fwd->planes.n;
+    a.dm_rows = a.n_planes * a.Kp;
+    a.vblock_rows = d.vblock_rows;
+    long long tiles = 0, floats64 = 0;
+    for (int p = 0; p < a.n_planes; ++p) {
+        const DevPlaneEntry& e = fwd->planes.e[p];
+        a.nlt[p] = (e.Lpad + 63) / 64;
+        a.vrow[p] = (int)e.v_off64;
+        a.tile0[p] = (int)tiles;
+        a.poff64[p] = (int)floats64;
+        tiles += (long long)(a.Kp / 64) * a.nlt[p];
+        floats64 += (long long)a.Kp * a.nlt[p];
+    }
+    a.tile0[a.n_planes] = (int)tiles;
+    a.n_tiles = (int)tiles;
+    a.split_floats = floats64 * 64;
+    // enough workgroups for two per CU, but never fewer than four blocks of tiles per range
+    long long splits = (2 * kNumCUs + tiles - 1) / tiles;
+    splits = std::max(1LL, std::min<long long>(splits, (a.tblocks + 3) / 4));
+    a.chunks_per_split = (int)((a.tblocks + splits - 1) / splits);
+    a.splits = (a.tblocks + a.chunks_per_split - 1) / a.chunks_per_split;
+    const long long lim = (1LL << 31) - 1;
+    if (tiles * a.splits > lim || a.split_floats > lim * 16 || (long long)a.tblocks * a.dm_rows > lim) {
+        dwm_plan_destroy(fwd);
+        delete bp;
+        return DWM_ERR_UNSUPPORTED;
+    }
+    // V, then 64 rows of slack (the last plane's 64-row tile may overhang its rows), dM, partial dU
+    bp->fwd_ws_bytes = (dwm_plan_workspace_bytes(fwd) + (size_t)64 * 64 * sizeof(float) + 255) / 256 * 256;
+    bp->dm_bytes = ((size_t)a.tblocks * a.dm_rows * 64 * sizeof(float) + 255) / 256 * 256;
+    bp->partial_bytes = (size_t)a.splits * a.split_floats * sizeof(float);
+    *out = bp;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_bwd_filter_plan_destroy(dwm_bwd_filter_plan_t* plan)
+{
+    if (!plan) return DWM_ERR_INVALID_ARG;
+    dwm_plan_destroy(plan->fwd);
+    delete plan;
+    return DWM_OK;
+}
+
+dwm_status_t dwm_bwd_filter_plan_info(const dwm_bwd_filter_plan_t* plan, dwm_bwd_filter_info_t* info)
+{
+    if (!plan || !info) return DWM_ERR_INVALID_ARG;
+    info->n_planes = plan->a.n_planes;
+    info->n_tiles = plan->a.n_tiles;
+    info->splits = plan->a.splits;
+    info->direct_flops = plan->fwd->info.direct_flops;
+    info->winograd_flops = plan->fwd->info.winograd_flops;
+    return DWM_OK;
+}
+
+size_t dwm_bwd_filter_workspace_bytes(const dwm_bwd_filter_plan_t* plan)
+{
+    return plan ? plan->fwd_ws_bytes + plan->dm_bytes + plan->partial_bytes : 0;
+}
+
+dwm_status_t dwm_bwd_filter_set_workspace(dwm_bwd_filter_plan_t* plan, void* ws_dev, size_t bytes)
+{
+    if (!plan) return DWM_ERR_INVALID_ARG;
+    if (!ws_dev || ((uintptr_t)ws_dev & 255u) || bytes < dwm_bwd_filter_workspace_bytes(plan)) return DWM_ERR_WORKSPACE;
+    const dwm_status_t st = dwm_plan_set_workspace(plan->fwd, ws_dev, plan->fwd_ws_bytes);
+    if (st != DWM_OK) return st;
+    plan->ws = static_cast<float*>(ws_dev);
+    return DWM_OK;
+}
+
+dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const float* x_dev, const float* dy_dev,
+                                      float* dw_dev, void* stream)
+{
+    using namespace dwm;
+    if (!plan || !x_dev || !dy_dev || !dw_dev) return DWM_ERR_INVALID_ARG;
+    if (!plan->ws) return DWM_ERR_WORKSPACE;
+    const WgradArgs& a = plan->a;
+    const DevPlan& d = plan->fwd->d;
+    hipStream_t s = (hipStream_t)stream;
+    float* V = plan->ws;
+    float* dM = plan->ws + plan->fwd_ws_bytes / sizeof(float);
+    float* partial = dM + plan->dm_bytes / sizeof(float);
+    // 1. V = B^T d B (and zeros in the columns past the last tile)
+    dwm_status_t st = dwm_input_transform(plan->fwd, x_dev, stream);
+    if (st != DWM_OK) return st;
+    if (d.T & 63) {
+        hipLaunchKernelGGL(wgrad_zero_tail_kernel, dim3(64), dim3(256), 0, s,
+                           V + (size_t)(a.tblocks - 1) * a.vblock_rows * 64, a.vblock_rows, d.T & 63);
+    }
+    // 2. dM = A dY A^T
+    const DyShape ds{d.T, d.K, a.Kp, d.TH, d.TW, d.OH, d.OW, a.dm_rows};
+    hipLaunchKernelGGL(wgrad_dy_transform_kernel, dim3(a.tblocks, a.Kp / 4), dim3(256), 0, s, ds, plan->fwd->planes,
+                       dy_dev, dM);
+    // 3. partial dU
+    constexpr int NS = 2;
+    constexpr int lds_bytes = NS * 2 * 64 * 64 * 4;
+    auto kernel = wgrad_gemm_kernel<NS>;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (attr != hipSuccess) return DWM_ERR_HIP;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.n_tiles * a.splits)), dim3(256), lds_bytes, s, a, dM, V, partial);
+    // 4. dw = G^T (sum) G
+    hipLaunchKernelGGL(wgrad_final_kernel, dim3((d.rows_total + 255) / 256, d.K), dim3(256), 0, s, d, a, partial, dw_dev);
+    return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
+}
+
+}  // extern "C"

@@ -142,3 +142,86 @@ def test_backward_data_benchmark_layers_full_size(index):
     ref = oracle.backward_data_f64_at(dy, w, (L.N, L.C, L.H, L.W), L.stride, L.pad, idx)
     got = dx.ravel()[idx].astype(np.float64)
     assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= TOL, L.name
+
+
+# ---- gradient with respect to the filter ----
+
+class WgradRunner:
+    def __init__(self, N, C, H, W, K, R, S, stride, pad):
+        self.plan = dwm.dwm_bwd_filter_plan_create(N, C, H, W, K, R, S, stride, pad)
+        dev = torch.device("cuda:0")
+        self.ws = torch.full((dwm.dwm_bwd_filter_workspace_bytes(self.plan) // 4,), float("nan"),
+                             dtype=torch.float32, device=dev)
+        dwm.dwm_bwd_filter_set_workspace(self.plan, self.ws.data_ptr(), self.ws.numel() * 4)
+        self.dw = torch.full((K, C, R, S), float("nan"), dtype=torch.float32, device=dev)
+
+    def run(self, x, dy):
+        st = torch.cuda.current_stream().cuda_stream
+        self.x = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        self.dy = torch.from_numpy(np.ascontiguousarray(dy)).cuda()
+        dwm.dwm_conv_backward_filter(self.plan, self.x.data_ptr(), self.dy.data_ptr(), self.dw.data_ptr(), st)
+        torch.cuda.synchronize()
+        return self.dw.cpu().numpy()
+
+    def close(self):
+        dwm.dwm_bwd_filter_plan_destroy(self.plan)
+
+
+def _rand_xdy(N, C, H, W, K, R, S, s, P, seed):
+    rng = np.random.default_rng(seed)
+    OH, OW = (H + 2 * P - R) // s + 1, (W + 2 * P - S) // s + 1
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    dy = rng.uniform(-1, 1, (N, K, OH, OW)).astype(np.float32)
+    return x, dy
+
+
+WSHAPES = SHAPES + [
+    (70, 2, 6, 6, 3, 3, 3, 1, 1),        # many images: the tile axis spans several blocks and ranges
+    (3, 5, 31, 33, 7, 5, 5, 1, 2),       # tile count not a multiple of 64: the zeroed tail columns
+    (2, 66, 12, 12, 67, 3, 3, 1, 1),     # channels and filters just past a 64 tile
+]
+
+
+@pytest.mark.parametrize("shape", WSHAPES)
+def test_backward_filter_matches_fp64_definition(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    x, dy = _rand_xdy(*shape, seed=700 + R * 7 + S)
+    ref = oracle.backward_filter_f64(x, dy, (K, C, R, S), s, P)
+    r = WgradRunner(*shape)
+    dw = r.run(x, dy)
+    r.close()
+    assert np.all(np.isfinite(dw))  # every tap written
+    assert _relerr(dw, ref) <= TOL, shape
+
+
+def test_backward_filter_is_deterministic_and_plan_reusable():
+    shape = (4, 8, 21, 20, 9, 5, 5, 2, 2)
+    x, dy = _rand_xdy(*shape, seed=6)
+    r = WgradRunner(*shape)
+    a = r.run(x, dy).copy()
+    r.dw.fill_(float("nan"))
+    b = r.run(x, dy).copy()
+    assert np.array_equal(a, b)
+    x2 = (x * 0.5).astype(np.float32)
+    c = r.run(x2, dy)
+    assert _relerr(c, oracle.backward_filter_f64(x2, dy, (9, 8, 5, 5), 2, 2)) <= TOL
+    r.close()
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
+def test_backward_filter_benchmark_layers_full_size(index):
+    """Whole layer on the GPU.  The oracle's definition costs the layer's full flop count, so it
+    computes the filter gradient of a handful of filters only (dw of filter k needs dy[:, k] alone),
+    the first and the last among them."""
+    L = wl.CONFIGS[index]
+    x, _ = wl.make_layer_tensors(L, index)
+    OH, OW = wl.out_hw(L)
+    dy = np.random.default_rng(4100 + index).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
+    r = WgradRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    dw = r.run(x, dy)
+    r.close()
+    assert dw.shape == (L.K, L.C, L.R, L.S) and np.all(np.isfinite(dw))
+    ks = sorted({0, L.K - 1, L.K // 2})[: (3 if index != 2 else 2)]
+    ref = oracle.backward_filter_f64(x, np.ascontiguousarray(dy[:, ks]), (len(ks), L.C, L.R, L.S), L.stride, L.pad)
+    got = dw[ks].astype(np.float64)
+    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= TOL, L.name
