@@ -416,8 +416,12 @@ bool fused_setup(const dwm_plan& p, FusedArgs* out)
     const DevPlan& d = p.d;
     FusedArgs f{};
     if (d.C > 127 || d.nh > 15 || d.nw > 15) return false;
-    // classes = pairs of families; inside a class, groups of equal (len_h, len_w), rows padded to 4
+    // classes = pairs of families; inside a class the rows (part, channel) follow each other sorted by
+    // (len_h, len_w), longest first, and only the class's end is padded to a multiple of four.  A step
+    // whose four rows mix piece lengths runs the planes of the longest: the shorter pieces' rows hold
+    // zeros in the filter copy for the frequencies they lack.
     int rows = 0, steps = 0;
+    int row_lh[kFusedMaxRows], row_lw[kFusedMaxRows];
     for (int wh = 1; wh >= 0; --wh)
         for (int ww = 1; ww >= 0; --ww) {
             FusedClass fc{};
@@ -427,31 +431,33 @@ bool fused_setup(const dwm_plan& p, FusedArgs* out)
             for (int lh = 3; lh >= 1; --lh)
                 for (int lw = 3; lw >= 1; --lw) {
                     if ((lh >= 2) != (wh == 1) || (lw >= 2) != (ww == 1)) continue;
-                    int first = -1, count = 0;
                     for (int a = 0; a < d.nh; ++a)
                         for (int b = 0; b < d.nw; ++b) {
                             if (d.ph[a].l != lh || d.pw[b].l != lw) continue;
                             for (int c = 0; c < d.C; ++c) {
                                 if (rows >= kFusedMaxRows) return false;
                                 f.rowdesc[rows] = (unsigned short)(a | b << 4 | c << 8 | 1 << 15);
-                                if (first < 0) first = rows;
-                                ++rows; ++count;
+                                row_lh[rows] = lh; row_lw[rows] = lw;
+                                ++rows;
                             }
                         }
-                    if (!count) continue;
-                    while (count & 3) {  // padding rows: a real row's offsets, zero filter rows
-                        if (rows >= kFusedMaxRows) return false;
-                        f.rowdesc[rows] = (unsigned short)(f.rowdesc[first] & 0x7fff);
-                        ++rows; ++count;
-                    }
-                    for (int sidx = 0; sidx < count / 4; ++sidx) {
-                        if (steps >= kFusedMaxSteps) return false;
-                        f.step_type[steps++] = lh * 4 + lw;
-                    }
                 }
+            if (rows == fc.row0) continue;
+            while ((rows - fc.row0) & 3) {  // padding rows: a real row's offsets, zero filter rows
+                if (rows >= kFusedMaxRows) return false;
+                f.rowdesc[rows] = (unsigned short)(f.rowdesc[rows - 1] & 0x7fff);
+                row_lh[rows] = row_lh[rows - 1]; row_lw[rows] = row_lw[rows - 1];
+                ++rows;
+            }
+            for (int r0 = fc.row0; r0 < rows; r0 += 4) {
+                if (steps >= kFusedMaxSteps) return false;
+                int mh = 0, mw = 0;
+                for (int r = r0; r < r0 + 4; ++r) { mh = std::max(mh, row_lh[r]); mw = std::max(mw, row_lw[r]); }
+                f.step_type[steps++] = mh * 4 + mw;
+            }
             fc.nsteps = steps - fc.step0;
             fc.rows = rows - fc.row0;
-            if (fc.nsteps) f.fc[f.nfc++] = fc;
+            f.fc[f.nfc++] = fc;
         }
     f.rows_total = rows;
 
@@ -497,12 +503,13 @@ bool fused_setup(const dwm_plan& p, FusedArgs* out)
     f.div_nphase.init((unsigned)f.nphase);
     for (int i = 0; i < kMaxPieces; ++i)
         for (int k = 0; k < 4; ++k) {
-            const int oh = i < d.nh ? d.s * (d.ph[i].j + k) + d.ph[i].p : 0;
-            const int ow = i < d.nw ? d.s * (d.pw[i].j + k) + d.pw[i].p : 0;
-            // offsets past the patch of a short piece are never used; keep them inside the region
-            f.roff[i][k] = std::min(oh, f.nrows - 1) * f.row_floats;
-            const int owc = std::min(ow, f.lw_in - 1);
-            f.coff[i][k] = (owc % f.nphase) * f.lwp + owc / f.nphase;
+            // offsets past a piece's own patch (k > its length) repeat its last element: they are read
+            // (the patch is always read 4 wide) and only ever multiplied by zeros, but must be finite
+            const int kh = i < d.nh ? std::min(k, d.ph[i].l) : 0, kw = i < d.nw ? std::min(k, d.pw[i].l) : 0;
+            const int oh = i < d.nh ? d.s * (d.ph[i].j + kh) + d.ph[i].p : 0;
+            const int ow = i < d.nw ? d.s * (d.pw[i].j + kw) + d.pw[i].p : 0;
+            f.roff[i][k] = oh * f.row_floats;
+            f.coff[i][k] = (ow % f.nphase) * f.lwp + ow / f.nphase;
         }
     f.lds_bytes = table_bytes + best_x;
     *out = f;
