@@ -9,6 +9,8 @@ compiles it with gcc on first use and exposes thin numpy wrappers:
 * ``direct_f64``            O1, the definition of the convolution (ground truth)
 * ``direct_f64_at``         O1 at sampled output positions
 * ``dwm_f64``               O2, the paper's five steps in FP64
+* ``dwm_half_f64``          O2 with binary16 storage of x, w, U and V (Table 1, "DWM FP16")
+* ``round_binary16``        nearest binary16 value of each double (ties to even)
 * ``backward_data_f64``     O1', the gradient with respect to the input, by definition
 * ``dwm_backward_data_f64`` O2', the same by the paper's backward formulas
 * ``backward_filter_f64``   O1'', the gradient with respect to the filter, by definition
@@ -40,7 +42,7 @@ def build(force=False):
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".%d.tmp" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-o", tmp, _SRC]
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-o", tmp, _SRC, "-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -122,6 +124,32 @@ def dwm_f64(x, w, stride, pad):
     rc = _load().oracle_dwm_f64(_fp(x), _fp(w), _dp(y), N, C, H, W, K, R, S, stride, pad)
     if rc:
         raise ValueError("oracle_dwm_f64: bad shape (rc=%d)" % rc)
+    return y
+
+
+def round_binary16(a):
+    """Each double rounded to the nearest IEEE binary16 value (ties to even), as float64."""
+    a = np.ascontiguousarray(a, np.float64)
+    out = np.empty_like(a)
+    _load().oracle_round_binary16(_dp(a), _dp(out), ctypes.c_longlong(a.size))
+    return out
+
+
+def dwm_half_f64(x, w, stride, pad):
+    """O2 with half-precision storage: x and w hold binary16 values (float16 arrays, or float32
+    arrays of such values); U and V are rounded to binary16 before the products; sums in FP64;
+    the FP64 result is returned unrounded."""
+    x = _f32(np.asarray(x).astype(np.float32))
+    w = _f32(np.asarray(w).astype(np.float32))
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C == C2
+    y = np.empty((N, K, out_size(H, R, stride, pad), out_size(W, S, stride, pad)), np.float64)
+    rc = _load().oracle_dwm_half_f64(_fp(x), _fp(w), _dp(y), N, C, H, W, K, R, S, stride, pad)
+    if rc == 3:
+        raise ValueError("oracle_dwm_half_f64: x and w must hold binary16 values")
+    if rc:
+        raise ValueError("oracle_dwm_half_f64: bad shape (rc=%d)" % rc)
     return y
 
 

@@ -19,6 +19,15 @@
  *                              size by the consecutive 3-tap cut of Sec. 4.1 "Large
  *                              kernel size" (eq. 8-11).
  *
+ *   O2h oracle_dwm_half_f64    O2 with half-precision storage (the "DWM FP16" column of
+ *                              Table 1): x and w hold binary16 values, the transformed
+ *                              filter U and the transformed input V are rounded to
+ *                              binary16 (nearest, ties to even) before they are
+ *                              multiplied; every sum is FP64 and the result is returned
+ *                              unrounded.  The paper does not say where its FP16
+ *                              implementation rounds; this reading is the one a matrix
+ *                              unit with FP16 operands and a wide accumulator computes.
+ *
  * and, for the gradient with respect to the input (the paper's backward pass, Sec. 3.1
  * eq. 5 and Sec. 4.2 eq. 16-17):
  *
@@ -37,6 +46,7 @@
  * the printed F(2,3) matrices, Table 3 multiplication counts, closed forms, a
  * library float64 convolution, brute force, and O2 == O1 to 1e-12).
  */
+#include <math.h>
 #include <stddef.h>
 #include <stdlib.h>
 #include <string.h>
@@ -325,8 +335,31 @@ int oracle_part_input_transform(const float* x, int C, int H, int W, int s, int 
 /* ------------------------------------------------------------------------- */
 /* O2: the whole method                                                       */
 /* ------------------------------------------------------------------------- */
-int oracle_dwm_f64(const float* x, const float* w, double* y,
-                   int N, int C, int H, int W, int K, int R, int S, int s, int P)
+/*
+ * The nearest IEEE binary16 value (ties to even; 11 significant bits, exponents -14..15,
+ * subnormals in steps of 2^-24, overflow to infinity from 65520 up), returned as a double.
+ */
+static double round_binary16(double v)
+{
+    if (v == 0.0 || v != v || isinf(v)) return v;
+    const double a = fabs(v);
+    if (a >= 65520.0) return v > 0 ? INFINITY : -INFINITY;
+    int e;
+    (void)frexp(a, &e);            /* a = m * 2^e, 0.5 <= m < 1: a lies in [2^(e-1), 2^e) */
+    int lsb = (e - 1) - 10;        /* weight of the last of 11 significant bits */
+    if (lsb < -24) lsb = -24;      /* subnormal range */
+    const double ulp = ldexp(1.0, lsb);
+    return copysign(nearbyint(a / ulp) * ulp, v); /* default rounding mode: ties to even */
+}
+
+int oracle_round_binary16(const double* in, double* out, long long n)
+{
+    for (long long i = 0; i < n; ++i) out[i] = round_binary16(in[i]);
+    return 0;
+}
+
+static int dwm_forward(const float* x, const float* w, double* y,
+                       int N, int C, int H, int W, int K, int R, int S, int s, int P, int half_storage)
 {
     if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 1;
     if (H + 2 * P < R || W + 2 * P < S) return 1;
@@ -350,10 +383,14 @@ int oracle_dwm_f64(const float* x, const float* w, double* y,
         const int th = pt->lh + 1, tw = pt->lw + 1;
         /* Transformation (kernel side): U = G g G^T. */
         rc = oracle_part_filter_transform(w, K, C, R, S, s, pt, U);
+        if (half_storage && !rc)
+            for (size_t i = 0; i < (size_t)K * C * th * tw; ++i) U[i] = round_binary16(U[i]);
         for (int n = 0; n < N && !rc; ++n) {
             /* Splitting (input side) + Transformation: V = B^T d B. */
             rc = oracle_part_input_transform(x, C, H, W, s, P, TH, TW, n, pt, V);
             if (rc) break;
+            if (half_storage)
+                for (size_t i = 0; i < (size_t)C * TH * TW * th * tw; ++i) V[i] = round_binary16(V[i]);
 #pragma omp parallel for schedule(static)
             for (int k = 0; k < K; ++k)
                 for (int ty = 0; ty < TH; ++ty)
@@ -389,6 +426,24 @@ int oracle_dwm_f64(const float* x, const float* w, double* y,
     }
     free(parts); free(U); free(V);
     return rc;
+}
+
+int oracle_dwm_f64(const float* x, const float* w, double* y,
+                   int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    return dwm_forward(x, w, y, N, C, H, W, K, R, S, s, P, 0);
+}
+
+/* O2h: x and w must hold binary16 values (checked); see the header for the rounding points. */
+int oracle_dwm_half_f64(const float* x, const float* w, double* y,
+                        int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1) return 1;
+    for (size_t i = 0; i < (size_t)N * C * H * W; ++i)
+        if (round_binary16((double)x[i]) != (double)x[i]) return 3;
+    for (size_t i = 0; i < (size_t)K * C * R * S; ++i)
+        if (round_binary16((double)w[i]) != (double)w[i]) return 3;
+    return dwm_forward(x, w, y, N, C, H, W, K, R, S, s, P, 1);
 }
 
 /* ------------------------------------------------------------------------- */

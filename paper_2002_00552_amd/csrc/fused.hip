@@ -531,8 +531,14 @@ dwm_status_t launch_fused_forward(const dwm_plan& p, const float* x, const float
     const FusedArgs& f = p.fused;
     auto kernel = f.nfc > 1 ? fused_forward_kernel<true> : fused_forward_kernel<false>;
     if (f.lds_bytes > 64 * 1024) {
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        // once for each instantiation, whichever of them the first plan happens to use
+        static const hipError_t attr = [] {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<true>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        }();
         if (attr != hipSuccess) return DWM_ERR_HIP;
     }
     dim3 grid((unsigned)(p.d.N * f.nbh * f.nbw), (unsigned)f.nkw), block(256);
