@@ -276,6 +276,48 @@ DWM_API dwm_status_t dwm_bwd_filter_set_workspace(dwm_bwd_filter_plan_t* plan, v
 DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const float* x_dev,
                                               const float* dy_dev, float* dw_dev, void* stream);
 
+/*
+ * Half-precision forward path: the "DWM FP16" setting of the paper's accuracy table (Table 1,
+ * discussed in Sec. 5.1).  x [N][C][H][W], w [K][C][R][S] and y [N][K][OH][OW] are dense IEEE
+ * binary16 (dwm_half_t = the 16-bit pattern).  The paper does not say where its FP16 version
+ * rounds; here the transformed filter U = G g G^T and the transformed input V = B^T d B are each
+ * rounded ONCE to binary16 (nearest, ties to even), their products are summed over channels and
+ * parts in FP32 on the FP16 matrix cores, the output transform is FP32 and y is rounded once.
+ * The kernel is cut exactly as eq. 8 writes it (3,3,...,remainder), so that the rounding points
+ * are those of the method as printed.
+ *
+ * Same conventions as the single-precision calls: the plan is host memory, every *_dev pointer is
+ * caller-owned device memory, kernels go to `stream`, nothing is allocated or synchronised, errors
+ * are return codes.  Workspace: dwm_f16_workspace_bytes, 256-byte aligned (V in binary16, partial
+ * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes.
+ * dwm_f16_set_variant(plan, "contract", v): v in 30..35 selects the contraction's tile shape
+ * (v < 0: the planner's choice); DWM_ERR_INVALID_ARG if it does not apply to the layer.
+ * dwm_f16_conv_forward_f32out is the same computation with y left in FP32 (not rounded): it
+ * exists so that tests can compare everything before the last rounding.
+ * dwm_f16_input_transform / dwm_f16_contract_output are the two stages of dwm_f16_conv_forward,
+ * exposed for timing.
+ */
+typedef struct dwm_f16_plan dwm_f16_plan_t;
+typedef unsigned short dwm_half_t;
+
+DWM_API dwm_status_t dwm_f16_plan_create(dwm_f16_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                                         int stride, int pad);
+DWM_API dwm_status_t dwm_f16_plan_destroy(dwm_f16_plan_t* plan);
+DWM_API dwm_status_t dwm_f16_plan_info(const dwm_f16_plan_t* plan, dwm_plan_info_t* info);
+DWM_API size_t dwm_f16_filter_bytes(const dwm_f16_plan_t* plan);
+DWM_API size_t dwm_f16_workspace_bytes(const dwm_f16_plan_t* plan);
+DWM_API dwm_status_t dwm_f16_set_workspace(dwm_f16_plan_t* plan, void* ws_dev, size_t bytes);
+DWM_API dwm_status_t dwm_f16_set_variant(dwm_f16_plan_t* plan, const char* stage, int variant);
+DWM_API dwm_status_t dwm_f16_filter_transform(const dwm_f16_plan_t* plan, const dwm_half_t* w_dev,
+                                              dwm_half_t* U_dev, void* stream);
+DWM_API dwm_status_t dwm_f16_conv_forward(const dwm_f16_plan_t* plan, const dwm_half_t* x_dev,
+                                          const dwm_half_t* U_dev, dwm_half_t* y_dev, void* stream);
+DWM_API dwm_status_t dwm_f16_conv_forward_f32out(const dwm_f16_plan_t* plan, const dwm_half_t* x_dev,
+                                                 const dwm_half_t* U_dev, float* y_dev, void* stream);
+DWM_API dwm_status_t dwm_f16_input_transform(const dwm_f16_plan_t* plan, const dwm_half_t* x_dev, void* stream);
+DWM_API dwm_status_t dwm_f16_contract_output(const dwm_f16_plan_t* plan, const dwm_half_t* U_dev,
+                                             dwm_half_t* y_dev, void* stream);
+
 DWM_API const char* dwm_status_string(dwm_status_t status);
 
 #ifdef __cplusplus

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdwm.so")
 PROBE_LIB = os.path.join(HERE, "libdwm_probe.so")
-SOURCES = ["plan.cpp", "transforms.hip", "contract.hip", "fused.hip", "backward.hip", "wgrad.hip"]
+SOURCES = ["plan.cpp", "transforms.hip", "contract.hip", "fused.hip", "backward.hip", "wgrad.hip", "half.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
@@ -25,7 +25,7 @@ def stale():
     t = os.path.getmtime(LIB)
     if not os.path.exists(PROBE_LIB):
         return True
-    deps = sources() + [os.path.join(CSRC, "probe.hip"), os.path.join(CSRC, "plan.hpp"), os.path.join(HERE, "..", "include", "dwm.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "dwm.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -283,6 +283,11 @@ dwm_status_t plan_from_spec(dwm_plan_t** out, const PlanSpec& sp)
     if (st == DWM_OK) *out = p;
     return st;
 }
+
+dwm_status_t plan_from_spec_as_printed(dwm_plan_t** out, const PlanSpec& sp)
+{
+    return plan_build(out, sp, false);
+}
 }  // namespace dwm
 
 extern "C" {
@@ -411,7 +416,7 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
         if (st != DWM_OK) plan->sk_mode = old_mode;
         return st;
     }
-    if (std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
+    if (std::strcmp(stage, "contract") || variant >= dwm::kFirstHalfVariant) return DWM_ERR_INVALID_ARG;
     dwm::ContractGeometry g;
     if (!dwm::contract_geometry(*plan, variant < 0 ? default_contract_variant(plan->lgran) : variant, &g))
         return DWM_ERR_INVALID_ARG;

@@ -86,7 +86,11 @@ constexpr ContractVariant kContractVariants[] = {
     {10, 2, 2, 1, 1, 16, 4}, {11, 2, 2, 1, 1, 32, 3}, {12, 2, 2, 1, 1, 64, 2}, {13, 4, 2, 1, 1, 32, 2},
     {14, 2, 4, 1, 1, 32, 3}, {15, 2, 2, 2, 1, 32, 2}, {16, 2, 2, 1, 2, 32, 2}, {17, 2, 2, 1, 1, 16, 2},
     {18, 2, 2, 1, 1, 32, 4}, {19, 2, 2, 1, 1, 64, 3},
+    // half-precision contraction (half.hip): ids 30 and up
+    {30, 2, 2, 1, 1, 16, 4}, {31, 2, 2, 1, 1, 32, 4}, {32, 2, 2, 1, 1, 64, 3}, {33, 2, 2, 1, 2, 32, 3},
+    {34, 2, 2, 2, 1, 32, 3}, {35, 2, 2, 1, 2, 64, 2},
 };
+constexpr int kFirstHalfVariant = 30;
 constexpr int kNumContractVariants = sizeof(kContractVariants) / sizeof(kContractVariants[0]);
 constexpr int kNumCUs = 256;  // MI355X
 
@@ -232,6 +236,8 @@ struct PlanSpec {
     OutMap om;
 };
 dwm_status_t plan_from_spec(dwm_plan_t** out, const PlanSpec& sp);
+// the same with the kernel cut exactly as eq. 8 writes it (3,3,...,remainder), staged path only
+dwm_status_t plan_from_spec_as_printed(dwm_plan_t** out, const PlanSpec& sp);
 // plan.cpp: geometry of a contraction variant for this plan; false if the variant does not apply
 bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out);
 // transforms.hip, contract.hip

@@ -8,53 +8,9 @@
 #include <algorithm>
 
 #include "plan.hpp"
+#include "xform.hpp"
 
 namespace dwm {
-
-// ---------------------------------------------------------------------------------
-// 1-D transforms, one row at a time
-// ---------------------------------------------------------------------------------
-
-// (G_l v)[i] for a piece of length l (v has l valid entries).
-__device__ __forceinline__ float g_row(int l, int i, float v0, float v1, float v2)
-{
-    if (l == 3) {
-        switch (i) {
-            case 0: return v0;
-            case 1: return 0.5f * (v0 + v1 + v2);
-            case 2: return 0.5f * (v0 - v1 + v2);
-            default: return v2;
-        }
-    }
-    if (l == 2) return i == 0 ? v0 : i == 1 ? v0 + v1 : v1;
-    return v0;
-}
-
-// (B_l^T d)[i] for a piece of length l (d has l+1 valid entries).
-template <int L>
-__device__ __forceinline__ void bt_apply(const float d[4], float out[4])
-{
-    if (L == 3) {
-        out[0] = d[0] - d[2];
-        out[1] = d[1] + d[2];
-        out[2] = d[2] - d[1];
-        out[3] = d[1] - d[3];
-    } else if (L == 2) {
-        out[0] = d[0] - d[1];
-        out[1] = d[1];
-        out[2] = d[2] - d[1];
-    } else {
-        out[0] = d[0];
-        out[1] = d[1];
-    }
-}
-
-__device__ __forceinline__ int find_class(const DevPlan& P, int row)
-{
-    int q = 0;
-    while (q + 1 < P.ncls && row >= P.cls[q + 1].row0) ++q;
-    return q;
-}
 
 // ---------------------------------------------------------------------------------
 // Filter transform: U = G_lh g G_lw^T for every part (Sec. 4.1 "Transformation")
