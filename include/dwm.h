@@ -291,7 +291,9 @@ DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan,
  * are return codes.  Workspace: dwm_f16_workspace_bytes, 256-byte aligned (V in binary16, partial
  * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes.
  * dwm_f16_set_variant(plan, "contract", v): v in 30..35 selects the contraction's tile shape
- * (v < 0: the planner's choice); DWM_ERR_INVALID_ARG if it does not apply to the layer.
+ * (v < 0: the planner's choice); (plan, "input", v): 0 = gather form of the input transform,
+ * 1 = LDS-staged form (C a multiple of 8 and a staged region that fits), v < 0: the planner's
+ * choice; DWM_ERR_INVALID_ARG if the variant does not apply to the layer.
  * dwm_f16_conv_forward_f32out is the same computation with y left in FP32 (not rounded): it
  * exists so that tests can compare everything before the last rounding.
  * dwm_f16_input_transform / dwm_f16_contract_output are the two stages of dwm_f16_conv_forward,

@@ -27,6 +27,8 @@
 namespace dwm {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float pfloat4 __attribute__((ext_vector_type(4)));
+typedef unsigned int puint4 __attribute__((ext_vector_type(4)));
 
 struct ContractArgs {
     int K, T, Kpad, Tpad;
@@ -319,43 +321,60 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
             const int g_first = (int)(((long long)trel * G.n_iter) / G.sk_ipw);
             const int g_last = (int)((((long long)trel + 1) * G.n_iter - 1) / G.sk_ipw);
             const int nc = g_last - g_first + 1;
-            float* slot0 = partial + (size_t)trel * G.sk_maxc * SLOT + tid;
-            float* mine = slot0 + (size_t)(gidx - g_first) * SLOT;
+            // partial outputs of this tile: [contributor][(block*4 + q)*4 + e/4][thread][4 floats], accessed
+            // as a raw buffer with device scope (the accesses complete, or are served, at the
+            // level all XCDs share) -- 16-byte accesses that the compiler is free to keep in flight
+            // together, which it is not for atomic loads
+            const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(
+                partial + (size_t)trel * G.sk_maxc * SLOT, 0, (int)((unsigned)G.sk_maxc * SLOT * 4u), 0x00020000);
+            constexpr int kDeviceScope = 16;  // cache-policy bits of the access: sc1 = device scope
+            const unsigned pvoff = (unsigned)tid * 16u;  // a wave's access is 1 KB contiguous
+            const unsigned mine = (unsigned)(gidx - g_first) * (unsigned)(SLOT * 4);
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        __hip_atomic_store(&mine[((blk * 4 + q) * 16 + e) * NT], Y[blk / WN][blk % WN][q][e],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // The partial output is written with device-scope stores (they complete at the level
-            // all XCDs share), so waiting for them -- not a flush of the whole L2 -- is all the
-            // release that the arrival count below needs.
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const floatx16& yv = Y[blk / WN][blk % WN][q];
+                        const pfloat4 v = {yv[4 * e4], yv[4 * e4 + 1], yv[4 * e4 + 2], yv[4 * e4 + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(puint4, v), prs, pvoff,
+                                                               mine + (unsigned)(((blk * 4 + q) * 4 + e4) * NT * 16),
+                                                               kDeviceScope);
+                    }
+            // waiting for the device-scope stores -- not a flush of the whole L2 -- is all the
+            // release that the arrival count below needs
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            wait_vmcnt<0>();
             __syncthreads();
             if (tid == 0) s_last = atomicAdd(&counters[trel], 1) == nc - 1;
             __syncthreads();
             store = s_last != 0;
             __syncthreads();  // s_last may be rewritten for the next segment
             if (store) {
-                // device-scope loads below bypass whatever this XCD's caches may hold
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
                 // sum all contributions (this workgroup's own included) in contributor order,
                 // so the result does not depend on which workgroup happened to arrive last
                 for (int c = 0; c < nc; ++c) {
-                    const float* src = slot0 + (size_t)c * SLOT;
+                    const unsigned soff = (unsigned)c * (unsigned)(SLOT * 4);
 #pragma unroll
-                    for (int blk = 0; blk < NBLK; ++blk)
+                    for (int blk = 0; blk < NBLK; ++blk) {
+                        pfloat4 v[16];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                        for (int i = 0; i < 16; ++i)
+                            v[i] = __builtin_bit_cast(
+                                pfloat4, __builtin_amdgcn_raw_buffer_load_b128(
+                                             prs, pvoff, soff + (unsigned)((blk * 16 + i) * NT * 16), kDeviceScope));
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) {
-                                const float v = __hip_atomic_load(&src[((blk * 4 + q) * 16 + e) * NT],
-                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                const float old = Y[blk / WN][blk % WN][q][e];
-                                Y[blk / WN][blk % WN][q][e] = c == 0 ? v : old + v;
+                        for (int i = 0; i < 16; ++i) {
+                            floatx16& yv = Y[blk / WN][blk % WN][i >> 2];
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const float old = yv[4 * (i & 3) + k];
+                                yv[4 * (i & 3) + k] = c == 0 ? v[i][k] : old + v[i][k];
                             }
+                        }
+                    }
                 }
                 if (tid == 0) counters[trel] = 0;  // ready for the next launch
             }

@@ -28,6 +28,8 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float pfloat4 __attribute__((ext_vector_type(4)));
+typedef unsigned int puint4 __attribute__((ext_vector_type(4)));
 
 // The binary16 value nearest to v, ties to even, in ONE rounding (a conversion through float
 // would round twice).  |v| is scaled so that binary16's last kept bit has weight one, rounded to
@@ -200,6 +202,140 @@ __global__ __launch_bounds__(256) void input_transform_f16_kernel(DevPlan P, con
         case 1 * 4 + 3: input_rows8_f16<1, 3>(P, q, x, V, l0, t); break;
         case 1 * 4 + 2: input_rows8_f16<1, 2>(P, q, x, V, l0, t); break;
         default: input_rows8_f16<1, 1>(P, q, x, V, l0, t); break;
+    }
+}
+
+
+// ---------------------------------------------------------------------------------
+// Input transform, LDS-staged form (layers whose channel count is a multiple of eight).
+//
+// A workgroup owns one 64-tile block of V (lane = tile) and `cg` input channels, a multiple of
+// eight.  Its four waves stage the input rows the block's tiles touch (coalesced binary16 loads,
+// widened to FP32 on the way to LDS, zero padding written explicitly, columns de-interleaved
+// modulo 2*stride so that the same patch element of adjacent tiles sits in adjacent LDS words).
+// After one barrier the work items (part, group of eight channels) are dealt to the waves: an
+// item reads its eight channels' patches from LDS, transforms them in FP32, rounds, and writes
+// one 16-byte word per plane and lane -- 1 KB contiguous per wave store.
+// ---------------------------------------------------------------------------------
+template <int LH, int LW>
+__device__ __forceinline__ void lds_part_rows8(const InLdsArgs& A, const float* __restrict__ xl,
+                                               half_t* __restrict__ vp, size_t plane, int hpiece, int wpiece,
+                                               bool valid)
+{
+    constexpr int TH_ = LH + 1, TW_ = LW + 1;
+    int ro[TH_], co[TW_];
+#pragma unroll
+    for (int i = 0; i < TH_; ++i) ro[i] = A.roff[hpiece][i];
+#pragma unroll
+    for (int j = 0; j < TW_; ++j) co[j] = A.coff[wpiece][j];
+    half2_t out[TH_ * TW_][4];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const float* xc = xl + c * A.chan_floats;
+        float d[TH_][TW_];
+#pragma unroll
+        for (int i = 0; i < TH_; ++i)
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) d[i][j] = xc[ro[i] + co[j]];
+        float tmp[4][4];
+#pragma unroll
+        for (int j = 0; j < TW_; ++j) {
+            float col[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+#pragma unroll
+            for (int i = 0; i < TH_; ++i) col[i] = d[i][j];
+            bt_apply<LH>(col, o);
+#pragma unroll
+            for (int i = 0; i < TH_; ++i) tmp[i][j] = o[i];
+        }
+#pragma unroll
+        for (int i = 0; i < TH_; ++i) {
+            float rowv[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) rowv[j] = tmp[i][j];
+            bt_apply<LW>(rowv, o);
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) out[i * TW_ + j][c >> 1][c & 1] = (half_t)o[j];
+        }
+    }
+    if (!valid) return;
+#pragma unroll
+    for (int pl = 0; pl < TH_ * TW_; ++pl) {
+        uint4 v;
+        v.x = __builtin_bit_cast(uint32_t, out[pl][0]);
+        v.y = __builtin_bit_cast(uint32_t, out[pl][1]);
+        v.z = __builtin_bit_cast(uint32_t, out[pl][2]);
+        v.w = __builtin_bit_cast(uint32_t, out[pl][3]);
+        *reinterpret_cast<uint4*>(vp + (size_t)pl * plane) = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void input_transform_f16_lds_kernel(DevPlan P, InLdsArgs A,
+                                                                      const half_t* __restrict__ x,
+                                                                      half_t* __restrict__ V,
+                                                                      int* __restrict__ counters, int n_counters)
+{
+    extern __shared__ __attribute__((aligned(16))) float xs16[];  // [cg][max_rows][nphase][lwp]
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int b = blockIdx.x;
+    const int bt = b / A.ncg, bc = b - bt * A.ncg;  // channel groups of one block run together: x rows meet in L2
+    const int c0 = bc * A.cg, cn = min(A.cg, P.C - c0);
+    const int t0 = bt * 64;
+    if (t0 >= P.T) return;  // a block of padding only (Tpad is rounded up to 256)
+    const int t1 = min(t0 + 63, P.T - 1);
+    const int s2 = 2 * P.s;
+    const int g0 = A.div_tw.div(t0), g1 = A.div_tw.div(t1);
+    const int n0 = A.div_th.div(g0), n1 = A.div_th.div(g1);
+    const int ty_a0 = g0 - n0 * P.TH, ty_b1 = g1 - n1 * P.TH;
+    const int rows0 = s2 * ((n1 == n0 ? ty_b1 : P.TH - 1) - ty_a0) + A.foot_h;
+
+    for (int cl = wave; cl < cn; cl += 4)
+        stage_channel<half_t>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, n0, n1, ty_a0, ty_b1, lane);
+    __syncthreads();
+
+    const int t = t0 + lane;
+    const bool valid = t < P.T;
+    int lane_base = 0;
+    if (valid) {
+        const int g = A.div_tw.div(t), tx = t - g * P.TW;
+        const int n = A.div_th.div(g), ty = g - n * P.TH;
+        const int base_row = n == n0 ? s2 * (ty - ty_a0) : rows0 + (n - n0 - 1) * A.rows_full + s2 * ty;
+        lane_base = base_row * A.row_floats + tx;
+    }
+    half_t* vb = V + (size_t)bt * P.vblock_rows * 64 + lane * 8;
+    const int ngr = cn >> 3;
+    int item = 0;
+    for (int qi = 0; qi < P.ncls; ++qi) {
+        const DevClass q = P.cls[qi];
+        const size_t plane = (size_t)q.Lpad * 64;
+        for (int slot = 0; slot < q.hn * q.wn; ++slot)
+            for (int g8 = 0; g8 < ngr; ++g8, ++item) {
+                if ((item & 3) != wave) continue;
+                const int a = slot / q.wn, bb = slot - a * q.wn;
+                const float* xl = xs16 + lane_base + g8 * 8 * A.chan_floats;
+                half_t* vp = vb + (size_t)(q.v_row0 + slot * P.C + c0 + g8 * 8) * 64;
+                const int hp = q.h0 + a, wp = q.w0 + bb;
+                switch (q.lh * 4 + q.lw) {
+                    case 3 * 4 + 3: lds_part_rows8<3, 3>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 3 * 4 + 2: lds_part_rows8<3, 2>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 3 * 4 + 1: lds_part_rows8<3, 1>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 2 * 4 + 3: lds_part_rows8<2, 3>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 2 * 4 + 2: lds_part_rows8<2, 2>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 2 * 4 + 1: lds_part_rows8<2, 1>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 1 * 4 + 3: lds_part_rows8<1, 3>(A, xl, vp, plane, hp, wp, valid); break;
+                    case 1 * 4 + 2: lds_part_rows8<1, 2>(A, xl, vp, plane, hp, wp, valid); break;
+                    default: lds_part_rows8<1, 1>(A, xl, vp, plane, hp, wp, valid); break;
+                }
+            }
+        // rows past the class's reduction length are zeros (the contraction multiplies them)
+        if (bc == 0 && valid) {
+            const int planes = (q.lh + 1) * (q.lw + 1);
+            for (int l = q.L + 8 * wave; l < q.Lpad; l += 32)
+                for (int pl = 0; pl < planes; ++pl)
+                    *reinterpret_cast<uint4*>(vb + (size_t)(q.v_row0 + l) * 64 + (size_t)pl * plane) = make_uint4(0, 0, 0, 0);
+        }
     }
 }
 
@@ -473,19 +609,31 @@ __global__ __launch_bounds__(256, 2) void contract16_kernel(Contract16Args A, Pl
             const int g_first = (int)(((long long)trel * G.n_iter) / G.sk_ipw);
             const int g_last = (int)((((long long)trel + 1) * G.n_iter - 1) / G.sk_ipw);
             const int nc = g_last - g_first + 1;
-            float* slot0 = partial + (size_t)trel * G.sk_maxc * SLOT + tid;
-            float* mine = slot0 + (size_t)(gidx - g_first) * SLOT;
+            // partial outputs of this tile: [contributor][(block*4 + q)*4 + e/4][thread][4 floats], accessed
+            // as a raw buffer with device scope (the accesses complete, or are served, at the
+            // level all XCDs share) -- 16-byte accesses that the compiler is free to keep in flight
+            // together, which it is not for atomic loads
+            const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(
+                partial + (size_t)trel * G.sk_maxc * SLOT, 0, (int)((unsigned)G.sk_maxc * SLOT * 4u), 0x00020000);
+            constexpr int kDeviceScope = 16;  // cache-policy bits of the access: sc1 = device scope
+            const unsigned pvoff = (unsigned)tid * 16u;  // a wave's access is 1 KB contiguous
+            const unsigned mine = (unsigned)(gidx - g_first) * (unsigned)(SLOT * 4);
 #pragma unroll
             for (int blk = 0; blk < NBLK; ++blk)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        __hip_atomic_store(&mine[((blk * 4 + q) * 16 + e) * NT], Y[blk / WN][blk % WN][q][e],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // device-scope stores complete at the level all XCDs share: waiting for them is the
-            // release that the arrival count needs
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        const floatx16& yv = Y[blk / WN][blk % WN][q];
+                        const pfloat4 v = {yv[4 * e4], yv[4 * e4 + 1], yv[4 * e4 + 2], yv[4 * e4 + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(puint4, v), prs, pvoff,
+                                                               mine + (unsigned)(((blk * 4 + q) * 4 + e4) * NT * 16),
+                                                               kDeviceScope);
+                    }
+            // waiting for the device-scope stores -- not a flush of the whole L2 -- is all the
+            // release that the arrival count below needs
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            wait_vmcnt<0>();
             __syncthreads();
             if (tid == 0) s_last = atomicAdd(&counters[trel], 1) == nc - 1;
             __syncthreads();
@@ -493,21 +641,28 @@ __global__ __launch_bounds__(256, 2) void contract16_kernel(Contract16Args A, Pl
             __syncthreads();  // s_last may be rewritten for the next segment
             if (store) {
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                // all contributions (this workgroup's own included) in contributor order: the
-                // result does not depend on which workgroup happened to arrive last
+                // sum all contributions (this workgroup's own included) in contributor order,
+                // so the result does not depend on which workgroup happened to arrive last
                 for (int c = 0; c < nc; ++c) {
-                    const float* srcp = slot0 + (size_t)c * SLOT;
+                    const unsigned soff = (unsigned)c * (unsigned)(SLOT * 4);
 #pragma unroll
-                    for (int blk = 0; blk < NBLK; ++blk)
+                    for (int blk = 0; blk < NBLK; ++blk) {
+                        pfloat4 v[16];
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                        for (int i = 0; i < 16; ++i)
+                            v[i] = __builtin_bit_cast(
+                                pfloat4, __builtin_amdgcn_raw_buffer_load_b128(
+                                             prs, pvoff, soff + (unsigned)((blk * 16 + i) * NT * 16), kDeviceScope));
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) {
-                                const float v = __hip_atomic_load(&srcp[((blk * 4 + q) * 16 + e) * NT],
-                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                const float old = Y[blk / WN][blk % WN][q][e];
-                                Y[blk / WN][blk % WN][q][e] = c == 0 ? v : old + v;
+                        for (int i = 0; i < 16; ++i) {
+                            floatx16& yv = Y[blk / WN][blk % WN][i >> 2];
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const float old = yv[4 * (i & 3) + k];
+                                yv[4 * (i & 3) + k] = c == 0 ? v[i][k] : old + v[i][k];
                             }
+                        }
+                    }
                 }
                 if (tid == 0) counters[trel] = 0;  // ready for the next launch
             }
@@ -525,6 +680,9 @@ struct dwm_f16_plan {
     dwm_plan* fwd;  // decomposition, row space, plane table; its geometry is this path's
     unsigned char* ws;
     size_t ws_bytes;
+    bool inlds_ok;         // the LDS-staged input transform applies
+    dwm::InLdsArgs inlds;
+    int variant_input;     // < 0: planner's choice, 0: gather form, 1: LDS-staged form
 
     static size_t up256(size_t b) { return (b + 255) / 256 * 256; }
     size_t v_bytes() const { return up256(fwd->v_floats * 2); }
@@ -582,10 +740,39 @@ static dwm_status_t launch_contract16(const dwm_f16_plan& hp, const half_t* U, v
     }
 }
 
+// The LDS-staged form needs whole groups of eight channels per part and a staged region that
+// leaves room for three workgroups per CU; with few parts a workgroup takes more channels so
+// that each of its four waves has an item.
+static bool input16_lds_setup(const dwm_plan& p, InLdsArgs* out)
+{
+    if (p.d.C % 8 != 0) return false;
+    const int nparts = p.info.n_parts;
+    int cg = 8 * ((4 + nparts - 1) / nparts);
+    if (cg > p.d.C) cg = p.d.C;
+    InLdsArgs a;
+    for (; cg >= 8; cg -= 8)
+        if (input_lds_setup(p, &a, cg) && a.cg == cg && a.lds_bytes <= 48 * 1024) {
+            *out = a;
+            return true;
+        }
+    // eight channels in up to 64 KB: two workgroups per CU
+    if (input_lds_setup(p, &a, 8) && a.cg == 8 && a.lds_bytes <= 64 * 1024) {
+        *out = a;
+        return true;
+    }
+    return false;
+}
+
 static dwm_status_t launch_input16(const dwm_f16_plan& hp, const half_t* x, hipStream_t s)
 {
     const DevPlan& d = hp.fwd->d;
     const int nb = d.Tpad / 64, ng = (d.rows_total / 8 + 3) / 4;
+    if (hp.variant_input != 0 && hp.inlds_ok) {
+        const InLdsArgs& a = hp.inlds;
+        hipLaunchKernelGGL(input_transform_f16_lds_kernel, dim3((unsigned)(nb * a.ncg)), dim3(256), a.lds_bytes, s, d, a,
+                           x, hp.v(), hp.counters(), hp.fwd->geo.n_sk_tiles);
+        return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
+    }
     if (ng > 65535) return DWM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(input_transform_f16_kernel, dim3(nb, ng), dim3(256), 0, s, d, x, hp.v(), hp.counters(),
                        hp.fwd->geo.n_sk_tiles);
@@ -625,6 +812,8 @@ dwm_status_t dwm_f16_plan_create(dwm_f16_plan_t** out, int N, int C, int H, int 
     hp->fwd = fwd;
     hp->ws = nullptr;
     hp->ws_bytes = 0;
+    hp->variant_input = -1;
+    hp->inlds_ok = dwm::input16_lds_setup(*fwd, &hp->inlds);
     *out = hp;
     return DWM_OK;
 }
@@ -659,7 +848,13 @@ dwm_status_t dwm_f16_set_workspace(dwm_f16_plan_t* plan, void* ws_dev, size_t by
 
 dwm_status_t dwm_f16_set_variant(dwm_f16_plan_t* plan, const char* stage, int variant)
 {
-    if (!plan || !stage || std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
+    if (!plan || !stage) return DWM_ERR_INVALID_ARG;
+    if (!std::strcmp(stage, "input")) {
+        if (variant > 1 || (variant == 1 && !plan->inlds_ok)) return DWM_ERR_INVALID_ARG;
+        plan->variant_input = variant;
+        return DWM_OK;
+    }
+    if (std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
     if (variant < 0) variant = dwm::default_variant16(plan->fwd->lgran);
     if (variant < 30 || variant > 35) return DWM_ERR_INVALID_ARG;
     dwm::ContractGeometry g;

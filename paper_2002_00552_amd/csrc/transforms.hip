@@ -186,22 +186,6 @@ __global__ __launch_bounds__(256) void input_transform_kernel(DevPlan P, const f
 // The 64 tiles of a block span a few tile rows, possibly of several images: the staged rows
 // are the union per image ("segments"), stored one after the other.
 // ---------------------------------------------------------------------------------
-constexpr int kInLdsBatch = 16;  // input rows a wave loads before it writes them to LDS
-
-// UN consecutive image rows, one float per lane each, into consecutive staged rows.
-// xrow: address of the first row's column 0 (the same for the whole wave); voff: the lane's
-// byte offset inside a row.
-template <int UN>
-__device__ __forceinline__ void stage_rows(const char* __restrict__ xrow, unsigned voff, size_t row_bytes,
-                                           float* __restrict__ xd, int row_floats, bool iw_ok)
-{
-    float v[UN];
-#pragma unroll
-    for (int u = 0; u < UN; ++u) v[u] = *reinterpret_cast<const float*>(xrow + u * row_bytes + voff);
-#pragma unroll
-    for (int u = 0; u < UN; ++u) xd[u * row_floats] = iw_ok ? v[u] : 0.f;
-}
-
 template <int LH, int LW>
 __device__ __forceinline__ void lds_class_rows(const DevPlan& P, const InLdsArgs& A, const DevClass& q,
                                                const float* __restrict__ xl, float* __restrict__ vb, int c0,
@@ -278,53 +262,8 @@ __global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InL
     // kInLdsBatch loads, segment by segment.  Rows above or below the image are written as
     // zeros; columns left or right of it are loaded from a clamped (legal) address and
     // replaced by zero on the way to LDS.
-    const size_t img = (size_t)P.C * P.H * P.W;
-    const size_t row_bytes = (size_t)P.W * sizeof(float);
-    for (int cl = wave; cl < cn; cl += 4) {
-        const float* xc = x + ((size_t)n0 * P.C + c0 + cl) * P.H * P.W;
-        float* xsc = xs + cl * A.chan_floats;
-        for (int cb = 0; cb < A.lw_in; cb += 64) {
-            const int col = cb + lane, iw = col - P.Pw;
-            const bool iw_ok = iw >= 0 && iw < P.W;
-            const unsigned voff = (unsigned)min(max(iw, 0), P.W - 1) * 4u;
-            const int idx = A.div_nphase.div(col);
-            float* xd = xsc + (col - idx * A.nphase) * A.lwp + idx;
-            if (col < A.lw_in) {
-                for (int k = 0; k <= n1 - n0; ++k) {
-                    const int ty_a = k == 0 ? ty_a0 : 0, ty_b = n0 + k == n1 ? ty_b1 : P.TH - 1;
-                    const int nrows = s2 * (ty_b - ty_a) + A.foot_h, ih0 = s2 * ty_a - P.Ph;
-                    const int r_lo = min(max(-ih0, 0), nrows), r_hi = max(min(P.H - ih0, nrows), r_lo);
-                    for (int r = 0; r < r_lo; ++r) xd[r * A.row_floats] = 0.f;
-                    for (int r = r_hi; r < nrows; ++r) xd[r * A.row_floats] = 0.f;
-                    const char* xrow = reinterpret_cast<const char*>(xc + (size_t)k * img) + (size_t)(ih0 + r_lo) * row_bytes;
-                    float* xdr = xd + r_lo * A.row_floats;
-                    int left = r_hi - r_lo;
-                    for (; left >= kInLdsBatch; left -= kInLdsBatch) {
-                        stage_rows<kInLdsBatch>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                        xrow += kInLdsBatch * row_bytes;
-                        xdr += kInLdsBatch * A.row_floats;
-                    }
-                    if (left & 8) {
-                        stage_rows<8>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                        xrow += 8 * row_bytes;
-                        xdr += 8 * A.row_floats;
-                    }
-                    if (left & 4) {
-                        stage_rows<4>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                        xrow += 4 * row_bytes;
-                        xdr += 4 * A.row_floats;
-                    }
-                    if (left & 2) {
-                        stage_rows<2>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                        xrow += 2 * row_bytes;
-                        xdr += 2 * A.row_floats;
-                    }
-                    if (left & 1) stage_rows<1>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                    xd += nrows * A.row_floats;
-                }
-            }
-        }
-    }
+    for (int cl = wave; cl < cn; cl += 4)
+        stage_channel<float>(P, A, x, xs + cl * A.chan_floats, c0 + cl, n0, n1, ty_a0, ty_b1, lane);
 
     // ---- 2. every part of every class for those channels ----
     const int t = t0 + lane;

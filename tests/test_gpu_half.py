@@ -27,10 +27,12 @@ TOL_F32OUT = 2e-5
 
 
 class HalfRunner:
-    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant=None):
+    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant=None, input_variant=None):
         self.plan = dwm.dwm_f16_plan_create(N, C, H, W, K, R, S, stride, pad)
         if variant is not None:
             dwm.dwm_f16_set_variant(self.plan, "contract", variant)
+        if input_variant is not None:
+            dwm.dwm_f16_set_variant(self.plan, "input", input_variant)
         self.info = dwm.dwm_f16_plan_info(self.plan)
         dev = torch.device("cuda:0")
         nan16 = 0x7E00
@@ -195,6 +197,29 @@ def test_every_contraction_variant(variant):
     _check_half_out(y16, ref)
 
 
+@pytest.mark.parametrize("shape", [
+    (3, 8, 19, 21, 70, 3, 3, 2, 1), (2, 24, 14, 14, 40, 7, 7, 1, 3), (2, 64, 30, 30, 64, 3, 3, 1, 1),
+    (4, 128, 28, 28, 96, 3, 3, 2, 1), (1, 8, 11, 100, 20, 5, 5, 3, 1), (1, 40, 9, 130, 4, 3, 5, 1, 2),
+    (70, 8, 6, 6, 8, 3, 3, 1, 1),  # blocks of 64 tiles that span several images
+])
+def test_input_transform_forms_agree(shape):
+    """Gather form and LDS-staged form of the input transform produce the same V, hence the same
+    output bits; both meet the bar."""
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand16(*shape, seed=1300 + R + C, dist="relu_normal")
+    ref = oracle.dwm_half_f64(x, w, s, P)
+    ys = []
+    for form in (0, 1):
+        r = HalfRunner(*shape, input_variant=form)
+        try:
+            ys.append(r.run(x, w, f32out=True))
+        finally:
+            r.close()
+    assert np.array_equal(ys[0].view(np.uint32), ys[1].view(np.uint32))
+    err = float(np.max(np.abs(ys[1].astype(np.float64) - ref)) / np.max(np.abs(ref)))
+    assert err <= TOL_F32OUT, err
+
+
 def test_repeated_calls_give_identical_bits():
     shape = (2, 64, 30, 30, 64, 3, 3, 1, 1)
     x, w = _rand16(*shape, seed=3)
@@ -272,5 +297,10 @@ def test_error_codes():
         with pytest.raises(dwm.DwmError) as e:
             dwm.dwm_f16_set_variant(plan, "contract", 32)  # 64-row chunks on a 16-row layout
         assert e.value.status == dwm.DWM_ERR_INVALID_ARG
+        p3 = dwm.dwm_f16_plan_create(1, 3, 8, 8, 4, 3, 3, 1, 1)
+        with pytest.raises(dwm.DwmError) as e:
+            dwm.dwm_f16_set_variant(p3, "input", 1)  # the LDS-staged form needs C % 8 == 0
+        assert e.value.status == dwm.DWM_ERR_INVALID_ARG
+        dwm.dwm_f16_plan_destroy(p3)
     finally:
         dwm.dwm_f16_plan_destroy(plan)
