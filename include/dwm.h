@@ -290,7 +290,7 @@ DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan,
  * caller-owned device memory, kernels go to `stream`, nothing is allocated or synchronised, errors
  * are return codes.  Workspace: dwm_f16_workspace_bytes, 256-byte aligned (V in binary16, partial
  * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes.
- * dwm_f16_set_variant(plan, "contract", v): v in 30..35 selects the contraction's tile shape
+ * dwm_f16_set_variant(plan, "contract", v): v in 30..47 selects the contraction's tile shape
  * (v < 0: the planner's choice); (plan, "input", v): 0 = gather form of the input transform,
  * 1 = LDS-staged form (C a multiple of 8 and a staged region that fits), v < 0: the planner's
  * choice; DWM_ERR_INVALID_ARG if the variant does not apply to the layer.

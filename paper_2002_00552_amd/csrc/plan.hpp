@@ -88,9 +88,12 @@ constexpr ContractVariant kContractVariants[] = {
     {18, 2, 2, 1, 1, 32, 4}, {19, 2, 2, 1, 1, 64, 3},
     // half-precision contraction (half.hip): ids 30 and up
     {30, 2, 2, 1, 1, 16, 4}, {31, 2, 2, 1, 1, 32, 4}, {32, 2, 2, 1, 1, 64, 3}, {33, 2, 2, 1, 2, 32, 3},
-    {34, 2, 2, 2, 1, 32, 3}, {35, 2, 2, 1, 2, 64, 2},
+    {34, 2, 2, 2, 1, 32, 3}, {35, 2, 2, 1, 2, 64, 2}, {36, 4, 2, 1, 1, 64, 2}, {37, 2, 4, 1, 1, 64, 2},
+    {38, 4, 2, 1, 2, 32, 3}, {39, 2, 4, 2, 1, 32, 3}, {40, 4, 2, 1, 1, 64, 3}, {41, 4, 2, 1, 2, 64, 2},
+    {42, 2, 2, 1, 1, 64, 5}, {43, 2, 2, 1, 1, 32, 8}, {44, 4, 2, 1, 1, 64, 4}, {45, 4, 2, 1, 2, 64, 3},
+    {46, 4, 2, 1, 2, 32, 6}, {47, 2, 2, 1, 1, 64, 8},
 };
-constexpr int kFirstHalfVariant = 30;
+constexpr int kFirstHalfVariant = 30, kLastHalfVariant = 47;
 constexpr int kNumContractVariants = sizeof(kContractVariants) / sizeof(kContractVariants[0]);
 constexpr int kNumCUs = 256;  // MI355X
 
