@@ -163,3 +163,65 @@ def test_error_codes():
     with pytest.raises(dwm.DwmError):
         dwm.dwm_plan_create(0, 1, 1, 1, 1, 1, 1, 1, 0)
     assert "workspace" in dwm.dwm_status_string(dwm.DWM_ERR_WORKSPACE)
+
+
+# ---------------------------------------------------------------------------------------
+# half-precision plan (host side only)
+# ---------------------------------------------------------------------------------------
+def test_half_plan_is_cut_as_printed():
+    """The half-precision plan cuts the kernel 3,3,...,remainder (eq. 8) on every layer, also
+    where the single-precision planner prefers 2+2 tails: the parts are the oracle's parts."""
+    import oracle
+    for L in wl.CONFIGS + [wl.Layer("k4", 1, 8, 20, 20, 8, 4, 4, 1, 1, "uniform")]:
+        p = dwm.dwm_f16_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+        info = dwm.dwm_f16_plan_info(p)
+        parts = oracle.split_2d(L.R, L.S, L.stride)
+        assert info.n_parts == len(parts)
+        assert info.mults_per_tile == oracle.mults_per_tile(L.R, L.S, L.stride)
+        assert info.forward_path == 0
+        # U16 holds every plane's Kpad x Lpad block, two bytes per element
+        assert dwm.dwm_f16_filter_bytes(p) % (2 * info.Kpad * 16) == 0
+        assert dwm.dwm_f16_filter_bytes(p) >= 2 * info.mults_per_tile * L.C * L.K
+        # workspace: V16 (all planes' rows for Tpad tiles) and then some
+        assert dwm.dwm_f16_workspace_bytes(p) >= 2 * info.mults_per_tile * L.C * info.T
+        dwm.dwm_f16_plan_destroy(p)
+
+
+def test_half_plan_error_codes():
+    L = dwm.lib()
+    h = ctypes.c_void_p()
+    assert L.dwm_f16_plan_create(None, 1, 1, 8, 8, 1, 3, 3, 1, 1) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_plan_create(ctypes.byref(h), 1, 1, 8, 8, 1, 3, 3, 0, 1) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_plan_create(ctypes.byref(h), 1, 1, 2, 2, 1, 3, 3, 1, 0) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_plan_create(ctypes.byref(h), 1, 1, 80, 80, 1, 49, 3, 1, 0) == dwm.DWM_ERR_UNSUPPORTED
+    assert L.dwm_f16_plan_create(ctypes.byref(h), 2, 64, 16, 16, 128, 3, 3, 1, 1) == dwm.DWM_OK
+    plan = h
+    one = ctypes.c_void_p(256)
+    assert L.dwm_f16_conv_forward(plan, one, one, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_f16_conv_forward_f32out(plan, one, one, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_f16_input_transform(plan, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_f16_contract_output(plan, one, one, None) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_f16_conv_forward(plan, None, one, one, None) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_filter_transform(plan, one, None, None) == dwm.DWM_ERR_INVALID_ARG
+    need = dwm.dwm_f16_workspace_bytes(plan)
+    assert L.dwm_f16_set_workspace(plan, ctypes.c_void_p(4096), need - 1) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_f16_set_workspace(plan, ctypes.c_void_p(4096 + 8), need) == dwm.DWM_ERR_WORKSPACE
+    assert L.dwm_f16_set_workspace(plan, None, need) == dwm.DWM_ERR_WORKSPACE
+    # variants: single-precision ids are refused, half-precision ids that fit are accepted, and
+    # one that needs more partial-output space than the workspace handed over holds is refused
+    assert L.dwm_f16_set_variant(plan, b"contract", 12) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_set_variant(plan, b"contract", 48) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_set_variant(plan, b"nonsense", 30) == dwm.DWM_ERR_INVALID_ARG
+    for v in range(30, 48):
+        assert L.dwm_f16_set_variant(plan, b"contract", v) == dwm.DWM_OK, v
+    assert L.dwm_f16_set_variant(plan, b"contract", -1) == dwm.DWM_OK
+    assert L.dwm_f16_set_variant(plan, b"input", 0) == dwm.DWM_OK
+    assert L.dwm_f16_set_variant(plan, b"input", 1) == dwm.DWM_OK
+    assert L.dwm_f16_set_variant(plan, b"input", 2) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_plan_set_variant(ctypes.c_void_p(0), b"contract", 30) == dwm.DWM_ERR_INVALID_ARG
+    assert L.dwm_f16_plan_destroy(plan) == dwm.DWM_OK
+    assert L.dwm_f16_plan_destroy(None) == dwm.DWM_ERR_INVALID_ARG
+    # a half-precision contraction id is not a single-precision variant
+    p32 = dwm.dwm_plan_create(2, 64, 16, 16, 128, 3, 3, 1, 1)
+    assert L.dwm_plan_set_variant(p32, b"contract", 32) == dwm.DWM_ERR_INVALID_ARG
+    dwm.dwm_plan_destroy(p32)
