@@ -763,8 +763,8 @@ static dwm_status_t launch_contract16(const dwm_f16_plan& hp, const half_t* U, v
 }
 
 // The LDS-staged form needs whole groups of eight channels per part and a staged region that
-// leaves room for three workgroups per CU; with few parts a workgroup takes more channels so
-// that each of its four waves has an item.
+// fits in LDS, preferably with room for three workgroups per CU; with few parts a workgroup takes
+// more channels so that each of its four waves has an item.
 static bool input16_lds_setup(const dwm_plan& p, InLdsArgs* out)
 {
     if (p.d.C % 8 != 0) return false;
@@ -777,8 +777,9 @@ static bool input16_lds_setup(const dwm_plan& p, InLdsArgs* out)
             *out = a;
             return true;
         }
-    // eight channels in up to 64 KB: two workgroups per CU
-    if (input_lds_setup(p, &a, 8) && a.cg == 8 && a.lds_bytes <= 64 * 1024) {
+    // eight channels in a larger region: two workgroups per CU, or one (still far ahead of the
+    // gather form, whose 2-byte loads are 2*stride elements apart)
+    if (input_lds_setup(p, &a, 8) && a.cg == 8 && a.lds_bytes <= 150 * 1024) {
         *out = a;
         return true;
     }
@@ -791,6 +792,12 @@ static dwm_status_t launch_input16(const dwm_f16_plan& hp, const half_t* x, hipS
     const int nb = d.Tpad / 64, ng = (d.rows_total / 8 + 3) / 4;
     if (hp.variant_input != 0 && hp.inlds_ok) {
         const InLdsArgs& a = hp.inlds;
+        if (a.lds_bytes > 64 * 1024) {
+            static const hipError_t attr =
+                hipFuncSetAttribute(reinterpret_cast<const void*>(input_transform_f16_lds_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (attr != hipSuccess) return DWM_ERR_HIP;
+        }
         hipLaunchKernelGGL(input_transform_f16_lds_kernel, dim3((unsigned)(nb * a.ncg)), dim3(256), a.lds_bytes, s, d, a,
                            x, hp.v(), hp.counters(), hp.fwd->geo.n_sk_tiles);
         return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;

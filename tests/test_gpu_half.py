@@ -201,6 +201,8 @@ def test_every_contraction_variant(variant):
     (3, 8, 19, 21, 70, 3, 3, 2, 1), (2, 24, 14, 14, 40, 7, 7, 1, 3), (2, 64, 30, 30, 64, 3, 3, 1, 1),
     (4, 128, 28, 28, 96, 3, 3, 2, 1), (1, 8, 11, 100, 20, 5, 5, 3, 1), (1, 40, 9, 130, 4, 3, 5, 1, 2),
     (70, 8, 6, 6, 8, 3, 3, 1, 1),  # blocks of 64 tiles that span several images
+    (9, 8, 14, 14, 16, 7, 7, 2, 3),  # four images per block: a staged region beyond 64 KB
+    (9, 16, 14, 14, 16, 11, 11, 2, 5),
 ])
 def test_input_transform_forms_agree(shape):
     """Gather form and LDS-staged form of the input transform produce the same V, hence the same
