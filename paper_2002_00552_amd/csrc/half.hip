@@ -294,8 +294,13 @@ __global__ __launch_bounds__(256) void input_transform_f16_lds_kernel(DevPlan P,
     const int ty_a0 = g0 - n0 * P.TH, ty_b1 = g1 - n1 * P.TH;
     const int rows0 = s2 * ((n1 == n0 ? ty_b1 : P.TH - 1) - ty_a0) + A.foot_h;
 
-    for (int cl = wave; cl < cn; cl += 4)
-        stage_channel<half_t>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, n0, n1, ty_a0, ty_b1, lane);
+    // a wave stages channels wave, wave+4, ...: cn is a multiple of eight, so they come in fours or
+    // pairs whose loads are in flight together (the staging is a chain of load latencies otherwise)
+    int cl = wave;
+    for (; cl + 12 < cn; cl += 16)
+        stage_channels<half_t, 4>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, 4, n0, n1, ty_a0, ty_b1, lane);
+    for (; cl < cn; cl += 8)
+        stage_channels<half_t, 2>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, 4, n0, n1, ty_a0, ty_b1, lane);
     __syncthreads();
 
     const int t = t0 + lane;

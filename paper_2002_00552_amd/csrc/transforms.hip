@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InL
     // zeros; columns left or right of it are loaded from a clamped (legal) address and
     // replaced by zero on the way to LDS.
     for (int cl = wave; cl < cn; cl += 4)
-        stage_channel<float>(P, A, x, xs + cl * A.chan_floats, c0 + cl, n0, n1, ty_a0, ty_b1, lane);
+        stage_channels<float, 1>(P, A, x, xs + cl * A.chan_floats, c0 + cl, 4, n0, n1, ty_a0, ty_b1, lane);
 
     // ---- 2. every part of every class for those channels ----
     const int t = t0 + lane;

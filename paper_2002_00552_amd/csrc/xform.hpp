@@ -56,34 +56,48 @@ __device__ __forceinline__ int find_class(const DevPlan& P, int row)
 // ---------------------------------------------------------------------------------
 constexpr int kInLdsBatch = 16;  // input rows a wave loads before it writes them to LDS
 
-// UN consecutive image rows, one element per lane each, into consecutive staged rows.
-// xrow: address of the first row's column 0 (the same for the whole wave); voff: the lane's
-// byte offset inside a row.
-template <int UN, typename T>
+// UN consecutive image rows of NC channels, one element per lane each, into consecutive staged
+// rows: all NC*UN loads are issued before the first value is used.  xrow: address of the first
+// channel's first row, column 0 (the same for the whole wave); voff: the lane's byte offset inside
+// a row; channels are chan_bytes apart in memory and chan_floats apart in LDS.
+template <int UN, int NC, bool TAIL, typename T>
 __device__ __forceinline__ void stage_rows(const char* __restrict__ xrow, unsigned voff, size_t row_bytes,
-                                           float* __restrict__ xd, int row_floats, bool iw_ok)
+                                           size_t chan_bytes, float* __restrict__ xd, int row_floats,
+                                           int chan_floats, bool iw_ok, int valid)
 {
-    T v[UN];
+    // TAIL: only the first `valid` (1..UN-1) rows exist; the others re-load the last valid row
+    // and are not stored, so that a remainder costs one round of loads instead of one per bit
+    T v[NC][UN];
 #pragma unroll
-    for (int u = 0; u < UN; ++u) v[u] = *reinterpret_cast<const T*>(xrow + u * row_bytes + voff);
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
-    for (int u = 0; u < UN; ++u) xd[u * row_floats] = iw_ok ? (float)v[u] : 0.f;
+        for (int u = 0; u < UN; ++u) {
+            const int r = TAIL ? min(u, valid - 1) : u;
+            v[c][u] = *reinterpret_cast<const T*>(xrow + c * chan_bytes + r * row_bytes + voff);
+        }
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            if (!TAIL || u < valid) xd[c * chan_floats + u * row_floats] = iw_ok ? (float)v[c][u] : 0.f;
 }
 
-// One wave stages channel c of the input rows that the tiles of a 64-tile block touch: the
-// block starts in image n0 at tile row ty_a0 and ends in image n1 at tile row ty_b1.  Lanes
-// run along a row, rows go in batches of up to kInLdsBatch loads, image by image ("segments",
-// stored one after the other).  Rows above or below the image are written as zeros; columns
-// left or right of it are loaded from a clamped (legal) address and replaced by zero on the way
-// to LDS.  Columns are de-interleaved modulo 2*stride.
-template <typename T>
-__device__ __forceinline__ void stage_channel(const DevPlan& P, const InLdsArgs& A, const T* __restrict__ x,
-                                              float* __restrict__ xsc, int c, int n0, int n1, int ty_a0, int ty_b1,
-                                              int lane)
+// One wave stages NC channels (c, c + cstep, ...) of the input rows that the tiles of a 64-tile
+// block touch: the block starts in image n0 at tile row ty_a0 and ends in image n1 at tile row
+// ty_b1.  Lanes run along a row, rows go in batches of up to kInLdsBatch loads per channel, image
+// by image ("segments", stored one after the other).  Rows above or below the image are written
+// as zeros; columns left or right of it are loaded from a clamped (legal) address and replaced by
+// zero on the way to LDS.  Columns are de-interleaved modulo 2*stride.  xsc: where channel c goes.
+template <typename T, int NC>
+__device__ __forceinline__ void stage_channels(const DevPlan& P, const InLdsArgs& A, const T* __restrict__ x,
+                                               float* __restrict__ xsc, int c, int cstep, int n0, int n1,
+                                               int ty_a0, int ty_b1, int lane)
 {
     const int s2 = 2 * P.s;
     const size_t img = (size_t)P.C * P.H * P.W;
     const size_t row_bytes = (size_t)P.W * sizeof(T);
+    const size_t chan_bytes = (size_t)cstep * P.H * P.W * sizeof(T);
+    const int chan_floats = cstep * A.chan_floats;
     const T* xc = x + ((size_t)n0 * P.C + c) * P.H * P.W;
     for (int cb = 0; cb < A.lw_in; cb += 64) {
         const int col = cb + lane, iw = col - P.Pw;
@@ -96,32 +110,26 @@ __device__ __forceinline__ void stage_channel(const DevPlan& P, const InLdsArgs&
                 const int ty_a = k == 0 ? ty_a0 : 0, ty_b = n0 + k == n1 ? ty_b1 : P.TH - 1;
                 const int nrows = s2 * (ty_b - ty_a) + A.foot_h, ih0 = s2 * ty_a - P.Ph;
                 const int r_lo = min(max(-ih0, 0), nrows), r_hi = max(min(P.H - ih0, nrows), r_lo);
-                for (int r = 0; r < r_lo; ++r) xd[r * A.row_floats] = 0.f;
-                for (int r = r_hi; r < nrows; ++r) xd[r * A.row_floats] = 0.f;
+#pragma unroll
+                for (int cc = 0; cc < NC; ++cc) {
+                    for (int r = 0; r < r_lo; ++r) xd[cc * chan_floats + r * A.row_floats] = 0.f;
+                    for (int r = r_hi; r < nrows; ++r) xd[cc * chan_floats + r * A.row_floats] = 0.f;
+                }
                 const char* xrow = reinterpret_cast<const char*>(xc + (size_t)k * img) + (size_t)(ih0 + r_lo) * row_bytes;
                 float* xdr = xd + r_lo * A.row_floats;
                 int left = r_hi - r_lo;
                 for (; left >= kInLdsBatch; left -= kInLdsBatch) {
-                    stage_rows<kInLdsBatch, T>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                    stage_rows<kInLdsBatch, NC, false, T>(xrow, voff, row_bytes, chan_bytes, xdr, A.row_floats,
+                                                          chan_floats, iw_ok, kInLdsBatch);
                     xrow += kInLdsBatch * row_bytes;
                     xdr += kInLdsBatch * A.row_floats;
                 }
-                if (left & 8) {
-                    stage_rows<8, T>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                    xrow += 8 * row_bytes;
-                    xdr += 8 * A.row_floats;
-                }
-                if (left & 4) {
-                    stage_rows<4, T>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                    xrow += 4 * row_bytes;
-                    xdr += 4 * A.row_floats;
-                }
-                if (left & 2) {
-                    stage_rows<2, T>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
-                    xrow += 2 * row_bytes;
-                    xdr += 2 * A.row_floats;
-                }
-                if (left & 1) stage_rows<1, T>(xrow, voff, row_bytes, xdr, A.row_floats, iw_ok);
+                if (left > 8)
+                    stage_rows<kInLdsBatch, NC, true, T>(xrow, voff, row_bytes, chan_bytes, xdr, A.row_floats,
+                                                         chan_floats, iw_ok, left);
+                else if (left > 0)
+                    stage_rows<8, NC, true, T>(xrow, voff, row_bytes, chan_bytes, xdr, A.row_floats, chan_floats, iw_ok,
+                                               left);
                 xd += nrows * A.row_floats;
             }
         }
