@@ -358,16 +358,16 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                 for (int c = 0; c < nc; ++c) {
                     const unsigned soff = (unsigned)c * (unsigned)(SLOT * 4);
 #pragma unroll
-                    for (int blk = 0; blk < NBLK; ++blk) {
-                        pfloat4 v[16];
+                    for (int hb = 0; hb < 2 * NBLK; ++hb) {  // half a block (two of its four outputs) at a time
+                        pfloat4 v[8];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i)
+                        for (int i = 0; i < 8; ++i)
                             v[i] = __builtin_bit_cast(
                                 pfloat4, __builtin_amdgcn_raw_buffer_load_b128(
-                                             prs, pvoff, soff + (unsigned)((blk * 16 + i) * NT * 16), kDeviceScope));
+                                             prs, pvoff, soff + (unsigned)((hb * 8 + i) * NT * 16), kDeviceScope));
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            floatx16& yv = Y[blk / WN][blk % WN][i >> 2];
+                        for (int i = 0; i < 8; ++i) {
+                            floatx16& yv = Y[(hb >> 1) / WN][(hb >> 1) % WN][(hb & 1) * 2 + (i >> 2)];
 #pragma unroll
                             for (int k = 0; k < 4; ++k) {
                                 const float old = yv[4 * (i & 3) + k];

@@ -1,0 +1,60 @@
+"""The library only enqueues kernels on the caller's stream (no allocation, no synchronisation,
+no memset): a forward call can therefore be captured into a HIP graph and replayed.  Every replay
+is checked against the eager result, with eager work and synchronisations between replays."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2002_00552_amd as dwm
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(shape, forward_variant):
+    N, C, H, W, K, R, S, s, P = shape
+    rng = np.random.default_rng(5)
+    x = torch.from_numpy(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)).cuda()
+    w = torch.from_numpy((rng.standard_normal((K, C, R, S)) * np.sqrt(2.0 / (C * R * S))).astype(np.float32)).cuda()
+    plan = dwm.dwm_plan_create(N, C, H, W, K, R, S, s, P)
+    if forward_variant is not None:
+        dwm.dwm_plan_set_variant(plan, "forward", forward_variant)
+    info = dwm.dwm_plan_info(plan)
+    U = torch.empty(dwm.dwm_plan_filter_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(dwm.dwm_plan_workspace_bytes(plan) // 4, 64), dtype=torch.float32, device="cuda")
+    dwm.dwm_plan_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+    y = torch.zeros((N, K, info.OH, info.OW), dtype=torch.float32, device="cuda")
+    return plan, x, w, U, ws, y
+
+
+@pytest.mark.parametrize("shape,forward_variant", [
+    ((1, 16, 32, 32, 16, 5, 5, 1, 2), None),   # single-kernel path
+    ((1, 16, 32, 32, 16, 5, 5, 1, 2), 0),      # staged path with split tiles (arrival counters)
+    ((2, 64, 30, 30, 64, 3, 3, 1, 1), 0),      # staged path, whole and split tiles
+])
+def test_forward_replays_from_a_graph(shape, forward_variant):
+    plan, x, w, U, ws, y = _setup(shape, forward_variant)
+    try:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            st = side.cuda_stream
+            dwm.dwm_filter_transform(plan, w.data_ptr(), U.data_ptr(), st)
+            dwm.dwm_conv_forward(plan, x.data_ptr(), U.data_ptr(), y.data_ptr(), st)  # eager, also warms up
+            side.synchronize()
+            eager = y.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                dwm.dwm_conv_forward(plan, x.data_ptr(), U.data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        for rep in range(4):
+            y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, eager), "replay %d" % rep
+            # eager work between replays, on another input, through the same plan and workspace
+            x2 = x * 0.5
+            dwm.dwm_conv_forward(plan, x2.data_ptr(), U.data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert not torch.equal(y, eager)
+    finally:
+        torch.cuda.synchronize()
+        dwm.dwm_plan_destroy(plan)
