@@ -209,8 +209,10 @@ DWM_API dwm_status_t dwm_contract_output(const dwm_plan_t* plan, const float* Ug
  * memory, results do not vary from run to run.
  * The plan takes the FORWARD layer's shape.  Limits: stride <= 8 and those of dwm_plan_create.
  * Memory, stream and error conventions are the same as for the forward calls; the workspace
- * (>= dwm_bwd_data_workspace_bytes, 256-byte aligned, non-null) is shared by the
- * sub-convolutions, which run one after the other on the stream.
+ * (>= dwm_bwd_data_workspace_bytes, 256-byte aligned, non-null) holds the sub-convolutions'
+ * transformed inputs: one after the other in the same space where the sub-convolutions run one
+ * after the other, side by side where their contractions are launched together (stride > 1,
+ * staged path).  Everything runs on the given stream.
  */
 typedef struct dwm_bwd_data_plan dwm_bwd_data_plan_t;
 

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdwm.so")
 PROBE_LIB = os.path.join(HERE, "libdwm_probe.so")
-SOURCES = ["plan.cpp", "transforms.hip", "contract.hip", "fused.hip", "backward.hip", "wgrad.hip", "half.hip"]
+SOURCES = ["plan.cpp", "transforms.hip", "contract.hip", "fused.hip", "contract_batch.hip", "backward.hip", "wgrad.hip", "half.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

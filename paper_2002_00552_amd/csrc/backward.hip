@@ -35,6 +35,14 @@ struct dwm_bwd_data_plan {
     size_t wtmp_floats;      // start of Ugw: scratch for one phase's gathered, flipped weights
     size_t filter_floats, ws_bytes;
     double direct_flops;
+    // all sub-convolutions contracted in one launch (contract_batch.hip): each then has its own
+    // slice of the workspace, ws_off[i] bytes from its start for phase i
+    bool batched;
+    int batch_lc;
+    dwm::BatchArgs batch;
+    dwm::PlaneTable batch_planes;
+    std::vector<size_t> ws_off;
+    float* ws;
 };
 
 namespace dwm {
@@ -70,6 +78,70 @@ __global__ __launch_bounds__(256) void bwd_zero_phase_kernel(float* __restrict__
 static int ceil_div(int x, int d) { return x >= 0 ? (x + d - 1) / d : -((-x) / d); }
 
 }  // namespace dwm
+
+// One launch for the contractions of all sub-convolutions where that applies: at least two of
+// them, all on the staged path, their planes fit one table.  The sub-convolutions are ordered
+// longest first; each keeps its own slice of the workspace (its V is alive until the one launch).
+static void setup_batch(dwm_bwd_data_plan& bp)
+{
+    using namespace dwm;
+    bp.batched = false;
+    bp.ws = nullptr;
+    bp.ws_off.assign(bp.phases.size(), 0);
+    std::vector<int> subs;
+    int planes = 0, lc = 64;
+    for (size_t i = 0; i < bp.phases.size(); ++i) {
+        const dwm_plan_t* sp = bp.phases[i].sub;
+        if (!sp) continue;
+        if (sp->use_fused()) return;
+        subs.push_back((int)i);
+        planes += sp->planes.n;
+        lc = std::min(lc, sp->lgran);
+    }
+    if (subs.size() < 2 || subs.size() > (size_t)kMaxBatch || planes > kMaxPlanes) return;
+    auto n_iter = [&](int i) {
+        int n = 0;
+        const PlaneTable& pt = bp.phases[i].sub->planes;
+        for (int q = 0; q < pt.n; ++q) n += pt.e[q].Lpad / lc;
+        return n;
+    };
+    std::stable_sort(subs.begin(), subs.end(), [&](int a, int b) { return n_iter(a) > n_iter(b); });
+    BatchArgs& A = bp.batch;
+    A = BatchArgs{};
+    A.K = bp.C;  // the sub-convolutions' filters are the layer's input channels
+    A.nkt = (bp.C + 63) / 64;
+    A.nprob = (int)subs.size();
+    bp.batch_planes = PlaneTable{};
+    size_t ws = 0;
+    long long tiles = 0;
+    for (int q = 0; q < A.nprob; ++q) {
+        const int i = subs[q];
+        const auto& ph = bp.phases[i];
+        const dwm_plan_t* sp = ph.sub;
+        if (ph.u_off % 64 != 0) return;
+        BatchProb& P = A.p[q];
+        P.plane0 = bp.batch_planes.n;
+        P.n_iter = n_iter(i);
+        P.tile0 = (int)tiles;
+        P.vblock = sp->d.vblock_rows * 64;
+        P.om = sp->d.om;
+        P.OH = sp->d.OH; P.OW = sp->d.OW; P.TH = sp->d.TH; P.TW = sp->d.TW; P.T = sp->d.T;
+        P.v_base = (long long)(ws / sizeof(float));
+        bp.ws_off[i] = ws;
+        ws += (dwm_plan_workspace_bytes(sp) + 255) / 256 * 256;
+        for (int e = 0; e < sp->planes.n; ++e) {
+            DevPlaneEntry pe = sp->planes.e[e];
+            pe.u_off64 += (uint32_t)(ph.u_off / 64);
+            bp.batch_planes.e[bp.batch_planes.n++] = pe;
+        }
+        tiles += (long long)A.nkt * ((sp->d.T + 63) / 64);
+    }
+    if (tiles > 0x7fffffffLL || ws / sizeof(float) > 0x7fffffffffffLL) return;
+    A.ntiles = (int)tiles;
+    bp.batch_lc = lc;
+    bp.ws_bytes = std::max<size_t>(ws, 256);
+    bp.batched = true;
+}
 
 extern "C" {
 
@@ -135,6 +207,7 @@ dwm_status_t dwm_bwd_data_plan_create(dwm_bwd_data_plan_t** out, int N, int C, i
             off += (dwm_plan_filter_bytes(ph.sub) / sizeof(float) + 63) / 64 * 64;
         }
     bp->filter_floats = off;
+    setup_batch(*bp);
     *out = bp;
     return DWM_OK;
 }
@@ -184,11 +257,15 @@ dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void* ws_dev,
 {
     if (!plan) return DWM_ERR_INVALID_ARG;
     if (bytes < plan->ws_bytes) return DWM_ERR_WORKSPACE;
-    for (auto& ph : plan->phases)
-        if (ph.sub) {
-            const dwm_status_t st = dwm_plan_set_workspace(ph.sub, ws_dev, bytes);
-            if (st != DWM_OK) return st;
-        }
+    for (size_t i = 0; i < plan->phases.size(); ++i) {
+        auto& ph = plan->phases[i];
+        if (!ph.sub) continue;
+        const size_t off = plan->batched ? plan->ws_off[i] : 0;
+        const dwm_status_t st = dwm_plan_set_workspace(ph.sub, ws_dev ? static_cast<char*>(ws_dev) + off : nullptr,
+                                                       plan->batched ? dwm_plan_workspace_bytes(ph.sub) : bytes);
+        if (st != DWM_OK) return st;
+    }
+    plan->ws = static_cast<float*>(ws_dev);
     return DWM_OK;
 }
 
@@ -224,9 +301,18 @@ dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float
             if (hipGetLastError() != hipSuccess) return DWM_ERR_HIP;
             continue;
         }
+        if (plan->batched) {  // its input transform now, its contraction with all the others below
+            if (!plan->ws) return DWM_ERR_WORKSPACE;
+            const dwm_status_t st = dwm::launch_input_transform(*ph.sub, dy_dev, ph.sub->ws, stream);
+            if (st != DWM_OK) return st;
+            continue;
+        }
         const dwm_status_t st = dwm_conv_forward(ph.sub, dy_dev, Ugw_dev + ph.u_off, dx_dev, stream);
         if (st != DWM_OK) return st;
     }
+    if (plan->batched)
+        return dwm::launch_contract_batch(plan->batch, plan->batch_planes, plan->batch_lc, Ugw_dev, plan->ws, dx_dev,
+                                          stream);
     return DWM_OK;
 }
 

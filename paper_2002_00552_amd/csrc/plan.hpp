@@ -199,6 +199,22 @@ struct InLdsArgs {
     size_t lds_bytes;
 };
 
+// Several stride-1 sub-convolutions contracted in one launch (contract_batch.hip): their planes
+// are concatenated in one PlaneTable, their (K tile, T tile) grids in one grid.
+constexpr int kMaxBatch = 16;
+struct BatchProb {
+    int plane0, n_iter;  // first plane in the table, chunks per tile (sum over its planes of Lpad/LC)
+    int tile0, vblock;   // first tile in the grid, floats of one 64-tile block of its V
+    OutMap om;
+    int OH, OW, TH, TW, T;
+    int pad_;
+    long long v_base;    // its V, in floats from the start of the workspace
+};
+struct BatchArgs {
+    int K, nkt, nprob, ntiles;
+    BatchProb p[kMaxBatch];
+};
+
 }  // namespace dwm
 
 // The opaque plan of the C ABI.
@@ -248,6 +264,9 @@ dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream);
 dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const float* V, float* y, void* stream);
 bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish);
+// contract_batch.hip
+dwm_status_t launch_contract_batch(const BatchArgs& a, const PlaneTable& pt, int lc, const float* U, const float* V,
+                                   float* y, void* stream);
 // fused.hip
 bool fused_setup(const dwm_plan& p, FusedArgs* out);
 dwm_status_t launch_fused_filter(const dwm_plan& p, const float* w, float* U, void* stream);
