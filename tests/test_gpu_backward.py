@@ -69,6 +69,9 @@ SHAPES = [  # N, C, H, W, K, R, S, stride, pad
     (2, 70, 21, 19, 130, 3, 3, 2, 1),
     (1, 3, 9, 300, 4, 3, 5, 1, 2),       # one long row
     (2, 6, 40, 33, 5, 5, 5, 2, 5),       # pad larger than the kernel reach: windows wholly in the padding
+    (1, 5, 20, 18, 140, 4, 6, 3, 2),     # nine sub-convolutions of different extents contracted in one launch
+    (2, 9, 17, 22, 200, 5, 5, 2, 2),     # four, 3- and 2-tap phases: several classes per sub-convolution
+    (1, 4, 23, 23, 130, 11, 11, 4, 0),   # sixteen: too many planes for one table, run one after the other
 ]
 
 
