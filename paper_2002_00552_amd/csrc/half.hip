@@ -110,9 +110,11 @@ __global__ __launch_bounds__(256) void filter_transform_f16_kernel(DevPlan P, co
 // B^T . B in FP32 -- exact but for sums that span more than 13 binades -- and rounds to binary16.
 // A wave's store is 1 KB contiguous per plane.
 // ---------------------------------------------------------------------------------
+// pc: the pieces' (phase, offset) in LDS, [dimension][piece][2] -- eight look-ups by a run-time
+// index into the by-value plan would make the compiler keep the whole plan in scratch memory
 template <int LH, int LW>
-__device__ __forceinline__ void input_rows8_f16(const DevPlan& P, const DevClass& q, const half_t* __restrict__ x,
-                                                half_t* __restrict__ V, int l0, int t)
+__device__ __forceinline__ void input_rows8_f16(const DevPlan& P, const DevClass& q, const int (*pc)[kMaxPieces][2],
+                                                const half_t* __restrict__ x, half_t* __restrict__ V, int l0, int t)
 {
     constexpr int TH_ = LH + 1, TW_ = LW + 1;
     const bool t_ok = t < P.T;
@@ -130,14 +132,15 @@ __device__ __forceinline__ void input_rows8_f16(const DevPlan& P, const DevClass
             const bool ok = row_ok && t_ok;
             const int slot = l / P.C, c = l - slot * P.C;
             const int a = slot / q.wn, b = slot - a * q.wn;
-            const DevPiece hp = P.ph[q.h0 + (row_ok ? a : 0)], wp = P.pw[q.w0 + (row_ok ? b : 0)];
+            const int hi = q.h0 + (row_ok ? a : 0), wi = q.w0 + (row_ok ? b : 0);
+            const int hp_p = pc[0][hi][0], hp_j = pc[0][hi][1], wp_p = pc[1][wi][0], wp_j = pc[1][wi][1];
             const half_t* xc = x + ((size_t)n * P.C + (row_ok ? c : 0)) * P.H * P.W;
 #pragma unroll
             for (int i = 0; i < TH_; ++i) {
-                const int ih = P.s * (2 * ty + hp.j + i) + hp.p - P.Ph;
+                const int ih = P.s * (2 * ty + hp_j + i) + hp_p - P.Ph;
 #pragma unroll
                 for (int j = 0; j < TW_; ++j) {
-                    const int iw = P.s * (2 * tx + wp.j + j) + wp.p - P.Pw;
+                    const int iw = P.s * (2 * tx + wp_j + j) + wp_p - P.Pw;
                     d[r][i][j] =
                         (ok && ih >= 0 && ih < P.H && iw >= 0 && iw < P.W) ? (float)xc[(size_t)ih * P.W + iw] : 0.f;
                 }
@@ -187,6 +190,14 @@ __global__ __launch_bounds__(256) void input_transform_f16_kernel(DevPlan P, con
     // The contraction that follows counts partial-tile arrivals in `counters`; they start at zero.
     if (blockIdx.x == 0 && blockIdx.y == 0)
         for (int i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
+    __shared__ int pc[2][kMaxPieces][2];
+    if (threadIdx.x < 2 * kMaxPieces) {
+        const int i = threadIdx.x % kMaxPieces;
+        const DevPiece piece = threadIdx.x < kMaxPieces ? P.ph[i] : P.pw[i];
+        pc[threadIdx.x / kMaxPieces][i][0] = piece.p;
+        pc[threadIdx.x / kMaxPieces][i][1] = piece.j;
+    }
+    __syncthreads();
     const int t = blockIdx.x * 64 + (threadIdx.x & 63);  // < Tpad by construction of the grid
     // 8 rows, never across a class (Lpad % 16 == 0); the same for the whole wave, so everything
     // derived from it (class, part, pieces) stays in scalar registers
@@ -196,15 +207,15 @@ __global__ __launch_bounds__(256) void input_transform_f16_kernel(DevPlan P, con
     const DevClass q = P.cls[qi];
     const int l0 = row - q.row0;
     switch (q.lh * 4 + q.lw) {
-        case 3 * 4 + 3: input_rows8_f16<3, 3>(P, q, x, V, l0, t); break;
-        case 3 * 4 + 2: input_rows8_f16<3, 2>(P, q, x, V, l0, t); break;
-        case 3 * 4 + 1: input_rows8_f16<3, 1>(P, q, x, V, l0, t); break;
-        case 2 * 4 + 3: input_rows8_f16<2, 3>(P, q, x, V, l0, t); break;
-        case 2 * 4 + 2: input_rows8_f16<2, 2>(P, q, x, V, l0, t); break;
-        case 2 * 4 + 1: input_rows8_f16<2, 1>(P, q, x, V, l0, t); break;
-        case 1 * 4 + 3: input_rows8_f16<1, 3>(P, q, x, V, l0, t); break;
-        case 1 * 4 + 2: input_rows8_f16<1, 2>(P, q, x, V, l0, t); break;
-        default: input_rows8_f16<1, 1>(P, q, x, V, l0, t); break;
+        case 3 * 4 + 3: input_rows8_f16<3, 3>(P, q, pc, x, V, l0, t); break;
+        case 3 * 4 + 2: input_rows8_f16<3, 2>(P, q, pc, x, V, l0, t); break;
+        case 3 * 4 + 1: input_rows8_f16<3, 1>(P, q, pc, x, V, l0, t); break;
+        case 2 * 4 + 3: input_rows8_f16<2, 3>(P, q, pc, x, V, l0, t); break;
+        case 2 * 4 + 2: input_rows8_f16<2, 2>(P, q, pc, x, V, l0, t); break;
+        case 2 * 4 + 1: input_rows8_f16<2, 1>(P, q, pc, x, V, l0, t); break;
+        case 1 * 4 + 3: input_rows8_f16<1, 3>(P, q, pc, x, V, l0, t); break;
+        case 1 * 4 + 2: input_rows8_f16<1, 2>(P, q, pc, x, V, l0, t); break;
+        default: input_rows8_f16<1, 1>(P, q, pc, x, V, l0, t); break;
     }
 }
 
