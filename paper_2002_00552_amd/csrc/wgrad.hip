@@ -16,6 +16,8 @@
 //   4. The partial dU are summed in a fixed order and G^T (.) G is applied: every tap of dw is
 //      written exactly once (the parts partition the taps), nothing is accumulated atomically,
 //      results do not vary from run to run.
+// Layers with few input channels (every class has at most 32 rows) and many tiles take another
+// form of steps 2-3 that never builds dM: see wgrad_small_kernel.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -37,7 +39,8 @@ struct WgradArgs {
     int tile0[kMaxPlanes + 1];   // first output tile of each plane
     int nlt[kMaxPlanes];         // 64-wide l tiles of each plane
     int vrow[kMaxPlanes];        // first V row of each plane
-    int poff64[kMaxPlanes];      // offset of the plane's dU[Kp][Lp64] inside a split, in units of 64 floats
+    int poff64[kMaxPlanes];      // offset of the plane's dU[Kp][lstride] inside a split, in units of 64 floats
+    int lstride[kMaxPlanes];     // floats between consecutive filters k of the plane's dU
 };
 
 // ---- step 2: dM[block][plane*Kp + k][t] = sum_q pattern_p[q] * dy[n][k][2ty+a][2tx+b] ----
@@ -176,6 +179,193 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradArgs A, const f
     for (int e = 0; e < 16; ++e) out[(size_t)(8 * (e >> 2) + 4 * lh + (e & 3)) * Lp64] = acc[e];
 }
 
+
+// ---------------------------------------------------------------------------------
+// Short reductions (layers with few input channels: every class has at most 32 rows).
+//
+// The GEMM form above would multiply 64-row tiles that are mostly padding and, worse, stream
+// dM -- planes x K x tiles floats, nine times the size of dy -- through memory twice.  Here a
+// workgroup owns 64 filters (16 per wave) and a range of tiles, for ALL planes of one class:
+// a lane reads the 2x2 blocks of dy of its filter for four tiles, applies A . A^T in registers
+// (the coefficients are compile-time constants), and that is the A operand of
+// v_mfma_f32_16x16x4_f32 for every plane; the B operand, V[l][four tiles], is one 16-byte load
+// per plane.  Which tile sits in which of the MFMA's four reduction slots is free, so slot q
+// of step m takes tile 4q+m: a lane's four steps use exactly its four tiles.  dM never exists.
+// Every workgroup writes its own partial dU (compact: [plane][k][16*LB]); a second kernel adds
+// the partials in a fixed order.
+// ---------------------------------------------------------------------------------
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// A^T of F(2,l), row a, column f: the forms of the staged forward path
+__host__ __device__ constexpr int at_coef(int l, int a, int f)
+{
+    return l == 3   ? (a == 0 ? (f < 3 ? 1 : 0) : (f == 0 ? 0 : f == 1 ? 1 : -1))
+           : l == 2 ? (a == 0 ? (f < 2 ? 1 : 0) : (f > 0 ? 1 : 0))
+                    : (a == f ? 1 : 0);
+}
+
+struct SmallArgs {
+    int K, Kp, T, OH, OW, TH, TW;
+    int vblock_rows, vrow0, Lpad;  // rows of a V block, the class's first row in it, rows per plane
+    int tiles_per_split;           // a multiple of 16
+    int poff;                      // floats from the start of a split's partial to this class's planes
+    long long split_floats;
+    FastDiv div_tiles, div_tw;
+};
+
+template <int LH, int LW, int LB>
+__global__ __launch_bounds__(256, 2) void wgrad_small_kernel(SmallArgs A, const float* __restrict__ dy,
+                                                             const float* __restrict__ V, float* __restrict__ partial)
+{
+    constexpr int NH = LH + 1, NW = LW + 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int ln = lane & 15, q = lane >> 4;
+    const int split = blockIdx.x, kt = blockIdx.y;
+    const int tiles = A.TH * A.TW;
+
+    floatx4 acc[NH * NW][LB];
+#pragma unroll
+    for (int p = 0; p < NH * NW; ++p)
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb) acc[p][lb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // dy of a chunk of 16 tiles goes through a wave-private piece of LDS so that the global loads
+    // are coalesced: for each of the wave's 16 filters one load instruction fetches the two output
+    // rows of the 16 tiles (lane = (row a, tile, column b): 128 contiguous bytes per row where the
+    // tiles are neighbours); a lane then picks up the 2x2 blocks of ITS filter and four tiles with
+    // four 16-byte LDS reads.  Rows are 68 floats apart (64 + 4: conflict-free 16-byte reads).
+    __shared__ __attribute__((aligned(16))) float dys[4][16][68];
+    float(*my)[68] = dys[wave];
+    // V of a chunk -- the class's rows x 16 tiles, the same for the four waves -- is loaded once
+    // per workgroup (a thread per (row, 16 bytes)), one chunk ahead, into one of two LDS buffers
+    extern __shared__ __attribute__((aligned(16))) float vs[];
+    constexpr int VROWS = NH * NW * LB * 16, VITEMS = (VROWS * 4 + 255) / 256;
+    floatx4 vreg[VITEMS];
+    // this thread's (row, 16 bytes) items: offsets inside the class's rows of a V block / an LDS buffer
+    int vsrc[VITEMS], vdst[VITEMS];
+#pragma unroll
+    for (int it = 0; it < VITEMS; ++it) {
+        const int idx = min((int)threadIdx.x + 256 * it, VROWS * 4 - 1);  // spare threads repeat the last item
+        vsrc[it] = (idx >> 2) * 64 + 4 * (idx & 3);
+        vdst[it] = idx * 4;
+    }
+#define DWM_LOAD_V(t0_)                                                                                     \
+    {                                                                                                       \
+        const float* vbase_ = V + ((size_t)((t0_) >> 6) * A.vblock_rows + A.vrow0) * 64 + ((t0_) & 63);       \
+        _Pragma("unroll") for (int it = 0; it < VITEMS; ++it)                                               \
+            vreg[it] = *reinterpret_cast<const floatx4*>(vbase_ + vsrc[it]);                                 \
+    }
+#define DWM_STORE_V(buf_)                                                                                   \
+    {                                                                                                       \
+        _Pragma("unroll") for (int it = 0; it < VITEMS; ++it)                                               \
+            *reinterpret_cast<floatx4*>(vs + (buf_) * (VROWS * 16) + vdst[it]) = vreg[it];                    \
+    }
+    const int la = lane >> 5, lt = (lane >> 1) & 15, lb_ = lane & 1;
+    const int kw = kt * 64 + wave * 16;
+
+    const int t_begin = split * A.tiles_per_split;
+    const int t_end = min(t_begin + A.tiles_per_split, (A.T + 15) & ~15);
+    const size_t kstep = (size_t)A.OH * A.OW;
+    float v[16];
+    auto load_dy = [&](int t0) {
+        const int t = t0 + lt;
+        const int n = A.div_tiles.div(min(t, A.T - 1)), rem = min(t, A.T - 1) - n * tiles;
+        const int ty = A.div_tw.div(rem), tx = rem - ty * A.TW;
+        const bool ok = t < A.T && 2 * ty + la < A.OH && 2 * tx + lb_ < A.OW;
+        const float* yp = dy + (((size_t)n * A.K + kw) * A.OH + 2 * ty + la) * A.OW + 2 * tx + lb_;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = (ok && kw + j < A.K) ? yp[(size_t)j * kstep] : 0.f;
+    };
+    if (t_begin < t_end) {
+        load_dy(t_begin);
+        DWM_LOAD_V(t_begin)
+    }
+    int cur = 0;
+    for (int t0 = t_begin; t0 < t_end; t0 += 16, cur ^= 1) {
+        DWM_STORE_V(cur)
+        __syncthreads();  // also: every wave is done with the other buffer, which the next chunk refills
+        if (t0 + 16 < t_end) DWM_LOAD_V(t0 + 16)
+        {
+            // other lanes of this wave read what this lane writes, and the other way round: the
+            // hardware runs a wave's LDS instructions in order; these keep the compiler from
+            // moving the reads of one phase across the writes of the other (no instruction emitted)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < 16; ++j) my[j][lane] = v[j];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // the next chunk's dy is in flight while this one is multiplied
+            if (t0 + 16 < t_end) load_dy(t0 + 16);
+        }
+        // r[i][fh][b] = sum_a A^T[a][fh] * dy[a][b] of this lane's tile 4q+i
+        float r[4][NH][2];
+        {
+            const float4 g0 = *reinterpret_cast<const float4*>(&my[ln][8 * q]);
+            const float4 g1 = *reinterpret_cast<const float4*>(&my[ln][8 * q + 4]);
+            const float4 h0 = *reinterpret_cast<const float4*>(&my[ln][32 + 8 * q]);
+            const float4 h1 = *reinterpret_cast<const float4*>(&my[ln][32 + 8 * q + 4]);
+            const float g[4][2][2] = {{{g0.x, g0.y}, {h0.x, h0.y}}, {{g0.z, g0.w}, {h0.z, h0.w}},
+                                      {{g1.x, g1.y}, {h1.x, h1.y}}, {{g1.z, g1.w}, {h1.z, h1.w}}};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int fh = 0; fh < NH; ++fh)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        r[i][fh][b] = (float)at_coef(LH, 0, fh) * g[i][0][b] + (float)at_coef(LH, 1, fh) * g[i][1][b];
+        }
+        // B operands: V[row = plane*Lpad + lb*16 + ln][tiles 4q .. 4q+3] of the chunk, from LDS
+        const float* vl = vs + cur * (VROWS * 16) + ln * 16 + 4 * q;
+#pragma unroll
+        for (int p = 0; p < NH * NW; ++p) {
+            const int fh = p / NW, fw = p % NW;
+            float a[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                a[i] = (float)at_coef(LW, 0, fw) * r[i][fh][0] + (float)at_coef(LW, 1, fw) * r[i][fh][1];
+#pragma unroll
+            for (int lb = 0; lb < LB; ++lb) {
+                const float4 b4 = *reinterpret_cast<const float4*>(vl + (p * LB + lb) * 256);
+                acc[p][lb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b4.x, acc[p][lb], 0, 0, 0);
+                acc[p][lb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b4.y, acc[p][lb], 0, 0, 0);
+                acc[p][lb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b4.z, acc[p][lb], 0, 0, 0);
+                acc[p][lb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b4.w, acc[p][lb], 0, 0, 0);
+            }
+        }
+    }
+    // lane (ln, q) holds dU[k = 4q + e][l = ln] of its wave's 16 filters
+    float* out = partial + (size_t)split * A.split_floats + A.poff +
+                 ((size_t)(kt * 64 + wave * 16 + 4 * q)) * (16 * LB) + ln;
+#pragma unroll
+    for (int p = 0; p < NH * NW; ++p)
+#pragma unroll
+        for (int lb = 0; lb < LB; ++lb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[((size_t)p * A.Kp + e) * (16 * LB) + lb * 16] = acc[p][lb][e];
+}
+
+#undef DWM_LOAD_V
+#undef DWM_STORE_V
+
+// sum of the partial dU over the splits, in split order
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ sum,
+                                                           long long n, int splits)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n) return;
+    // eight running sums so that eight loads are in flight; the order of the additions is fixed
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int s = 0;
+    for (; s + 8 <= splits; s += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] += partial[(size_t)(s + u) * n + e];
+    }
+    for (; s < splits; ++s) v[0] += partial[(size_t)s * n + e];
+    sum[e] = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+}
+
 // ---- step 4: dw = G^T (sum of partial dU) G, one thread per (row of a class, filter) ----
 __device__ __forceinline__ float gt_col(int l, int a, const float u[4])
 {
@@ -207,7 +397,7 @@ __global__ __launch_bounds__(256) void wgrad_final_kernel(DevPlan P, WgradArgs A
             float v = 0.f;
             if (i <= q.lh && j <= q.lw) {
                 const int p = q.plane0 + i * tw + j;
-                const float* src = partial + (size_t)A.poff64[p] * 64 + (size_t)k * (A.nlt[p] * 64) + l;
+                const float* src = partial + (size_t)A.poff64[p] * 64 + (size_t)k * A.lstride[p] + l;
                 for (int s = 0; s < A.splits; ++s) v += src[(size_t)s * A.split_floats];
             }
             u[i][j] = v;
@@ -238,7 +428,96 @@ struct dwm_bwd_filter_plan {
     dwm::WgradArgs a;
     size_t fwd_ws_bytes, dm_bytes, partial_bytes;
     float* ws;
+    // short-reduction form (every class has at most 32 rows): one launch per class
+    bool small;
+    int small_kt;                      // 64-filter tiles
+    size_t sum_bytes;                  // the summed dU after the partials
+    dwm::SmallArgs sc[dwm::kMaxClasses];
 };
+
+namespace dwm {
+
+template <int LH, int LW>
+static void launch_small_lb(int lb, dim3 grid, hipStream_t s, const SmallArgs& a, const float* dy, const float* V,
+                            float* partial)
+{
+    const int lds = 2 * (LH + 1) * (LW + 1) * lb * 16 * 16 * (int)sizeof(float);  // two chunks of the class's V
+    if (lb == 2) {
+        auto kernel = wgrad_small_kernel<LH, LW, 2>;
+        if (lds > 40 * 1024) {
+            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+            (void)attr;
+        }
+        hipLaunchKernelGGL(kernel, grid, dim3(256), lds, s, a, dy, V, partial);
+    } else {
+        hipLaunchKernelGGL((wgrad_small_kernel<LH, LW, 1>), grid, dim3(256), lds, s, a, dy, V, partial);
+    }
+}
+
+static void launch_small(int lh, int lw, int lb, dim3 grid, hipStream_t s, const SmallArgs& a, const float* dy,
+                         const float* V, float* partial)
+{
+    switch (lh * 4 + lw) {
+        case 3 * 4 + 3: launch_small_lb<3, 3>(lb, grid, s, a, dy, V, partial); break;
+        case 3 * 4 + 2: launch_small_lb<3, 2>(lb, grid, s, a, dy, V, partial); break;
+        case 3 * 4 + 1: launch_small_lb<3, 1>(lb, grid, s, a, dy, V, partial); break;
+        case 2 * 4 + 3: launch_small_lb<2, 3>(lb, grid, s, a, dy, V, partial); break;
+        case 2 * 4 + 2: launch_small_lb<2, 2>(lb, grid, s, a, dy, V, partial); break;
+        case 2 * 4 + 1: launch_small_lb<2, 1>(lb, grid, s, a, dy, V, partial); break;
+        case 1 * 4 + 3: launch_small_lb<1, 3>(lb, grid, s, a, dy, V, partial); break;
+        case 1 * 4 + 2: launch_small_lb<1, 2>(lb, grid, s, a, dy, V, partial); break;
+        default: launch_small_lb<1, 1>(lb, grid, s, a, dy, V, partial); break;
+    }
+}
+
+// The short-reduction form applies when every class has at most 32 (padded) rows and there are
+// enough tiles to fill the chip with one class at a time (it is one launch per class: on a small
+// layer the GEMM form's four launches are faster).  The tiles are cut into ranges so that one
+// class's launch puts two workgroups on every CU.
+static bool small_setup(dwm_bwd_filter_plan& bp)
+{
+    const DevPlan& d = bp.fwd->d;
+    if (d.T < 16384) return false;
+    for (int c = 0; c < d.ncls; ++c)
+        if (d.cls[c].Lpad > 32) return false;
+    WgradArgs& a = bp.a;
+    bp.small_kt = a.Kp / 64;
+    const long long t16 = ((long long)d.T + 15) / 16 * 16;
+    long long want = std::max(1, 2 * kNumCUs / bp.small_kt);
+    long long per = (t16 + want - 1) / want;
+    per = std::max<long long>(64, (per + 15) / 16 * 16);
+    const long long nsplit = (t16 + per - 1) / per;
+    if (per > 0x7fffffffLL || nsplit > 65535 * 16) return false;
+    long long off = 0;
+    for (int c = 0; c < d.ncls; ++c) {
+        const DevClass& q = d.cls[c];
+        const int lb = q.Lpad / 16, planes = (q.lh + 1) * (q.lw + 1);
+        SmallArgs& sa = bp.sc[c];
+        sa = SmallArgs{};
+        sa.K = d.K; sa.Kp = a.Kp; sa.T = d.T; sa.OH = d.OH; sa.OW = d.OW; sa.TH = d.TH; sa.TW = d.TW;
+        sa.vblock_rows = d.vblock_rows; sa.vrow0 = q.v_row0; sa.Lpad = q.Lpad;
+        sa.tiles_per_split = (int)per;
+        sa.poff = (int)off;
+        sa.div_tiles.init((unsigned)(d.TH * d.TW));
+        sa.div_tw.init((unsigned)d.TW);
+        for (int pl = 0; pl < planes; ++pl) {
+            a.poff64[q.plane0 + pl] = (int)((off + (long long)pl * a.Kp * 16 * lb) / 64);
+            a.lstride[q.plane0 + pl] = 16 * lb;
+        }
+        off += (long long)planes * a.Kp * 16 * lb;
+    }
+    if (off * nsplit > (1LL << 40)) return false;
+    for (int c = 0; c < d.ncls; ++c) bp.sc[c].split_floats = off;
+    a.split_floats = off;
+    a.splits = (int)nsplit;  // what the plan reports; the final kernel reads the summed dU (one "split")
+    bp.dm_bytes = 0;
+    bp.partial_bytes = ((size_t)nsplit * off * sizeof(float) + 255) / 256 * 256;
+    bp.sum_bytes = ((size_t)off * sizeof(float) + 255) / 256 * 256;
+    return true;
+}
+
+}  // namespace dwm
 
 extern "C" {
 
@@ -268,6 +547,7 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
     for (int p = 0; p < a.n_planes; ++p) {
         const DevPlaneEntry& e = fwd->planes.e[p];
         a.nlt[p] = (e.Lpad + 63) / 64;
+        a.lstride[p] = a.nlt[p] * 64;
         a.vrow[p] = (int)e.v_off64;
         a.tile0[p] = (int)tiles;
         a.poff64[p] = (int)floats64;
@@ -292,6 +572,8 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
     bp->fwd_ws_bytes = (dwm_plan_workspace_bytes(fwd) + (size_t)64 * 64 * sizeof(float) + 255) / 256 * 256;
     bp->dm_bytes = ((size_t)a.tblocks * a.dm_rows * 64 * sizeof(float) + 255) / 256 * 256;
     bp->partial_bytes = (size_t)a.splits * a.split_floats * sizeof(float);
+    bp->sum_bytes = 0;
+    bp->small = small_setup(*bp);
     *out = bp;
     return DWM_OK;
 }
@@ -317,7 +599,7 @@ dwm_status_t dwm_bwd_filter_plan_info(const dwm_bwd_filter_plan_t* plan, dwm_bwd
 
 size_t dwm_bwd_filter_workspace_bytes(const dwm_bwd_filter_plan_t* plan)
 {
-    return plan ? plan->fwd_ws_bytes + plan->dm_bytes + plan->partial_bytes : 0;
+    return plan ? plan->fwd_ws_bytes + plan->dm_bytes + plan->partial_bytes + plan->sum_bytes : 0;
 }
 
 dwm_status_t dwm_bwd_filter_set_workspace(dwm_bwd_filter_plan_t* plan, void* ws_dev, size_t bytes)
@@ -348,6 +630,19 @@ dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const f
     if (d.T & 63) {
         hipLaunchKernelGGL(wgrad_zero_tail_kernel, dim3(64), dim3(256), 0, s,
                            V + (size_t)(a.tblocks - 1) * a.vblock_rows * 64, a.vblock_rows, d.T & 63);
+    }
+    if (plan->small) {
+        // 2'. per class: partial dU straight from dy and V; 3'. their sum; 4. dw = G^T (sum) G
+        float* sum = partial + plan->partial_bytes / sizeof(float);
+        for (int c = 0; c < d.ncls; ++c)
+            launch_small(d.cls[c].lh, d.cls[c].lw, d.cls[c].Lpad / 16, dim3((unsigned)a.splits, (unsigned)plan->small_kt), s,
+                         plan->sc[c], dy_dev, V, partial);
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((a.split_floats + 255) / 256)), dim3(256), 0, s, partial,
+                           sum, a.split_floats, a.splits);
+        WgradArgs fa = a;
+        fa.splits = 1;
+        hipLaunchKernelGGL(wgrad_final_kernel, dim3((d.rows_total + 255) / 256, d.K), dim3(256), 0, s, d, fa, sum, dw_dev);
+        return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
     }
     // 2. dM = A dY A^T
     const DyShape ds{d.T, d.K, a.Kp, d.TH, d.TW, d.OH, d.OW, a.dm_rows};
