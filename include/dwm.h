@@ -256,7 +256,8 @@ DWM_API dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, con
  * forward pass's transformed input; the sum over tiles is a GEMM per Winograd-domain plane.
  * dw [K][C][R][S] is fully overwritten; results do not vary from run to run.
  * The plan takes the forward layer's shape; the workspace (dwm_bwd_filter_workspace_bytes,
- * 256-byte aligned) holds V, A dY A^T and the partial sums.  Conventions as for the forward calls.
+ * 256-byte aligned) holds V, A dY A^T (not for layers with few input channels, where it is never
+ * written to memory) and the partial sums.  Conventions as for the forward calls.
  */
 typedef struct dwm_bwd_filter_plan dwm_bwd_filter_plan_t;
 
