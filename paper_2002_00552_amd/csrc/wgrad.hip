@@ -557,9 +557,26 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
     a.tile0[a.n_planes] = (int)tiles;
     a.n_tiles = (int)tiles;
     a.split_floats = floats64 * 64;
-    // enough workgroups for two per CU, but never fewer than four blocks of tiles per range
-    long long splits = (2 * kNumCUs + tiles - 1) / tiles;
-    splits = std::max(1LL, std::min<long long>(splits, (a.tblocks + 3) / 4));
+    // How many ranges the tile axis is cut into.  The chip holds 2 workgroups per CU at a time, so
+    // the launch runs in ceil(tiles*splits / 512) rounds of ceil(tblocks/splits) chunks each
+    // (2.1 us per chunk-round measured: two workgroups share a CU's matrix cores), and every range
+    // writes a partial dU that is read back once (priced at 4 TB/s).  Never fewer than four blocks
+    // of tiles per range.
+    long long splits = 1;
+    {
+        const long long max_splits = std::max(1LL, std::min<long long>(32, (a.tblocks + 3) / 4));
+        const double partial_us = 2.0 * (double)floats64 * 64 * sizeof(float) / 4e6;
+        double best = 0.0;
+        for (long long sp = 1; sp <= max_splits; ++sp) {
+            const long long rounds = (tiles * sp + 2 * kNumCUs - 1) / (2 * kNumCUs);
+            const long long chunks = (a.tblocks + sp - 1) / sp;
+            const double t = 2.1 * (double)(rounds * chunks) + partial_us * (double)sp;
+            if (sp == 1 || t < best * 0.97) {  // a further cut must pay for itself clearly
+                best = t;
+                splits = sp;
+            }
+        }
+    }
     a.chunks_per_split = (int)((a.tblocks + splits - 1) / splits);
     a.splits = (a.tblocks + a.chunks_per_split - 1) / a.chunks_per_split;
     const long long lim = (1LL << 31) - 1;
