@@ -322,6 +322,7 @@ def main():
     st = torch.cuda.current_stream().cuda_stream
     xp, Up, yp = xd.data_ptr(), U.data_ptr(), y.data_ptr()
 
+    dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st)  # first call: code object load
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     ev[0].record()
     dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st)
