@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstring>
 #include <new>
 #include <vector>
 
@@ -43,6 +44,9 @@ struct dwm_bwd_data_plan {
     dwm::PlaneTable batch_planes;
     std::vector<size_t> ws_off;
     float* ws;
+    // ... and, where their tile grids coincide, ONE input transform for all of them: a plan that
+    // holds every sub-convolution's pieces and classes (used by the input transform only)
+    dwm_plan_t* merged;
 };
 
 namespace dwm {
@@ -79,6 +83,111 @@ static int ceil_div(int x, int d) { return x >= 0 ? (x + d - 1) / d : -((-x) / d
 
 }  // namespace dwm
 
+
+// (the batch's plane table with every plane pointing into its own sub-convolution's V)
+static void setup_batch_unmerged_planes(dwm_bwd_data_plan& bp, const std::vector<int>& subs)
+{
+    for (int q = 0; q < bp.batch.nprob; ++q) {
+        const dwm_plan_t* sp = bp.phases[subs[q]].sub;
+        for (int e = 0; e < sp->planes.n; ++e) bp.batch_planes.e[bp.batch.p[q].plane0 + e].v_off64 = sp->planes.e[e].v_off64;
+    }
+}
+
+// One input transform for all sub-convolutions.  They read the same dy; what differs is which
+// window of it a tile of phase (a, b) starts at.  A sub-convolution's patch element is at row
+// 2*ty + j + i - Ph_a of dy; with Ph = the largest Ph_a and j' = j + (Ph - Ph_a) that is
+// 2*ty + j' + i - Ph for all of them, so one plan can hold the pieces of every phase (those of
+// phase a once, shifted), and one class per (sub-convolution, class) whose parts are the products
+// of ITS phases' pieces.  The staged rows of dy are then fetched once instead of once per phase.
+// Applies when the tile grids coincide and the pieces and classes fit the plan's tables.
+static void setup_merged(dwm_bwd_data_plan& bp, const std::vector<int>& subs)
+{
+    using namespace dwm;
+    bp.merged = nullptr;
+    const dwm_plan_t* first = bp.phases[subs[0]].sub;
+    int Ph = first->d.Ph, Pw = first->d.Pw, ncls = 0;
+    for (int i : subs) {
+        const DevPlan& d = bp.phases[i].sub->d;
+        if (d.TH != first->d.TH || d.TW != first->d.TW || d.T != first->d.T || d.OH != first->d.OH ||
+            d.OW != first->d.OW)
+            return;
+        Ph = std::max(Ph, d.Ph);
+        Pw = std::max(Pw, d.Pw);
+        ncls += d.ncls;
+    }
+    if (ncls > kMaxClasses) return;
+    dwm_plan* m = new (std::nothrow) dwm_plan;
+    if (!m) return;
+    std::memset(m, 0, sizeof(*m));
+    DevPlan& d = m->d;
+    d = first->d;
+    d.Ph = Ph; d.Pw = Pw;
+    d.nh = d.nw = d.ncls = d.rows_total = d.vblock_rows = 0;
+    // pieces: those of phase a (rows) / b (columns) once
+    std::vector<int> hoff(bp.s, -1), woff(bp.s, -1);
+    bool ok = true;
+    for (int i : subs) {
+        const auto& ph = bp.phases[i];
+        const DevPlan& sd = ph.sub->d;
+        if (hoff[ph.a] < 0) {
+            if (d.nh + sd.nh > kMaxPieces) { ok = false; break; }
+            hoff[ph.a] = d.nh;
+            for (int q = 0; q < sd.nh; ++q) {
+                DevPiece pc = sd.ph[q];
+                pc.j += Ph - sd.Ph;
+                d.ph[d.nh++] = pc;
+            }
+        }
+        if (woff[ph.b] < 0) {
+            if (d.nw + sd.nw > kMaxPieces) { ok = false; break; }
+            woff[ph.b] = d.nw;
+            for (int q = 0; q < sd.nw; ++q) {
+                DevPiece pc = sd.pw[q];
+                pc.j += Pw - sd.Pw;
+                d.pw[d.nw++] = pc;
+            }
+        }
+    }
+    long long v_off = 0;
+    if (ok)
+        for (int q = 0; q < bp.batch.nprob && ok; ++q) {
+            const auto& ph = bp.phases[subs[q]];
+            const DevPlan& sd = ph.sub->d;
+            for (int c = 0; c < sd.ncls; ++c) {
+                DevClass cl = sd.cls[c];
+                const int planes = (cl.lh + 1) * (cl.lw + 1);
+                cl.h0 += hoff[ph.a];
+                cl.w0 += woff[ph.b];
+                cl.row0 = d.rows_total;
+                cl.v_row0 = (int)v_off;
+                // this class's planes in the batch's table now point into the merged V
+                for (int pl = 0; pl < planes; ++pl)
+                    bp.batch_planes.e[bp.batch.p[q].plane0 + sd.cls[c].plane0 + pl].v_off64 = (uint32_t)(v_off + (long long)pl * cl.Lpad);
+                d.cls[d.ncls++] = cl;
+                d.rows_total += cl.Lpad;
+                v_off += (long long)planes * cl.Lpad;
+                if (v_off * d.Tpad >= ((1LL << 31) - 1) * 32) ok = false;
+            }
+        }
+    if (!ok) {
+        delete m;
+        setup_batch_unmerged_planes(bp, subs);
+        return;
+    }
+    d.vblock_rows = (int)v_off;
+    m->v_floats = (size_t)v_off * (size_t)d.Tpad;
+    m->lgran = bp.batch_lc;
+    m->variant_input = -1;
+    m->variant_forward = 0;
+    m->inlds_ok = input_lds_setup(*m, &m->inlds, 0);
+    for (int q = 0; q < bp.batch.nprob; ++q) {
+        bp.batch.p[q].vblock = d.vblock_rows * 64;
+        bp.batch.p[q].v_base = 0;
+    }
+    bp.ws_bytes = std::max<size_t>((m->v_floats * sizeof(float) + 255) / 256 * 256 + 256, 256);
+    bp.merged = m;
+}
+
 // One launch for the contractions of all sub-convolutions where that applies: at least two of
 // them, all on the staged path, their planes fit one table.  The sub-convolutions are ordered
 // longest first; each keeps its own slice of the workspace (its V is alive until the one launch).
@@ -86,6 +195,7 @@ static void setup_batch(dwm_bwd_data_plan& bp)
 {
     using namespace dwm;
     bp.batched = false;
+    bp.merged = nullptr;
     bp.ws = nullptr;
     bp.ws_off.assign(bp.phases.size(), 0);
     std::vector<int> subs;
@@ -141,6 +251,7 @@ static void setup_batch(dwm_bwd_data_plan& bp)
     bp.batch_lc = lc;
     bp.ws_bytes = std::max<size_t>(ws, 256);
     bp.batched = true;
+    setup_merged(bp, subs);
 }
 
 extern "C" {
@@ -217,6 +328,7 @@ dwm_status_t dwm_bwd_data_plan_destroy(dwm_bwd_data_plan_t* plan)
     if (!plan) return DWM_ERR_INVALID_ARG;
     for (auto& ph : plan->phases)
         if (ph.sub) dwm_plan_destroy(ph.sub);
+    delete plan->merged;
     delete plan;
     return DWM_OK;
 }
@@ -257,6 +369,13 @@ dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void* ws_dev,
 {
     if (!plan) return DWM_ERR_INVALID_ARG;
     if (bytes < plan->ws_bytes) return DWM_ERR_WORKSPACE;
+    if (plan->merged) {
+        if (!ws_dev || ((uintptr_t)ws_dev & 255u)) return DWM_ERR_WORKSPACE;
+        plan->merged->ws = static_cast<float*>(ws_dev);
+        plan->merged->ws_bytes = bytes;
+        plan->ws = static_cast<float*>(ws_dev);
+        return DWM_OK;
+    }
     for (size_t i = 0; i < plan->phases.size(); ++i) {
         auto& ph = plan->phases[i];
         if (!ph.sub) continue;
@@ -301,6 +420,7 @@ dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float
             if (hipGetLastError() != hipSuccess) return DWM_ERR_HIP;
             continue;
         }
+        if (plan->merged) continue;  // one input transform for all of them, below
         if (plan->batched) {  // its input transform now, its contraction with all the others below
             if (!plan->ws) return DWM_ERR_WORKSPACE;
             const dwm_status_t st = dwm::launch_input_transform(*ph.sub, dy_dev, ph.sub->ws, stream);
@@ -308,6 +428,11 @@ dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float
             continue;
         }
         const dwm_status_t st = dwm_conv_forward(ph.sub, dy_dev, Ugw_dev + ph.u_off, dx_dev, stream);
+        if (st != DWM_OK) return st;
+    }
+    if (plan->merged) {
+        if (!plan->ws) return DWM_ERR_WORKSPACE;
+        const dwm_status_t st = dwm::launch_input_transform(*plan->merged, dy_dev, plan->ws, stream);
         if (st != DWM_OK) return st;
     }
     if (plan->batched)

@@ -72,6 +72,10 @@ SHAPES = [  # N, C, H, W, K, R, S, stride, pad
     (1, 5, 20, 18, 140, 4, 6, 3, 2),     # nine sub-convolutions of different extents contracted in one launch
     (2, 9, 17, 22, 200, 5, 5, 2, 2),     # four, 3- and 2-tap phases: several classes per sub-convolution
     (1, 4, 23, 23, 130, 11, 11, 4, 0),   # sixteen: too many planes for one table, run one after the other
+    (2, 10, 20, 24, 150, 3, 3, 2, 1),    # even sizes: equal tile grids, ONE input transform for the four sub-convolutions
+    (1, 6, 16, 16, 130, 7, 7, 2, 3),     # the same with nine classes in the merged plan (3+1 and 3 taps per phase)
+    (1, 4, 18, 18, 140, 5, 5, 3, 1),     # stride 3: nine sub-convolutions of 2x2 .. 1x1 taps
+    (3, 5, 12, 12, 128, 2, 2, 2, 0),     # one tap per phase: four 1x1 sub-convolutions
 ]
 
 
