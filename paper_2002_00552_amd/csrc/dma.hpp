@@ -17,6 +17,17 @@ __device__ __forceinline__ void dma16(const float* g, uint32_t lds_byte_addr_uni
                  : "memory");
 }
 
+// The same DMA with the address split into a wave-uniform base (a scalar register pair) and
+// the lane's unsigned 32-bit byte offset: stepping the base costs no vector instruction.
+__device__ __forceinline__ void dma16s(const float* base_uniform, uint32_t lane_byte_offset,
+                                       uint32_t lds_byte_addr_uniform)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_byte_offset), "s"(base_uniform), "s"(lds_byte_addr_uniform)
+                 : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {

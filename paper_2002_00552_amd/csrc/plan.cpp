@@ -185,7 +185,10 @@ static dwm_status_t plan_build(dwm_plan_t** out, const dwm::PlanSpec& sp, bool e
                 const long long L = (long long)q.hn * q.wn * C;
                 const long long Lpad = round_up(L, lgran);
                 const int planes = (lh + 1) * (lw + 1);
-                if (Lpad >= lim) { ok = false; break; }
+                // the contraction's DMA addresses a lane's share of a chunk with an unsigned 32-bit
+                // byte offset from the chunk's base: up to 128 rows of U (row length Lpad), and one
+                // V block (v_off rows of 64 tiles) plus a chunk
+                if (Lpad > (1LL << 22)) { ok = false; break; }
                 q.L = (int)L; q.Lpad = (int)Lpad;
                 q.row0 = d.rows_total; q.plane0 = p->planes.n;
                 q.u_off = u_off; q.v_row0 = (int)v_off;
@@ -207,7 +210,7 @@ static dwm_status_t plan_build(dwm_plan_t** out, const dwm::PlanSpec& sp, bool e
                     }
                 u_off += planes * Kpad * Lpad;
                 v_off += planes * Lpad;  // rows of a V block so far
-                if (u_off >= lim * 32 || v_off * Tpad >= lim * 32) { ok = false; break; }
+                if (u_off >= lim * 32 || v_off * Tpad >= lim * 32 || v_off > (1LL << 23)) { ok = false; break; }
                 for (int a = 0; a < q.hn; ++a)
                     for (int b = 0; b < q.wn; ++b) {
                         dwm_part_t& pt = p->parts[n_parts++];
