@@ -56,20 +56,20 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
         if (LC == 32) return ((i >> 1) & 7) ^ ((i & 1) << 2);
         return i & 15;
     };
-    int a_row[A_I], a_col[A_I], b_row[B_I], b_col[B_I];
+    uint32_t a_row4[A_I], a_col4[A_I];  // 4 * row, 4 * column: byte offset = a_row4 * Lpad + a_col4
+    uint32_t b_voff[B_I];               // bytes
 #pragma unroll
     for (int q = 0; q < A_I; ++q) {
         const int s = (wave * A_I + q) * 64 + lane;
         const int row = s / A_C4, cp = s % A_C4;
-        a_row[q] = row;
-        a_col[q] = (cp ^ a_swz(row & 31)) * 4;
+        a_row4[q] = (uint32_t)row * 4u;
+        a_col4[q] = (uint32_t)(cp ^ a_swz(row & 31)) * 16u;
     }
 #pragma unroll
     for (int q = 0; q < B_I; ++q) {
         const int s = (wave * B_I + q) * 64 + lane;
         const int row = s / B_C4, sp = s % B_C4;
-        b_row[q] = row;
-        b_col[q] = (sp ^ (((row >> 2) & 1) << 3)) * 4;  // TT = 64: one V block
+        b_voff[q] = (uint32_t)(row * 64 + (sp ^ (((row >> 2) & 1) << 3)) * 4) * 4u;  // TT = 64: one V block
     }
     const int swz = a_swz(li);
 
@@ -85,55 +85,51 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
     int p = Q.plane0, j = 0;
     int nch = PT.e[p].Lpad / LC;
 
-    // issue cursor: the chunk whose loads go out next; parks on the last chunk
-    int ip = p, ij = 0, inch = nch, istage = 0, ileft = nit;
-    const float* pa[A_I];
-    const float* pb[B_I];
-    auto point_at = [&](int pl, int ch) {
+    // issue cursor: the chunk whose loads go out next; parks on the last chunk.  A DMA address is
+    // (uniform chunk base) + (the lane's byte offset inside the chunk): moving on is scalar arithmetic.
+    int ip = p, ij = 0, inch = nch, ileft = nit;
+    const float* sa;
+    const float* sb;
+    uint32_t ilpad;
+    auto point_at = [&](int pl) {
         const DevPlaneEntry e = PT.e[pl];
-        const float* Ub = U + (size_t)e.u_off64 * 64 + (size_t)(kt * KT) * e.Lpad + ch * LC;
-        const float* Vb = Vp + (size_t)tt * Q.vblock + ((size_t)e.v_off64 + ch * LC) * 64;
-#pragma unroll
-        for (int q = 0; q < A_I; ++q) pa[q] = Ub + (size_t)a_row[q] * e.Lpad + a_col[q];
-#pragma unroll
-        for (int q = 0; q < B_I; ++q) pb[q] = Vb + b_row[q] * 64 + b_col[q];
+        sa = U + (size_t)e.u_off64 * 64 + (size_t)(kt * KT) * e.Lpad;
+        sb = Vp + (size_t)tt * Q.vblock + (size_t)e.v_off64 * 64;
+        ilpad = (uint32_t)e.Lpad;
     };
-    point_at(ip, 0);
-    auto issue_one = [&](int d) {
-        const uint32_t sa = lds0 + (uint32_t)(istage * STAGE * 4);
-        if (d < A_I) dma16(pa[d], sa + (wave * A_I + d) * 1024);
-        else dma16(pb[d - A_I], sa + A_FLOATS * 4 + (wave * B_I + (d - A_I)) * 1024);
+    point_at(ip);
+    auto issue_one = [&](int d, int istage) {
+        const uint32_t ls = lds0 + (uint32_t)(istage * STAGE * 4);
+        if (d < A_I) dma16s(sa, __umul24(a_row4[d], ilpad) + a_col4[d], ls + (wave * A_I + d) * 1024);
+        else dma16s(sb, b_voff[d - A_I], ls + A_FLOATS * 4 + (wave * B_I + (d - A_I)) * 1024);
     };
     auto advance_issue = [&]() {
-        istage = istage + 1 == NS ? 0 : istage + 1;
         if (--ileft <= 0) return;  // parked: the same chunk is loaded again into a free stage
         if (++ij < inch) {
-#pragma unroll
-            for (int q = 0; q < A_I; ++q) pa[q] += LC;
-#pragma unroll
-            for (int q = 0; q < B_I; ++q) pb[q] += LC * 64;
+            sa += LC;
+            sb += LC * 64;
         } else {
             ++ip;
             ij = 0;
             inch = PT.e[ip].Lpad / LC;
-            point_at(ip, 0);
+            point_at(ip);
         }
     };
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) {
 #pragma unroll
-        for (int d = 0; d < N_DMA; ++d) issue_one(d);
+        for (int d = 0; d < N_DMA; ++d) issue_one(d, s);
         advance_issue();
     }
 
-    int stage = 0;
-    for (int it = 0; it < nit; ++it) {
+    auto chunk = [&](const int stage, const int it) {
         wait_vmcnt<(NS - 2) * N_DMA>();
         __syncthreads();
 
         const float* as = smem_b + stage * STAGE + (wave_m * 32 + li) * LC;
         const float* bs = smem_b + stage * STAGE + A_FLOATS + (4 * lh) * TT;
         const int bcol = (wave_n * 32 + li) ^ (lh << 5);
+        const int istage = (stage + NS - 1) % NS;
         float4 av[2];
         float bv[2][4];
         auto load_frags = [&](int g, int fb) {
@@ -153,10 +149,9 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
             }
 #pragma unroll
             for (int d = 0; d < N_DMA; ++d)
-                if (d * GROUPS / N_DMA == g) issue_one(d);
+                if (d * GROUPS / N_DMA == g) issue_one(d, istage);
         }
         advance_issue();
-        stage = stage + 1 == NS ? 0 : stage + 1;
 
         if (++j == nch) {
             // fold M_p into the 2x2 outputs
@@ -177,6 +172,14 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
                 j = 0;
                 nch = PT.e[p].Lpad / LC;
             }
+        }
+    };
+    // the ring position is a compile-time constant inside the body
+    for (int it = 0; it < nit;) {
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            if (it < nit) chunk(st, it);
+            ++it;
         }
     }
     // every DMA write (the parked re-loads too) has landed before the workgroup ends

@@ -403,18 +403,19 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
     // DMA instruction d of this wave is instruction i = d*NW + wave of the chunk; the first N_A
     // fill the U tile [RG][KT][8], the others the V tile [RG][TT][8]: instruction i lands at
     // byte i*1024 of the stage either way.
+    // A source address is (uniform base of the chunk in U or V) + (the lane's fixed byte offset).
     bool is_a[N_DMA];
-    int off[N_DMA];  // this lane's source offset from the tile's first element
+    uint32_t voff[N_DMA];
 #pragma unroll
     for (int d = 0; d < N_DMA; ++d) {
         const int i = d * NW + wave;
         is_a[d] = i < N_A;
         if (is_a[d]) {
             const int rg = i / (KT / 64), part = i % (KT / 64);
-            off[d] = (rg * A.Kpad + part * 64 + lane) * 8;
+            voff[d] = (uint32_t)((rg * A.Kpad + part * 64 + lane) * 8) * 2u;
         } else {
             const int rg = (i - N_A) / (TT / 64), blk = (i - N_A) % (TT / 64);
-            off[d] = blk * A.vblock + (rg * 64 + lane) * 8;
+            voff[d] = (uint32_t)(blk * A.vblock + (rg * 64 + lane) * 8) * 2u;
         }
     }
 
@@ -442,25 +443,24 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
         }
 
         // issue cursor: the chunk whose loads go out next; parks on the last chunk of the segment
-        int ip = p, ij = j, inch = nch, istage = 0, ileft = nit;
-        const half_t* src[N_DMA];
+        int ip = p, ij = j, inch = nch, ileft = nit;
+        const half_t* sa;
+        const half_t* sb;
         auto point_at = [&](int pl, int ch) {
             const DevPlaneEntry e = PT.e[pl];
-            const half_t* Ub = U + (size_t)e.u_off64 * 64 + (size_t)ch * LC * A.Kpad + (size_t)(kt * KT) * 8;
-            const half_t* Vb = V + (size_t)(tt * (TT / 64)) * A.vblock + ((size_t)e.v_off64 + ch * LC) * 64;
-#pragma unroll
-            for (int d = 0; d < N_DMA; ++d) src[d] = (is_a[d] ? Ub : Vb) + off[d];
+            sa = U + (size_t)e.u_off64 * 64 + (size_t)ch * LC * A.Kpad + (size_t)(kt * KT) * 8;
+            sb = V + (size_t)(tt * (TT / 64)) * A.vblock + ((size_t)e.v_off64 + ch * LC) * 64;
         };
         point_at(ip, ij);
-        auto issue_one = [&](int d) {
-            dma16(reinterpret_cast<const float*>(src[d]), lds0 + (uint32_t)(istage * STAGE + (d * NW + wave) * 1024));
+        auto issue_one = [&](int d, int istage) {
+            dma16s(reinterpret_cast<const float*>(is_a[d] ? sa : sb), voff[d],
+                   lds0 + (uint32_t)(istage * STAGE + (d * NW + wave) * 1024));
         };
         auto advance_issue = [&]() {
-            istage = istage + 1 == NS ? 0 : istage + 1;
             if (--ileft <= 0) return;  // parked: the same chunk is loaded again into a free stage
             if (++ij < inch) {
-#pragma unroll
-                for (int d = 0; d < N_DMA; ++d) src[d] += is_a[d] ? LC * A.Kpad : LC * 64;
+                sa += (size_t)LC * A.Kpad;
+                sb += LC * 64;
             } else {
                 ++ip;
                 ij = 0;
@@ -471,17 +471,17 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
 #pragma unroll
-            for (int d = 0; d < N_DMA; ++d) issue_one(d);
+            for (int d = 0; d < N_DMA; ++d) issue_one(d, s);
             advance_issue();
         }
 
-        int stage = 0;
-        for (int it = 0; it < nit; ++it) {
+        auto chunk = [&](const int stage, const int it) {
             wait_vmcnt<(NS - 2) * N_DMA>();
             __syncthreads();
 
             const unsigned char* as = smem16 + stage * STAGE + (lh * KT + wave_m * 32 * WM + li) * 16;
             const unsigned char* bs = smem16 + stage * STAGE + A_BYTES + (lh * TT + wave_n * 32 * WN + li) * 16;
+            const int istage = (stage + NS - 1) % NS;
             half8_t av[2][WM], bv[2][WN];
             auto load_frags = [&](int g, int fb) {
 #pragma unroll
@@ -503,11 +503,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
                                                                               0, 0, 0);
                 if (g == 0) {
 #pragma unroll
-                    for (int d = 0; d < N_DMA; ++d) issue_one(d);
+                    for (int d = 0; d < N_DMA; ++d) issue_one(d, istage);
                 }
             }
             advance_issue();
-            stage = stage + 1 == NS ? 0 : stage + 1;
 
             const bool plane_done = ++j == nch;
             if (plane_done || it + 1 == nit) {
@@ -538,6 +537,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
                     j = 0;
                     nch = PT.e[p].Lpad / LC;
                 }
+            }
+        };
+        // the ring position is a compile-time constant inside the body
+        for (int it = 0; it < nit;) {
+#pragma unroll
+            for (int st = 0; st < NS; ++st) {
+                if (it < nit) chunk(st, it);
+                ++it;
             }
         }
         // every DMA write (the parked re-loads too) has landed and every wave is done reading

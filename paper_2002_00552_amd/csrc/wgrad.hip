@@ -114,60 +114,70 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradArgs A, const f
     const int nit = c1 - c0;
 
     // this wave's DMA sources: rows of 64 floats, 16-byte group cp of row `row` goes to slot cp,
-    // fetched from group cp ^ (row & 15)
-    const float* pa[4];
-    const float* pb[4];
+    // fetched from group cp ^ (row & 15).  An address is (uniform chunk base) + (the lane's fixed
+    // byte offset): stepping to the next chunk is scalar arithmetic.
+    uint32_t voff[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int s = (wave * 4 + q) * 64 + lane;
         const int row = s >> 4, cp = s & 15;
-        const int off = row * 64 + ((cp ^ (row & 15)) << 2);
-        pa[q] = dM + ((size_t)c0 * A.dm_rows + (size_t)p * A.Kp + kt * 64) * 64 + off;
-        pb[q] = V + ((size_t)c0 * A.vblock_rows + A.vrow[p] + lt * 64) * 64 + off;
+        voff[q] = (uint32_t)(row * 64 + ((cp ^ (row & 15)) << 2)) * 4u;
     }
+    const float* sa = dM + ((size_t)c0 * A.dm_rows + (size_t)p * A.Kp + kt * 64) * 64;
+    const float* sb = V + ((size_t)c0 * A.vblock_rows + A.vrow[p] + lt * 64) * 64;
     const size_t stepA = (size_t)A.dm_rows * 64, stepB = (size_t)A.vblock_rows * 64;
-    int istage = 0, ileft = nit;
-    auto issue_chunk = [&]() {
-        const uint32_t sa = lds0 + (uint32_t)(istage * STAGE * 4);
+    int ileft = nit;
+    auto issue_chunk = [&](int istage) {
+        const uint32_t ls = lds0 + (uint32_t)(istage * STAGE * 4);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dma16(pa[q], sa + (wave * 4 + q) * 1024);
+        for (int q = 0; q < 4; ++q) dma16s(sa, voff[q], ls + (wave * 4 + q) * 1024);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dma16(pb[q], sa + TILE * 4 + (wave * 4 + q) * 1024);
-        istage = istage + 1 == NS ? 0 : istage + 1;
+        for (int q = 0; q < 4; ++q) dma16s(sb, voff[q], ls + TILE * 4 + (wave * 4 + q) * 1024);
         if (--ileft > 0) {  // the last chunk is simply loaded again: the counts stay uniform
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                pa[q] += stepA;
-                pb[q] += stepB;
-            }
+            sa += stepA;
+            sb += stepB;
         }
     };
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue_chunk();
+    for (int s = 0; s < NS - 1; ++s) issue_chunk(s);
 
     floatx16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
     const int swz = li & 15;
-    int stage = 0;
-    for (int it = 0; it < nit; ++it) {
+    auto chunk = [&](const int stage) {
         wait_vmcnt<(NS - 2) * N_DMA>();
         __syncthreads();
-        // chunk it has landed and every wave is done with the stage chunk it-1 was read from:
-        // that stage is refilled while this chunk is multiplied
-        issue_chunk();
+        // this chunk has landed and every wave is done with the stage the previous one was read
+        // from: that stage is refilled while this chunk is multiplied
+        issue_chunk((stage + NS - 1) % NS);
         const float* as = smem + stage * STAGE + (wave_m * 32 + li) * 64;
         const float* bs = smem + stage * STAGE + TILE + (wave_n * 32 + li) * 64;
+        // the fragments of group g+1 are read from LDS before the MFMAs of group g
+        float4 a4[2], b4[2];
+        a4[0] = *reinterpret_cast<const float4*>(as + ((lh ^ swz) << 2));
+        b4[0] = *reinterpret_cast<const float4*>(bs + ((lh ^ swz) << 2));
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
-            const float4 a4 = *reinterpret_cast<const float4*>(as + (((2 * g + lh) ^ swz) << 2));
-            const float4 b4 = *reinterpret_cast<const float4*>(bs + (((2 * g + lh) ^ swz) << 2));
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4.x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4.y, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4.z, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4.w, acc, 0, 0, 0);
+            if (g + 1 < 8) {
+                a4[(g + 1) & 1] = *reinterpret_cast<const float4*>(as + (((2 * g + 2 + lh) ^ swz) << 2));
+                b4[(g + 1) & 1] = *reinterpret_cast<const float4*>(bs + (((2 * g + 2 + lh) ^ swz) << 2));
+                __builtin_amdgcn_sched_barrier(0);  // or the scheduler sinks the reads to their uses
+            }
+            const float4 a = a4[g & 1], b = b4[g & 1];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
         }
-        stage = stage + 1 == NS ? 0 : stage + 1;
+    };
+    // the ring position is a compile-time constant inside the body
+    for (int it = 0; it < nit;) {
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            if (it < nit) chunk(st);
+            ++it;
+        }
     }
     wait_vmcnt<0>();
 
