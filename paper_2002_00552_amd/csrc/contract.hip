@@ -169,6 +169,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
             const float* bs = smem + stage * STAGE + A_FLOATS + (4 * lh) * TT;
             const int bcol = (wave_n * 32 * WN + li) ^ (lh << 5);
             const int istage = (stage + NS - 1) % NS;
+            const bool fresh = j == 0 || it == 0;  // first chunk of a plane, or of the segment
+            const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             // operand fragments of group g+1 are read from LDS before the MFMAs of group g
             float4 av[2][WM];
             float bv[2][4][WN];
@@ -192,9 +194,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                         const float4 a4 = av[g & 1][mi];
                         const float a_s = s == 0 ? a4.x : s == 1 ? a4.y : s == 2 ? a4.z : a4.w;
 #pragma unroll
-                        for (int nj = 0; nj < WN; ++nj)
-                            acc[mi][nj] =
-                                __builtin_amdgcn_mfma_f32_32x32x2f32(a_s, bv[g & 1][s][nj], acc[mi][nj], 0, 0, 0);
+                        for (int nj = 0; nj < WN; ++nj) {
+                            if (g == 0 && s == 0 && fresh) {
+                                // a plane's first product starts from zero: no accumulator is cleared
+                                acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s, bv[0][0][nj], zero16, 0, 0, 0);
+                            } else {
+                                acc[mi][nj] =
+                                    __builtin_amdgcn_mfma_f32_32x32x2f32(a_s, bv[g & 1][s][nj], acc[mi][nj], 0, 0, 0);
+                            }
+                        }
                     }
                 }
                 // the next chunk's loads are spread over the MFMA groups of this one
@@ -222,12 +230,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                                     Y[mi][nj][q][e] = fmaf(sg, acc[mi][nj][e], Y[mi][nj][q][e]);
                     }
                 }
-#pragma unroll
-                for (int mi = 0; mi < WM; ++mi)
-#pragma unroll
-                    for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) acc[mi][nj][e] = 0.f;
                 if (plane_done && it + 1 < nit) {
                     ++p;
                     j = 0;

@@ -482,6 +482,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
             const unsigned char* as = smem16 + stage * STAGE + (lh * KT + wave_m * 32 * WM + li) * 16;
             const unsigned char* bs = smem16 + stage * STAGE + A_BYTES + (lh * TT + wave_n * 32 * WN + li) * 16;
             const int istage = (stage + NS - 1) % NS;
+            const bool fresh = j == 0 || it == 0;  // first chunk of a plane, or of the segment
+            const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             half8_t av[2][WM], bv[2][WN];
             auto load_frags = [&](int g, int fb) {
 #pragma unroll
@@ -498,9 +500,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
 #pragma unroll
                 for (int mi = 0; mi < WM; ++mi)
 #pragma unroll
-                    for (int nj = 0; nj < WN; ++nj)
-                        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[g & 1][mi], bv[g & 1][nj], acc[mi][nj],
-                                                                              0, 0, 0);
+                    for (int nj = 0; nj < WN; ++nj) {
+                        if (g == 0 && fresh) {
+                            // a plane's first product starts from zero: no accumulator is cleared
+                            acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[0][mi], bv[0][nj], zero16, 0, 0, 0);
+                        } else {
+                            acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[g & 1][mi], bv[g & 1][nj],
+                                                                                  acc[mi][nj], 0, 0, 0);
+                        }
+                    }
                 if (g == 0) {
 #pragma unroll
                     for (int d = 0; d < N_DMA; ++d) issue_one(d, istage);
@@ -526,12 +534,6 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
                                     Y[mi][nj][q][e] = fmaf(sg, acc[mi][nj][e], Y[mi][nj][q][e]);
                     }
                 }
-#pragma unroll
-                for (int mi = 0; mi < WM; ++mi)
-#pragma unroll
-                    for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) acc[mi][nj][e] = 0.f;
                 if (plane_done && it + 1 < nit) {
                     ++p;
                     j = 0;
