@@ -41,12 +41,22 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
     const int li = lane & 31, lh = lane >> 5;
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem_b;
 
-    // which sub-convolution, which of its tiles (K tiles of one T tile next to each other)
+    // which sub-convolution, which of its tiles
     int pi = 0;
     while (pi + 1 < A.nprob && (int)blockIdx.x >= A.p[pi + 1].tile0) ++pi;
     const BatchProb Q = A.p[pi];
+    // Workgroups are dealt round-robin to the 8 XCDs: the K tiles of one T tile take launch
+    // positions that differ by multiples of 8, so they run on one XCD and share its L2.
     const int r0 = (int)blockIdx.x - Q.tile0;
-    const int kt = r0 % A.nkt, tt = r0 / A.nkt;
+    const int ntt = (Q.T + TT - 1) / TT, full8 = 8 * A.nkt * (ntt / 8);
+    int kt, tt;
+    if (r0 < full8) {
+        kt = (r0 >> 3) % A.nkt;
+        tt = ((r0 >> 3) / A.nkt) * 8 + (r0 & 7);
+    } else {
+        kt = (r0 - full8) % A.nkt;
+        tt = (ntt / 8) * 8 + (r0 - full8) / A.nkt;
+    }
     const float* Vp = V + Q.v_base;
 
     // per-lane source coordinates of this wave's DMA instructions (tile-relative); the XOR
