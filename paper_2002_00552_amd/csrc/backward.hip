@@ -199,7 +199,7 @@ static void setup_batch(dwm_bwd_data_plan& bp)
     bp.ws = nullptr;
     bp.ws_off.assign(bp.phases.size(), 0);
     std::vector<int> subs;
-    int planes = 0, lc = 64;
+    int planes = 0, lc = 32;  // 32-step chunks, three stages: 48 KB of LDS, three workgroups per CU (measured best)
     for (size_t i = 0; i < bp.phases.size(); ++i) {
         const dwm_plan_t* sp = bp.phases[i].sub;
         if (!sp) continue;
