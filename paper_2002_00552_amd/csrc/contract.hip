@@ -312,8 +312,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
     const int gidx = whole ? 0 : b - G.n_full;
     const int tile_base = whole ? b : G.n_full;
     const long long total = (long long)G.n_sk_tiles * G.n_iter;
-    long long lo = whole ? 0 : (long long)gidx * G.sk_ipw;
-    const long long hi = whole ? G.n_iter : (lo + G.sk_ipw < total ? lo + G.sk_ipw : total);
+    long long lo, hi;
+    if (whole) {
+        lo = 0;
+        hi = G.n_iter;
+    } else if (G.sk_f > 0) {  // piece gidx % sk_f of tile gidx / sk_f (empty if the tile ran out)
+        const long long t0 = (long long)(gidx / G.sk_f) * G.n_iter;
+        lo = t0 + (long long)(gidx % G.sk_f) * G.sk_ipw;
+        hi = lo + G.sk_ipw < t0 + G.n_iter ? lo + G.sk_ipw : t0 + G.n_iter;
+    } else {
+        lo = (long long)gidx * G.sk_ipw;
+        hi = lo + G.sk_ipw < total ? lo + G.sk_ipw : total;
+    }
     constexpr int SLOT = KT * TT * 4;  // floats per partial output
     while (lo < hi) {
         const int trel = (int)(lo / G.n_iter);
@@ -326,8 +336,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
         bool store = nit == G.n_iter;  // the whole tile was computed here
         if (!store) {
             // contributors of this tile, in iteration order
-            const int g_first = (int)(((long long)trel * G.n_iter) / G.sk_ipw);
-            const int g_last = (int)((((long long)trel + 1) * G.n_iter - 1) / G.sk_ipw);
+            const int g_first = G.sk_f > 0 ? trel * G.sk_f : (int)(((long long)trel * G.n_iter) / G.sk_ipw);
+            const int g_last = G.sk_f > 0 ? g_first + (G.n_iter - 1) / G.sk_ipw
+                                          : (int)((((long long)trel + 1) * G.n_iter - 1) / G.sk_ipw);
             const int nc = g_last - g_first + 1;
             // partial outputs of this tile: [contributor][(block*4 + q)*4 + e/4][thread][4 floats], accessed
             // as a raw buffer with device scope (the accesses complete, or are served, at the

@@ -101,9 +101,28 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
     // (there is no full round whose workgroups share the CUs with the ranges) costs more in
     // partial outputs and their summing than the idle CUs do: measured 0.42 -> 0.26 ms on the
     // four sub-convolutions of the stride-2 layer's data gradient.
-    if (g.n_full == 0 && rest * 2 >= kNumCUs) { g.n_full = g.ntiles; rest = 0; }
+    if (g.n_full == 0 && rest * 2 >= kNumCUs && sk_slots == kNumCUs) { g.n_full = g.ntiles; rest = 0; }
+    // At most one workgroup per CU, all of them whole tiles, and long tiles: a CU's four SIMDs
+    // would run one wave each, with nothing to issue while that wave waits at a barrier or for
+    // LDS.  Every tile is cut into 2..4 ranges of its own instead, so that a CU holds two
+    // workgroups that finish together (measured on 256-tile layers: 58 % -> 77-83 % of the MFMA
+    // peak); ranges that do not straddle tiles keep the K tiles of a T tile on one XCD.
+    g.sk_f = 0;
+    // (single precision only: the half-precision contraction is bound by operand delivery, not by
+    // issue gaps, and lost 8-60 % with its tiles cut this way)
+    if (p.sk_mode == 0 && variant < kFirstHalfVariant && rest == 0 && g.ntiles <= kNumCUs && g.ntiles * 2 > kNumCUs &&
+        g.n_iter >= 32) {
+        g.sk_f = 2;
+        g.n_full = 0;
+        rest = g.ntiles;
+    }
     g.n_sk_tiles = rest;
-    if (rest > 0) {
+    if (g.sk_f > 0) {
+        g.sk_ipw = (g.n_iter + g.sk_f - 1) / g.sk_f;
+        g.sk_wgs = rest * g.sk_f;
+        g.sk_maxc = g.sk_f;
+        g.partial_floats = (size_t)rest * g.sk_maxc * cv->kt() * cv->tt() * 4;
+    } else if (rest > 0) {
         const long long total = (long long)rest * g.n_iter;
         long long wgs = total < sk_slots ? total : sk_slots;
         long long ipw = (total + wgs - 1) / wgs;

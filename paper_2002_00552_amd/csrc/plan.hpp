@@ -112,6 +112,8 @@ struct ContractGeometry {
     int sk_wgs;      // stream-K workgroups
     int sk_ipw;      // iterations per stream-K workgroup
     int sk_maxc;     // partial-output slots per shared tile
+    int sk_f;        // > 0: every stream-K tile is cut into sk_f ranges of sk_ipw iterations of its own
+                     // (range g = piece g % sk_f of tile g / sk_f); 0: equal ranges of the flattened axis
     size_t partial_floats;
 };
 

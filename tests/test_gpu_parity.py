@@ -203,6 +203,8 @@ E2E_SHAPES = [
     (1, 3, 9, 300, 4, 3, 5, 1, 2),       # one long row
     (1, 2, 150, 700, 3, 5, 5, 2, 2),     # several bands of tile rows in the input transform
     (2, 2, 301, 64, 3, 7, 3, 1, 3),      # tall image
+    (3, 16, 56, 56, 256, 5, 5, 1, 2),    # 148 long tiles on 256 CUs: every tile is cut into two ranges of its own
+    (11, 32, 56, 56, 256, 5, 5, 2, 2),   # the same with 136 tiles of 49 32-step chunks (odd: ranges of 25 and 24)
 ]
 
 

@@ -225,3 +225,22 @@ def test_half_plan_error_codes():
     p32 = dwm.dwm_plan_create(2, 64, 16, 16, 128, 3, 3, 1, 1)
     assert L.dwm_plan_set_variant(p32, b"contract", 32) == dwm.DWM_ERR_INVALID_ARG
     dwm.dwm_plan_destroy(p32)
+
+
+def test_workspace_holds_two_partial_outputs_per_tile_when_every_tile_is_cut():
+    """Between half a tile and one tile per CU, with long tiles, the contraction cuts every tile
+    into two ranges of its own: the workspace then holds two 64x64x(2x2) partial outputs per tile
+    after V.  With short tiles (few chunks) or more tiles than CUs it does not."""
+    def extra(shape):
+        p = dwm.dwm_plan_create(*shape)
+        info = dwm.dwm_plan_info(p)
+        e = dwm.dwm_plan_workspace_bytes(p) - 4 * info.Vblock * (info.Tpad // 64)
+        tiles = ((info.K + 63) // 64) * ((info.T + 63) // 64)
+        dwm.dwm_plan_destroy(p)
+        return e, tiles
+    e, tiles = extra((3, 16, 56, 56, 256, 5, 5, 1, 2))
+    assert tiles == 148 and e >= tiles * 2 * 64 * 64 * 4 * 4
+    e, tiles = extra((3, 16, 56, 56, 256, 3, 3, 1, 1))   # 16 chunks per tile: whole tiles
+    assert tiles == 148 and e < 64 * 64 * 4 * 4
+    e, tiles = extra((8, 16, 56, 56, 256, 5, 5, 1, 2))   # 392 tiles: one round of whole tiles + ranges
+    assert tiles == 392 and e < tiles * 2 * 64 * 64 * 4 * 4
