@@ -331,3 +331,25 @@ def test_benchmark_layers_full_size(index):
     mse = float(np.mean((got - ref) ** 2))
     print("%s: max rel err %.3e, MSE %.3e, log10(MSE)+10 = %.2f" %
           (L.name, np.max(np.abs(got - ref)) / scale, mse, np.log10(mse) + 10))
+
+
+@pytest.mark.parametrize("kernel,hw,stride", [(7, 14, 2),    # 256 tiles: every tile cut into two ranges of its own
+                                              (3, 28, 1),    # 1568 tiles: three workgroups per CU
+                                              (5, 14, 1)])   # 784 tiles, four classes
+def test_paper_layers_full_size(kernel, hw, stride):
+    """The paper's own single-layer shapes (Sec. 5.1: batch 256, same padding, standard-normal
+    inputs and weights) at full size, in the launch configuration the planner picks; the oracle
+    computes 20 000 sampled outputs one by one."""
+    L = wl.paper_layer(kernel, hw, stride)
+    x, w = wl.make_layer_tensors(L, 10 * kernel + stride)
+    y = conv(x, w, L.stride, L.pad)
+    OH, OW = wl.out_hw(L)
+    assert y.shape == (L.N, L.K, OH, OW) and np.all(np.isfinite(y))
+    rng = np.random.default_rng(777 + kernel)
+    idx = rng.choice(y.size, 20000, replace=False)
+    n, k = L.N - 1, L.K - 1
+    edge = [((n * L.K + k) * OH + OH - 1) * OW + j for j in range(OW)] + [j for j in range(OW)]
+    idx = np.unique(np.concatenate([idx, np.array(edge)]))
+    ref = oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
+    got = y.ravel()[idx].astype(np.float64)
+    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= TOL, L.name
