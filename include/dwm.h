@@ -160,7 +160,11 @@ DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size
  *               2, 3 = LDS-staged form (channel groups fastest / blocks fastest; refused when the
  *               rows one block of 64 tiles needs do not fit in LDS);
  *   "input_cg": channels per workgroup of the LDS-staged form (0 = planner's choice);
- *   "split":    0 = whole tiles + split remainder, 1 = all tiles split evenly, 2 = whole tiles only (contraction).  For tuning and tests; results are the same up to fp32 rounding.
+ *   "split":    how the contraction shares out its tiles: 0 = planner's choice (whole tiles for every
+ *               full round of the CUs + the remainder cut into equal ranges; with at most one long
+ *               tile per CU, every tile cut into two ranges of its own), 1 = one round and a
+ *               remainder are cut into equal ranges altogether, 2 = whole tiles only.  For tuning
+ *               and tests; results are the same up to fp32 rounding.
  * The workspace size depends on the contraction variant: choose it BEFORE asking
  * dwm_plan_workspace_bytes.  DWM_ERR_INVALID_ARG for an unknown stage or a variant that does
  * not apply to this plan; DWM_ERR_WORKSPACE (variant unchanged) if a workspace was already
