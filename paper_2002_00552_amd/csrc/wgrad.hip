@@ -224,13 +224,14 @@ struct SmallArgs {
 };
 
 template <int LH, int LW, int LB>
-__global__ __launch_bounds__(256, 2) void wgrad_small_kernel(SmallArgs A, const float* __restrict__ dy,
-                                                             const float* __restrict__ V, float* __restrict__ partial)
+__device__ __forceinline__ void wgrad_small_body(const SmallArgs& A, const float* __restrict__ dy,
+                                                 const float* __restrict__ V, float* __restrict__ partial,
+                                                 const int split, const int kt, float (*dys)[16][68],
+                                                 float* __restrict__ vs)
 {
     constexpr int NH = LH + 1, NW = LW + 1;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int ln = lane & 15, q = lane >> 4;
-    const int split = blockIdx.x, kt = blockIdx.y;
     const int tiles = A.TH * A.TW;
 
     floatx4 acc[NH * NW][LB];
@@ -244,11 +245,9 @@ __global__ __launch_bounds__(256, 2) void wgrad_small_kernel(SmallArgs A, const 
     // rows of the 16 tiles (lane = (row a, tile, column b): 128 contiguous bytes per row where the
     // tiles are neighbours); a lane then picks up the 2x2 blocks of ITS filter and four tiles with
     // four 16-byte LDS reads.  Rows are 68 floats apart (64 + 4: conflict-free 16-byte reads).
-    __shared__ __attribute__((aligned(16))) float dys[4][16][68];
     float(*my)[68] = dys[wave];
     // V of a chunk -- the class's rows x 16 tiles, the same for the four waves -- is loaded once
-    // per workgroup (a thread per (row, 16 bytes)), one chunk ahead, into one of two LDS buffers
-    extern __shared__ __attribute__((aligned(16))) float vs[];
+    // per workgroup (a thread per (row, 16 bytes)), one chunk ahead, into one of two LDS buffers (vs)
     constexpr int VROWS = NH * NW * LB * 16, VITEMS = (VROWS * 4 + 255) / 256;
     floatx4 vreg[VITEMS];
     // this thread's (row, 16 bytes) items: offsets inside the class's rows of a V block / an LDS buffer
@@ -359,6 +358,53 @@ __global__ __launch_bounds__(256, 2) void wgrad_small_kernel(SmallArgs A, const 
 #undef DWM_LOAD_V
 #undef DWM_STORE_V
 
+// All classes (of one LB) in ONE launch.  The classes of one (range of tiles, 64 filters) read the
+// same dy: their workgroups sit next to each other in launch order on one XCD (launch position
+// mod 8), so that dy comes from memory once and from that XCD's L2 for the other classes --
+// launched class by class, each class streamed all of dy from memory again.
+struct SmallAllArgs {
+    int ncls, nkt, splits;
+    int code[kMaxClasses];  // 4 * len_h + len_w
+    SmallArgs c[kMaxClasses];
+};
+
+template <int LB>
+__global__ __launch_bounds__(256, 2) void wgrad_small_all_kernel(SmallAllArgs AA, const float* __restrict__ dy,
+                                                                 const float* __restrict__ V,
+                                                                 float* __restrict__ partial)
+{
+    __shared__ __attribute__((aligned(16))) float dys[4][16][68];
+    extern __shared__ __attribute__((aligned(16))) float vs[];
+    // launch position -> (range of tiles, 64 filters, class): class fastest among the groups of eight
+    const int b = blockIdx.x, s_lo = b & 7;
+    int r = b >> 3;
+    const int ci = r % AA.ncls;
+    r /= AA.ncls;
+    const int kt = r % AA.nkt;
+    const int split = (r / AA.nkt) * 8 + s_lo;
+    if (split >= AA.splits) return;
+    // the class's arguments through compile-time indexes (they stay in scalar registers)
+    SmallArgs A = AA.c[0];
+    int code = AA.code[0];
+#pragma unroll
+    for (int i = 1; i < kMaxClasses; ++i)
+        if (ci == i) {
+            A = AA.c[i];
+            code = AA.code[i];
+        }
+    switch (code) {
+        case 3 * 4 + 3: wgrad_small_body<3, 3, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 3 * 4 + 2: wgrad_small_body<3, 2, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 3 * 4 + 1: wgrad_small_body<3, 1, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 2 * 4 + 3: wgrad_small_body<2, 3, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 2 * 4 + 2: wgrad_small_body<2, 2, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 2 * 4 + 1: wgrad_small_body<2, 1, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 1 * 4 + 3: wgrad_small_body<1, 3, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        case 1 * 4 + 2: wgrad_small_body<1, 2, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+        default: wgrad_small_body<1, 1, LB>(A, dy, V, partial, split, kt, dys, vs); break;
+    }
+}
+
 // sum of the partial dU over the splits, in split order
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ sum,
                                                            long long n, int splits)
@@ -438,7 +484,7 @@ struct dwm_bwd_filter_plan {
     dwm::WgradArgs a;
     size_t fwd_ws_bytes, dm_bytes, partial_bytes;
     float* ws;
-    // short-reduction form (every class has at most 32 rows): one launch per class
+    // short-reduction form (every class has at most 32 rows): one launch for all classes of 16 rows, one for those of 32
     bool small;
     int small_kt;                      // 64-filter tiles
     size_t sum_bytes;                  // the summed dU after the partials
@@ -447,44 +493,30 @@ struct dwm_bwd_filter_plan {
 
 namespace dwm {
 
-template <int LH, int LW>
-static void launch_small_lb(int lb, dim3 grid, hipStream_t s, const SmallArgs& a, const float* dy, const float* V,
-                            float* partial)
+// One launch for the classes whose planes have 16 * lb rows.
+static dwm_status_t launch_small_all(int lb, const SmallAllArgs& aa, hipStream_t s, const float* dy, const float* V,
+                                     float* partial)
 {
-    const int lds = 2 * (LH + 1) * (LW + 1) * lb * 16 * 16 * (int)sizeof(float);  // two chunks of the class's V
+    int planes = 0;  // the largest class decides the LDS for V: two chunks of planes * lb * 16 rows x 16 tiles
+    for (int i = 0; i < aa.ncls; ++i) planes = std::max(planes, (aa.code[i] / 4 + 1) * (aa.code[i] % 4 + 1));
+    const int lds = 2 * planes * lb * 16 * 16 * (int)sizeof(float);
+    const dim3 grid((unsigned)((aa.splits + 7) / 8 * 8 * aa.nkt * aa.ncls));
     if (lb == 2) {
-        auto kernel = wgrad_small_kernel<LH, LW, 2>;
-        if (lds > 40 * 1024) {
-            static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-            (void)attr;
-        }
-        hipLaunchKernelGGL(kernel, grid, dim3(256), lds, s, a, dy, V, partial);
+        auto kernel = wgrad_small_all_kernel<2>;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        if (attr != hipSuccess) return DWM_ERR_HIP;
+        hipLaunchKernelGGL(kernel, grid, dim3(256), lds, s, aa, dy, V, partial);
     } else {
-        hipLaunchKernelGGL((wgrad_small_kernel<LH, LW, 1>), grid, dim3(256), lds, s, a, dy, V, partial);
+        hipLaunchKernelGGL(wgrad_small_all_kernel<1>, grid, dim3(256), lds, s, aa, dy, V, partial);
     }
-}
-
-static void launch_small(int lh, int lw, int lb, dim3 grid, hipStream_t s, const SmallArgs& a, const float* dy,
-                         const float* V, float* partial)
-{
-    switch (lh * 4 + lw) {
-        case 3 * 4 + 3: launch_small_lb<3, 3>(lb, grid, s, a, dy, V, partial); break;
-        case 3 * 4 + 2: launch_small_lb<3, 2>(lb, grid, s, a, dy, V, partial); break;
-        case 3 * 4 + 1: launch_small_lb<3, 1>(lb, grid, s, a, dy, V, partial); break;
-        case 2 * 4 + 3: launch_small_lb<2, 3>(lb, grid, s, a, dy, V, partial); break;
-        case 2 * 4 + 2: launch_small_lb<2, 2>(lb, grid, s, a, dy, V, partial); break;
-        case 2 * 4 + 1: launch_small_lb<2, 1>(lb, grid, s, a, dy, V, partial); break;
-        case 1 * 4 + 3: launch_small_lb<1, 3>(lb, grid, s, a, dy, V, partial); break;
-        case 1 * 4 + 2: launch_small_lb<1, 2>(lb, grid, s, a, dy, V, partial); break;
-        default: launch_small_lb<1, 1>(lb, grid, s, a, dy, V, partial); break;
-    }
+    return DWM_OK;
 }
 
 // The short-reduction form applies when every class has at most 32 (padded) rows and there are
-// enough tiles to fill the chip with one class at a time (it is one launch per class: on a small
-// layer the GEMM form's four launches are faster).  The tiles are cut into ranges so that one
-// class's launch puts two workgroups on every CU.
+// enough tiles to fill the chip (on a small layer the GEMM form's four launches are faster).  The
+// tiles are cut into ranges so that the workgroups of ONE class would put two workgroups on every CU;
+// all classes go out in one launch, several rounds deep.
 static bool small_setup(dwm_bwd_filter_plan& bp)
 {
     const DevPlan& d = bp.fwd->d;
@@ -661,9 +693,17 @@ dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const f
     if (plan->small) {
         // 2'. per class: partial dU straight from dy and V; 3'. their sum; 4. dw = G^T (sum) G
         float* sum = partial + plan->partial_bytes / sizeof(float);
-        for (int c = 0; c < d.ncls; ++c)
-            launch_small(d.cls[c].lh, d.cls[c].lw, d.cls[c].Lpad / 16, dim3((unsigned)a.splits, (unsigned)plan->small_kt), s,
-                         plan->sc[c], dy_dev, V, partial);
+        for (int lb = 1; lb <= 2; ++lb) {
+            SmallAllArgs aa{};
+            aa.nkt = plan->small_kt;
+            aa.splits = a.splits;
+            for (int c = 0; c < d.ncls; ++c)
+                if (d.cls[c].Lpad / 16 == lb) {
+                    aa.code[aa.ncls] = d.cls[c].lh * 4 + d.cls[c].lw;
+                    aa.c[aa.ncls++] = plan->sc[c];
+                }
+            if (aa.ncls > 0 && launch_small_all(lb, aa, s, dy_dev, V, partial) != DWM_OK) return DWM_ERR_HIP;
+        }
         hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((a.split_floats + 255) / 256)), dim3(256), 0, s, partial,
                            sum, a.split_floats, a.splits);
         WgradArgs fa = a;
