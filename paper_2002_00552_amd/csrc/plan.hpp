@@ -237,6 +237,8 @@ struct dwm_plan {
     dwm::FusedArgs fused;
     size_t uf_gap, uf_begin;  // end of what precedes its filter copy in Ugw, first float of the copy
     bool inlds_ok;      // the LDS-staged input transform applies (its staged rows fit in LDS)
+    bool skip_pad_rows; // the consumer of V never reads the rows past a class's reduction length: the
+                        // LDS-staged input transform does not write their zeros
     dwm::InLdsArgs inlds;
     bool use_fused() const { return fused_ok && variant_forward != 0; }
 

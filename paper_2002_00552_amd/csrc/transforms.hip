@@ -238,7 +238,7 @@ __device__ __forceinline__ void lds_class_rows(const DevPlan& P, const InLdsArgs
 __global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InLdsArgs A,
                                                                   const float* __restrict__ x,
                                                                   float* __restrict__ V, int* __restrict__ counters,
-                                                                  int n_counters, int chan_fast)
+                                                                  int n_counters, int chan_fast, int write_pad_rows)
 {
     extern __shared__ __attribute__((aligned(16))) float xs[];  // [cg][max_rows][nphase][lwp]
     if (blockIdx.x == 0)
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void input_transform_lds_kernel(DevPlan P, InL
             default: lds_class_rows<1, 1>(P, A, q, xl, vb, c0, cn, wave, valid); break;
         }
         // rows past the class's reduction length are zeros (the contraction multiplies them)
-        if (bc == 0 && valid) {
+        if (bc == 0 && valid && write_pad_rows) {
             const int planes = (q.lh + 1) * (q.lw + 1);
             for (int l = q.L + wave; l < q.Lpad; l += 4)
                 for (int pl = 0; pl < planes; ++pl) vb[((size_t)q.v_row0 + (size_t)pl * q.Lpad + l) * 64] = 0.f;
@@ -394,7 +394,7 @@ dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V,
             if (attr != hipSuccess) return DWM_ERR_HIP;
         }
         hipLaunchKernelGGL(kernel, dim3((unsigned)(nb * a.ncg)), block, a.lds_bytes, (hipStream_t)stream, d, a, x, V,
-                           p.sk_counters(), p.geo.n_sk_tiles, variant == 2);
+                           p.sk_counters(), p.geo.n_sk_tiles, variant == 2, p.skip_pad_rows ? 0 : 1);
         return check_launch();
     }
     int rows_fast = variant;

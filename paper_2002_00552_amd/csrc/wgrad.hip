@@ -217,6 +217,7 @@ __host__ __device__ constexpr int at_coef(int l, int a, int f)
 struct SmallArgs {
     int K, Kp, T, OH, OW, TH, TW;
     int vblock_rows, vrow0, Lpad;  // rows of a V block, the class's first row in it, rows per plane
+    int L;                         // of which real (the others are zeros, supplied here, not read)
     int tiles_per_split;           // a multiple of 16
     int poff;                      // floats from the start of a split's partial to this class's planes
     long long split_floats;
@@ -252,17 +253,20 @@ __device__ __forceinline__ void wgrad_small_body(const SmallArgs& A, const float
     floatx4 vreg[VITEMS];
     // this thread's (row, 16 bytes) items: offsets inside the class's rows of a V block / an LDS buffer
     int vsrc[VITEMS], vdst[VITEMS];
+    bool vreal[VITEMS];  // rows past the class's reduction length are not in memory: zeros
 #pragma unroll
     for (int it = 0; it < VITEMS; ++it) {
         const int idx = min((int)threadIdx.x + 256 * it, VROWS * 4 - 1);  // spare threads repeat the last item
         vsrc[it] = (idx >> 2) * 64 + 4 * (idx & 3);
         vdst[it] = idx * 4;
+        vreal[it] = ((idx >> 2) % (16 * LB)) < A.L;
     }
 #define DWM_LOAD_V(t0_)                                                                                     \
     {                                                                                                       \
         const float* vbase_ = V + ((size_t)((t0_) >> 6) * A.vblock_rows + A.vrow0) * 64 + ((t0_) & 63);       \
         _Pragma("unroll") for (int it = 0; it < VITEMS; ++it)                                               \
-            vreg[it] = *reinterpret_cast<const floatx4*>(vbase_ + vsrc[it]);                                 \
+            vreg[it] = vreal[it] ? *reinterpret_cast<const floatx4*>(vbase_ + vsrc[it])                      \
+                                 : floatx4{0.f, 0.f, 0.f, 0.f};                                              \
     }
 #define DWM_STORE_V(buf_)                                                                                   \
     {                                                                                                       \
@@ -538,7 +542,7 @@ static bool small_setup(dwm_bwd_filter_plan& bp)
         SmallArgs& sa = bp.sc[c];
         sa = SmallArgs{};
         sa.K = d.K; sa.Kp = a.Kp; sa.T = d.T; sa.OH = d.OH; sa.OW = d.OW; sa.TH = d.TH; sa.TW = d.TW;
-        sa.vblock_rows = d.vblock_rows; sa.vrow0 = q.v_row0; sa.Lpad = q.Lpad;
+        sa.vblock_rows = d.vblock_rows; sa.vrow0 = q.v_row0; sa.Lpad = q.Lpad; sa.L = q.L;
         sa.tiles_per_split = (int)per;
         sa.poff = (int)off;
         sa.div_tiles.init((unsigned)(d.TH * d.TW));
@@ -556,6 +560,7 @@ static bool small_setup(dwm_bwd_filter_plan& bp)
     bp.dm_bytes = 0;
     bp.partial_bytes = ((size_t)nsplit * off * sizeof(float) + 255) / 256 * 256;
     bp.sum_bytes = ((size_t)off * sizeof(float) + 255) / 256 * 256;
+    bp.fwd->skip_pad_rows = true;  // the class kernels supply the zero rows themselves
     return true;
 }
 
