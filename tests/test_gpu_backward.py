@@ -186,11 +186,12 @@ WSHAPES = SHAPES + [
     (70, 2, 6, 6, 3, 3, 3, 1, 1),        # many images: the tile axis spans several blocks and ranges
     (3, 5, 31, 33, 7, 5, 5, 1, 2),       # tile count not a multiple of 64: the zeroed tail columns
     (2, 66, 12, 12, 67, 3, 3, 1, 1),     # channels and filters just past a 64 tile
-    # few channels and many tiles: the short-reduction form (one launch per class, dy straight into the MFMA)
+    # few channels and many tiles: the short-reduction form (dy straight into the MFMA)
     (8, 3, 190, 181, 20, 7, 7, 2, 3),    # odd output sizes: masked rows and columns of dy, tail of the tile axis
     (21, 3, 227, 227, 33, 11, 11, 4, 0), # a class with two blocks of sixteen rows
     (4, 4, 128, 130, 70, 5, 5, 1, 2),    # filters past one 64-filter tile
     (16, 6, 130, 127, 16, 3, 3, 2, 1),   # classes of 2-tap and 1-tap pieces
+    (9, 3, 180, 180, 20, 9, 9, 2, 4),    # pieces of 3, 2 and 1 taps: all nine classes in the one launch
 ]
 
 
