@@ -191,7 +191,7 @@ WSHAPES = SHAPES + [
     (21, 3, 227, 227, 33, 11, 11, 4, 0), # a class with two blocks of sixteen rows
     (4, 4, 128, 130, 70, 5, 5, 1, 2),    # filters past one 64-filter tile
     (16, 6, 130, 127, 16, 3, 3, 2, 1),   # classes of 2-tap and 1-tap pieces
-    (9, 3, 180, 180, 20, 9, 9, 2, 4),    # pieces of 3, 2 and 1 taps: all nine classes in the one launch
+    (9, 3, 180, 180, 20, 9, 9, 2, 4),    # phases of five and four taps: sixteen parts in four classes, one launch
 ]
 
 
