@@ -259,7 +259,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1)
-    ap.add_argument("--paper-layer", type=str, default="", help="KERNEL,HW,STRIDE e.g. 7,14,1")
+    ap.add_argument("--paper-layer", type=str, default="", help="KERNEL,HW,STRIDE[,BATCH] e.g. 7,14,1")
     ap.add_argument("--contract-variant", type=int, default=-1)
     ap.add_argument("--input-variant", type=int, default=-1)
     ap.add_argument("--split-mode", type=int, default=-1)
@@ -288,8 +288,9 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     if args.paper_layer:
-        kern, hw, stride = (int(v) for v in args.paper_layer.split(","))
-        L = wl.paper_layer(kern, hw, stride)
+        vals = [int(v) for v in args.paper_layer.split(",")]
+        kern, hw, stride = vals[:3]
+        L = wl.paper_layer(kern, hw, stride, *vals[3:4])  # optional fourth value: batch size (the paper's is 256)
         x, w = wl.make_layer_tensors(L, 100 * kern + hw + stride)
     else:
         L = wl.CONFIGS[args.config]

@@ -107,19 +107,22 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
     // partial outputs and their summing than the idle CUs do: measured 0.42 -> 0.26 ms on the
     // four sub-convolutions of the stride-2 layer's data gradient.
     if (g.n_full == 0 && rest * 2 >= kNumCUs && sk_slots == kNumCUs) { g.n_full = g.ntiles; rest = 0; }
-    // At most one workgroup per CU, all of them whole tiles, and long tiles: a CU's four SIMDs
-    // would run one wave each, with nothing to issue while that wave waits at a barrier or for
-    // LDS.  Every tile is cut into 2..4 ranges of its own instead, so that a CU holds two
-    // workgroups that finish together (measured on 256-tile layers: 58 % -> 77-83 % of the MFMA
-    // peak); ranges that do not straddle tiles keep the K tiles of a T tile on one XCD.
-    g.sk_f = 0;
+    // At most one tile per CU, and long tiles: as whole tiles (or as one flattened range per CU) a
+    // CU's four SIMDs would run one wave each, with nothing to issue while that wave waits at a
+    // barrier or for LDS.  Every tile is cut into 2..8 ranges of its own instead -- about two
+    // workgroups per CU, which finish together, no range shorter than 16 chunks (measured on
+    // 256-tile layers: 58 % -> 77-86 % of the MFMA peak; on a 128-tile layer: 30 % -> 78 %); ranges that do not
+    // straddle tiles keep the K tiles of a T tile in step on one XCD, sharing V in its L2.
     // (single precision only: the half-precision contraction is bound by operand delivery, not by
     // issue gaps, and lost 8-60 % with its tiles cut this way)
-    if (p.sk_mode == 0 && variant < kFirstHalfVariant && rest == 0 && g.ntiles <= kNumCUs && g.ntiles * 2 > kNumCUs &&
-        g.n_iter >= 32) {
-        g.sk_f = 2;
-        g.n_full = 0;
-        rest = g.ntiles;
+    g.sk_f = 0;
+    if (p.sk_mode == 0 && variant < kFirstHalfVariant && g.ntiles <= kNumCUs && g.n_iter >= 32) {
+        const int f = std::min(std::min(8, 2 * kNumCUs / g.ntiles), g.n_iter / 16);
+        if (f >= 2) {
+            g.sk_f = f;
+            g.n_full = 0;
+            rest = g.ntiles;
+        }
     }
     g.n_sk_tiles = rest;
     if (g.sk_f > 0) {
