@@ -162,7 +162,7 @@ DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size
  *   "input_cg": channels per workgroup of the LDS-staged form (0 = planner's choice);
  *   "split":    how the contraction shares out its tiles: 0 = planner's choice (whole tiles for every
  *               full round of the CUs + the remainder cut into equal ranges; with at most one long
- *               tile per CU, every tile cut into two ranges of its own), 1 = one round and a
+ *               tile per CU, every tile cut into 2..8 ranges of its own), 1 = one round and a
  *               remainder are cut into equal ranges altogether, 2 = whole tiles only.  For tuning
  *               and tests; results are the same up to fp32 rounding.
  * The workspace size depends on the contraction variant: choose it BEFORE asking
