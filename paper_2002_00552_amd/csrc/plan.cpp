@@ -109,15 +109,23 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
     if (g.n_full == 0 && rest * 2 >= kNumCUs && sk_slots == kNumCUs) { g.n_full = g.ntiles; rest = 0; }
     // At most one tile per CU, and long tiles: as whole tiles (or as one flattened range per CU) a
     // CU's four SIMDs would run one wave each, with nothing to issue while that wave waits at a
-    // barrier or for LDS.  Every tile is cut into 2..8 ranges of its own instead -- about two
-    // workgroups per CU, which finish together, no range shorter than 16 chunks (measured on
+    // barrier or for LDS.  Every tile is cut into 2..8 ranges of its own instead -- two workgroups
+    // per CU, in as few and as full rounds as possible, no range shorter than 16 chunks (measured on
     // 256-tile layers: 58 % -> 77-86 % of the MFMA peak; on a 128-tile layer: 30 % -> 78 %); ranges that do not
     // straddle tiles keep the K tiles of a T tile in step on one XCD, sharing V in its L2.
     // (single precision only: the half-precision contraction is bound by operand delivery, not by
     // issue gaps, and lost 8-60 % with its tiles cut this way)
     g.sk_f = 0;
     if (p.sk_mode == 0 && variant < kFirstHalfVariant && g.ntiles <= kNumCUs && g.n_iter >= 32) {
-        const int f = std::min(std::min(8, 2 * kNumCUs / g.ntiles), g.n_iter / 16);
+        // the cut that needs the least time: rounds of two workgroups per CU, each round one range long
+        // (plus a little per range for its partial output)
+        int f = 1;
+        double best = 1e30;
+        for (int c = 2; c <= 8 && c <= g.n_iter / 16; ++c) {
+            const int rounds = (g.ntiles * c + 2 * kNumCUs - 1) / (2 * kNumCUs);
+            const double t = (double)rounds / c + 0.004 * c;
+            if (t < best) { best = t; f = c; }
+        }
         if (f >= 2) {
             g.sk_f = f;
             g.n_full = 0;
