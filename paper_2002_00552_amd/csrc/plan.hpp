@@ -102,7 +102,8 @@ constexpr int kNumCUs = 256;  // MI355X
 // cut along the flattened (plane, chunk) iteration axis into sk_wgs equal ranges, one
 // per extra workgroup, so that every CU ends up with the same amount of MFMA work; a
 // tile shared by several workgroups is summed from per-workgroup partial outputs by
-// whichever of them finishes last.
+// whichever of them finishes last.  A layer with at most one (long) tile per CU has no
+// whole-tile workgroups: each of its tiles is cut into sk_f ranges of its own.
 struct ContractGeometry {
     int variant;
     int nkt, ntt, ntiles, full8;
