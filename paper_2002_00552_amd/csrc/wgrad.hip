@@ -17,7 +17,7 @@
 //      written exactly once (the parts partition the taps), nothing is accumulated atomically,
 //      results do not vary from run to run.
 // Layers with few input channels (every class has at most 32 rows) and many tiles take another
-// form of steps 2-3 that never builds dM: see wgrad_small_kernel.
+// form of steps 2-3 that never builds dM: see wgrad_small_body / wgrad_small_all_kernel.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
