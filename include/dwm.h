@@ -299,7 +299,7 @@ DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan,
  * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes.
  * dwm_f16_set_variant(plan, "contract", v): v in 30..47 selects the contraction's tile shape
  * (v < 0: the planner's choice); (plan, "input", v): 0 = gather form of the input transform,
- * 1 = LDS-staged form (C a multiple of 8 and a staged region that fits), v < 0: the planner's
+ * 1 = LDS-staged form (C a multiple of 8, or at most 64, and a staged region that fits), v < 0: the planner's
  * choice; DWM_ERR_INVALID_ARG if the variant does not apply to the layer.
  * dwm_f16_conv_forward_f32out is the same computation with y left in FP32 (not rounded): it
  * exists so that tests can compare everything before the last rounding.

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) void input_transform_f16_kernel(DevPlan P, con
 
 
 // ---------------------------------------------------------------------------------
-// Input transform, LDS-staged form (layers whose channel count is a multiple of eight).
+// Input transform, LDS-staged form.
 //
 // A workgroup owns one 64-tile block of V (lane = tile) and `cg` input channels, a multiple of
 // eight.  Its four waves stage the input rows the block's tiles touch (coalesced binary16 loads,
@@ -283,14 +283,76 @@ __device__ __forceinline__ void lds_part_rows8(const InLdsArgs& A, const float* 
     }
 }
 
+// The same for ANY channel count: eight consecutive reduction rows l0 .. l0+7 of a class, each with its
+// own part (slot = l / C) and channel (l % C) -- wave-uniform values; the pieces' patch offsets come
+// from a table in LDS (run-time indexes into the by-value argument struct would put it in scratch);
+// rows past the class's reduction length are written as zeros.
+template <int LH, int LW>
+__device__ __forceinline__ void lds_mixed_rows8(const DevPlan& P, const InLdsArgs& A, const DevClass& q,
+                                                const int (*pofs)[kMaxPieces][4], const float* __restrict__ xt,
+                                                half_t* __restrict__ vp, size_t plane, int l0, bool valid)
+{
+    constexpr int TH_ = LH + 1, TW_ = LW + 1;
+    half2_t out[TH_ * TW_][4];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const int l = l0 + c;
+        const bool real = l < q.L;
+        const int lc = real ? l : 0;
+        const int slot = lc / P.C, ch = lc - slot * P.C;
+        const int a = slot / q.wn, bb = slot - a * q.wn;
+        const int hpiece = q.h0 + a, wpiece = q.w0 + bb;
+        const float* xc = xt + ch * A.chan_floats;
+        float d[TH_][TW_];
+#pragma unroll
+        for (int i = 0; i < TH_; ++i)
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) d[i][j] = real ? xc[pofs[0][hpiece][i] + pofs[1][wpiece][j]] : 0.f;
+        float tmp[4][4];
+#pragma unroll
+        for (int j = 0; j < TW_; ++j) {
+            float col[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+#pragma unroll
+            for (int i = 0; i < TH_; ++i) col[i] = d[i][j];
+            bt_apply<LH>(col, o);
+#pragma unroll
+            for (int i = 0; i < TH_; ++i) tmp[i][j] = o[i];
+        }
+#pragma unroll
+        for (int i = 0; i < TH_; ++i) {
+            float rowv[4] = {0.f, 0.f, 0.f, 0.f}, o[4];
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) rowv[j] = tmp[i][j];
+            bt_apply<LW>(rowv, o);
+#pragma unroll
+            for (int j = 0; j < TW_; ++j) out[i * TW_ + j][c >> 1][c & 1] = (half_t)o[j];
+        }
+    }
+    if (!valid) return;
+#pragma unroll
+    for (int pl = 0; pl < TH_ * TW_; ++pl) {
+        uint4 v;
+        v.x = __builtin_bit_cast(uint32_t, out[pl][0]);
+        v.y = __builtin_bit_cast(uint32_t, out[pl][1]);
+        v.z = __builtin_bit_cast(uint32_t, out[pl][2]);
+        v.w = __builtin_bit_cast(uint32_t, out[pl][3]);
+        *reinterpret_cast<uint4*>(vp + (size_t)pl * plane) = v;
+    }
+}
+
 __global__ __launch_bounds__(256) void input_transform_f16_lds_kernel(DevPlan P, InLdsArgs A,
                                                                       const half_t* __restrict__ x,
                                                                       half_t* __restrict__ V,
                                                                       int* __restrict__ counters, int n_counters)
 {
     extern __shared__ __attribute__((aligned(16))) float xs16[];  // [cg][max_rows][nphase][lwp]
+    __shared__ int pofs[2][kMaxPieces][4];  // LDS offsets of the patch rows / columns of every piece
     if (blockIdx.x == 0)
         for (int i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
+    if (threadIdx.x < kMaxPieces * 4) {
+        pofs[0][threadIdx.x >> 2][threadIdx.x & 3] = A.roff[threadIdx.x >> 2][threadIdx.x & 3];
+        pofs[1][threadIdx.x >> 2][threadIdx.x & 3] = A.coff[threadIdx.x >> 2][threadIdx.x & 3];
+    }
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int b = blockIdx.x;
@@ -305,13 +367,15 @@ __global__ __launch_bounds__(256) void input_transform_f16_lds_kernel(DevPlan P,
     const int ty_a0 = g0 - n0 * P.TH, ty_b1 = g1 - n1 * P.TH;
     const int rows0 = s2 * ((n1 == n0 ? ty_b1 : P.TH - 1) - ty_a0) + A.foot_h;
 
-    // a wave stages channels wave, wave+4, ...: cn is a multiple of eight, so they come in fours or
+    // a wave stages channels wave, wave+4, ...: where cn is a multiple of eight they come in fours or
     // pairs whose loads are in flight together (the staging is a chain of load latencies otherwise)
     int cl = wave;
     for (; cl + 12 < cn; cl += 16)
         stage_channels<half_t, 4>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, 4, n0, n1, ty_a0, ty_b1, lane);
-    for (; cl < cn; cl += 8)
+    for (; cl + 4 < cn; cl += 8)
         stage_channels<half_t, 2>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, 4, n0, n1, ty_a0, ty_b1, lane);
+    for (; cl < cn; cl += 4)  // channel counts that are not a multiple of eight
+        stage_channels<half_t, 1>(P, A, x, xs16 + cl * A.chan_floats, c0 + cl, 4, n0, n1, ty_a0, ty_b1, lane);
     __syncthreads();
 
     const int t = t0 + lane;
@@ -324,6 +388,31 @@ __global__ __launch_bounds__(256) void input_transform_f16_lds_kernel(DevPlan P,
         lane_base = base_row * A.row_floats + tx;
     }
     half_t* vb = V + (size_t)bt * P.vblock_rows * 64 + lane * 8;
+    if (P.C & 7) {
+        // one workgroup holds all channels (cg = C): items are (class, eight rows), padding rows included
+        int item = 0;
+        for (int qi = 0; qi < P.ncls; ++qi) {
+            const DevClass q = P.cls[qi];
+            const size_t plane = (size_t)q.Lpad * 64;
+            for (int l0 = 0; l0 < q.Lpad; l0 += 8, ++item) {
+                if ((item & 3) != wave) continue;
+                const float* xt = xs16 + lane_base;
+                half_t* vp = vb + (size_t)(q.v_row0 + l0) * 64;
+                switch (q.lh * 4 + q.lw) {
+                    case 3 * 4 + 3: lds_mixed_rows8<3, 3>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 3 * 4 + 2: lds_mixed_rows8<3, 2>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 3 * 4 + 1: lds_mixed_rows8<3, 1>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 2 * 4 + 3: lds_mixed_rows8<2, 3>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 2 * 4 + 2: lds_mixed_rows8<2, 2>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 2 * 4 + 1: lds_mixed_rows8<2, 1>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 1 * 4 + 3: lds_mixed_rows8<1, 3>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    case 1 * 4 + 2: lds_mixed_rows8<1, 2>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                    default: lds_mixed_rows8<1, 1>(P, A, q, pofs, xt, vp, plane, l0, valid); break;
+                }
+            }
+        }
+        return;
+    }
     const int ngr = cn >> 3;
     int item = 0;
     for (int qi = 0; qi < P.ncls; ++qi) {
@@ -803,7 +892,15 @@ static dwm_status_t launch_contract16(const dwm_f16_plan& hp, const half_t* U, v
 // more channels so that each of its four waves has an item.
 static bool input16_lds_setup(const dwm_plan& p, InLdsArgs* out)
 {
-    if (p.d.C % 8 != 0) return false;
+    if (p.d.C % 8 != 0) {
+        // all channels in one workgroup, rows in groups of eight across parts and channels
+        InLdsArgs a;
+        if (p.d.C <= 64 && input_lds_setup(p, &a, p.d.C) && a.cg == p.d.C && a.ncg == 1 && a.lds_bytes <= 48 * 1024) {
+            *out = a;
+            return true;
+        }
+        return false;
+    }
     const int nparts = p.info.n_parts;
     int cg = 8 * ((4 + nparts - 1) / nparts);
     if (cg > p.d.C) cg = p.d.C;
@@ -828,10 +925,10 @@ static dwm_status_t launch_input16(const dwm_f16_plan& hp, const half_t* x, hipS
     const int nb = d.Tpad / 64, ng = (d.rows_total / 8 + 3) / 4;
     if (hp.variant_input != 0 && hp.inlds_ok) {
         const InLdsArgs& a = hp.inlds;
-        if (a.lds_bytes > 64 * 1024) {
+        if (a.lds_bytes + 1024 > 64 * 1024) {  // the kernel's static table comes on top
             static const hipError_t attr =
                 hipFuncSetAttribute(reinterpret_cast<const void*>(input_transform_f16_lds_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024);
             if (attr != hipSuccess) return DWM_ERR_HIP;
         }
         hipLaunchKernelGGL(input_transform_f16_lds_kernel, dim3((unsigned)(nb * a.ncg)), dim3(256), a.lds_bytes, s, d, a,

@@ -203,6 +203,9 @@ def test_every_contraction_variant(variant):
     (70, 8, 6, 6, 8, 3, 3, 1, 1),  # blocks of 64 tiles that span several images
     (9, 8, 14, 14, 16, 7, 7, 2, 3),  # four images per block: a staged region beyond 64 KB
     (9, 16, 14, 14, 16, 11, 11, 2, 5),
+    # channel counts that are not a multiple of eight: groups of eight rows across parts and channels
+    (2, 3, 37, 35, 33, 7, 7, 2, 3), (2, 3, 43, 47, 20, 11, 11, 4, 0), (1, 5, 9, 10, 2, 1, 7, 1, 3),
+    (3, 12, 20, 22, 24, 5, 5, 1, 2), (2, 20, 14, 14, 40, 3, 3, 1, 1), (70, 2, 6, 6, 3, 3, 3, 1, 1),
 ])
 def test_input_transform_forms_agree(shape):
     """Gather form and LDS-staged form of the input transform produce the same V, hence the same
@@ -299,9 +302,9 @@ def test_error_codes():
         with pytest.raises(dwm.DwmError) as e:
             dwm.dwm_f16_set_variant(plan, "contract", 32)  # 64-row chunks on a 16-row layout
         assert e.value.status == dwm.DWM_ERR_INVALID_ARG
-        p3 = dwm.dwm_f16_plan_create(1, 3, 8, 8, 4, 3, 3, 1, 1)
+        p3 = dwm.dwm_f16_plan_create(1, 70, 8, 8, 4, 3, 3, 1, 1)
         with pytest.raises(dwm.DwmError) as e:
-            dwm.dwm_f16_set_variant(p3, "input", 1)  # the LDS-staged form needs C % 8 == 0
+            dwm.dwm_f16_set_variant(p3, "input", 1)  # the LDS-staged form needs C % 8 == 0 or C <= 64
         assert e.value.status == dwm.DWM_ERR_INVALID_ARG
         dwm.dwm_f16_plan_destroy(p3)
     finally:
