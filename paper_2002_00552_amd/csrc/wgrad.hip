@@ -80,6 +80,42 @@ __global__ __launch_bounds__(256) void wgrad_dy_transform_kernel(DyShape P, Plan
     }
 }
 
+// The same with two neighbouring tiles per lane (output rows of a multiple of four pixels: a tile pair's
+// two pixel rows are two aligned 16-byte loads, a plane's pair of values one 8-byte store): a wave
+// covers two filters x 64 tiles with half the memory instructions.
+__global__ __launch_bounds__(256) void wgrad_dy_transform2_kernel(DyShape P, PlaneTable PT,
+                                                                  const float* __restrict__ dy, float* __restrict__ dM)
+{
+    const int blk = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blk * 64 + 2 * (lane & 31);                 // tiles t, t + 1: same tile row (TW is even)
+    const int k = blockIdx.y * 8 + wave * 2 + (lane >> 5);
+    float4 r0 = make_float4(0.f, 0.f, 0.f, 0.f), r1 = r0;      // pixel rows 2ty, 2ty+1: [t: b=0,1 | t+1: b=0,1]
+    if (t < P.T && k < P.K) {
+        const int tiles = P.TH * P.TW;
+        const int n = t / tiles, rem = t - n * tiles;
+        const int ty = rem / P.TW, tx = rem - ty * P.TW;
+        const float* yp = dy + (((size_t)n * P.K + k) * P.OH + 2 * ty) * P.OW + 2 * tx;
+        r0 = *reinterpret_cast<const float4*>(yp);
+        if (2 * ty + 1 < P.OH) r1 = *reinterpret_cast<const float4*>(yp + P.OW);
+    }
+    const float g0[4] = {r0.x, r0.y, r1.x, r1.y}, g1[4] = {r0.z, r0.w, r1.z, r1.w};
+    // rows k >= K and columns t >= T are written as zeros: the GEMM multiplies them
+    float* out = dM + ((size_t)blk * P.dm_rows + k) * 64 + 2 * (lane & 31);
+    if (k >= P.Kp) return;
+    for (int p = 0; p < PT.n; ++p) {
+        const int coef = PT.e[p].coef;
+        float v0 = 0.f, v1 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int cq = (coef >> (2 * q)) & 3;
+            v0 += cq == 1 ? g0[q] : cq == 3 ? -g0[q] : 0.f;
+            v1 += cq == 1 ? g1[q] : cq == 3 ? -g1[q] : 0.f;
+        }
+        *reinterpret_cast<float2*>(out + (size_t)p * P.Kp * 64) = make_float2(v0, v1);
+    }
+}
+
 // columns past the last tile of the last V block: zeros (the forward pass leaves them unwritten)
 __global__ __launch_bounds__(256) void wgrad_zero_tail_kernel(float* __restrict__ V, int rows, int first_col)
 {
@@ -718,8 +754,13 @@ dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const f
     }
     // 2. dM = A dY A^T
     const DyShape ds{d.T, d.K, a.Kp, d.TH, d.TW, d.OH, d.OW, a.dm_rows};
-    hipLaunchKernelGGL(wgrad_dy_transform_kernel, dim3(a.tblocks, a.Kp / 4), dim3(256), 0, s, ds, plan->fwd->planes,
-                       dy_dev, dM);
+    if (d.OW % 4 == 0 && (reinterpret_cast<uintptr_t>(dy_dev) & 15) == 0) {
+        hipLaunchKernelGGL(wgrad_dy_transform2_kernel, dim3(a.tblocks, a.Kp / 8), dim3(256), 0, s, ds, plan->fwd->planes,
+                           dy_dev, dM);
+    } else {
+        hipLaunchKernelGGL(wgrad_dy_transform_kernel, dim3(a.tblocks, a.Kp / 4), dim3(256), 0, s, ds, plan->fwd->planes,
+                           dy_dev, dM);
+    }
     // 3. partial dU
     constexpr int NS = 2;
     constexpr int lds_bytes = NS * 2 * 64 * 64 * 4;
