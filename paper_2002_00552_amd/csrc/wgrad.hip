@@ -494,7 +494,14 @@ __global__ __launch_bounds__(256) void wgrad_final_kernel(DevPlan P, WgradArgs A
             if (i <= q.lh && j <= q.lw) {
                 const int p = q.plane0 + i * tw + j;
                 const float* src = partial + (size_t)A.poff64[p] * 64 + (size_t)k * A.lstride[p] + l;
-                for (int s = 0; s < A.splits; ++s) v += src[(size_t)s * A.split_floats];
+                // four loads in flight at a time; the additions keep their order
+                int s = 0;
+                for (; s + 4 <= A.splits; s += 4) {
+                    const float a0 = src[(size_t)s * A.split_floats], a1 = src[(size_t)(s + 1) * A.split_floats];
+                    const float a2 = src[(size_t)(s + 2) * A.split_floats], a3 = src[(size_t)(s + 3) * A.split_floats];
+                    v = (((v + a0) + a1) + a2) + a3;
+                }
+                for (; s < A.splits; ++s) v += src[(size_t)s * A.split_floats];
             }
             u[i][j] = v;
         }
