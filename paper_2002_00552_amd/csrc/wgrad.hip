@@ -524,6 +524,70 @@ __global__ __launch_bounds__(256) void wgrad_final_kernel(DevPlan P, WgradArgs A
             }
 }
 
+// The same with whole records: a workgroup owns one filter and 64 channels, its waves walk the parts
+// (a wave = one part x 64 channels, loads coalesced along c), the taps go to an LDS copy of the 64
+// records dw[k][c0..c0+63][R][S], which are contiguous in memory and written out coalesced -- the
+// kernel above writes every record in 4-byte pieces from workgroups far apart in time.
+__global__ __launch_bounds__(256) void wgrad_final_lds_kernel(DevPlan P, WgradArgs A, const float* __restrict__ partial,
+                                                              float* __restrict__ dw)
+{
+    extern __shared__ float rec[];  // [64][R * S]
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int c0 = blockIdx.x * 64, k = blockIdx.y;
+    const int c = c0 + lane, RS = P.R * P.S;
+    int part0 = 0;
+    for (int qi = 0; qi < P.ncls; ++qi) {
+        const DevClass q = P.cls[qi];
+        const int tw = q.lw + 1, nslot = q.hn * q.wn;
+        for (int slot = 0; slot < nslot; ++slot) {
+            if (((part0 + slot) & 3) != wave) continue;
+            const int ai = slot / q.wn, bi = slot - ai * q.wn;
+            const DevPiece hp = P.ph[q.h0 + ai], wp = P.pw[q.w0 + bi];
+            const int l = slot * P.C + min(c, P.C - 1);
+            float u[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float v = 0.f;
+                    if (i <= q.lh && j <= q.lw) {
+                        const int p = q.plane0 + i * tw + j;
+                        const float* src = partial + (size_t)A.poff64[p] * 64 + (size_t)k * A.lstride[p] + l;
+                        int s = 0;
+                        for (; s + 4 <= A.splits; s += 4) {
+                            const float a0 = src[(size_t)s * A.split_floats], a1 = src[(size_t)(s + 1) * A.split_floats];
+                            const float a2 = src[(size_t)(s + 2) * A.split_floats], a3 = src[(size_t)(s + 3) * A.split_floats];
+                            v = (((v + a0) + a1) + a2) + a3;
+                        }
+                        for (; s < A.splits; ++s) v += src[(size_t)s * A.split_floats];
+                    }
+                    u[i][j] = v;
+                }
+            float t[3][4];
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float col[4] = {u[0][j], u[1][j], u[2][j], u[3][j]};
+                    t[a][j] = a < q.lh ? gt_col(q.lh, a, col) : 0.f;
+                }
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
+#pragma unroll
+                for (int b = 0; b < 3; ++b)
+                    if (a < q.lh && b < q.lw) {
+                        const int r = P.s * (hp.j + a) + hp.p, s2 = P.s * (wp.j + b) + wp.p;
+                        rec[lane * RS + r * P.S + s2] = gt_col(q.lw, b, t[a]);
+                    }
+        }
+        part0 += nslot;
+    }
+    __syncthreads();
+    const int n = min(64, P.C - c0) * RS;
+    float* out = dw + ((size_t)k * P.C + c0) * RS;
+    for (int i = threadIdx.x; i < n; i += 256) out[i] = rec[i];
+}
+
 }  // namespace dwm
 
 struct dwm_bwd_filter_plan {
@@ -607,6 +671,19 @@ static bool small_setup(dwm_bwd_filter_plan& bp)
     return true;
 }
 
+}  // namespace dwm
+
+namespace dwm {
+// dw = G^T (sum of partial dU) G: whole records through LDS where 64 of them fit and the layer has them
+static void launch_final(const DevPlan& d, const WgradArgs& a, const float* partial, float* dw, hipStream_t s)
+{
+    const size_t lds = (size_t)64 * d.R * d.S * sizeof(float);
+    if (lds <= 48 * 1024 && d.C >= 32) {  // (with few channels most of the 64 lanes would idle)
+        hipLaunchKernelGGL(wgrad_final_lds_kernel, dim3((d.C + 63) / 64, d.K), dim3(256), lds, s, d, a, partial, dw);
+    } else {
+        hipLaunchKernelGGL(wgrad_final_kernel, dim3((d.rows_total + 255) / 256, d.K), dim3(256), 0, s, d, a, partial, dw);
+    }
+}
 }  // namespace dwm
 
 extern "C" {
@@ -756,7 +833,7 @@ dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const f
                            sum, a.split_floats, a.splits);
         WgradArgs fa = a;
         fa.splits = 1;
-        hipLaunchKernelGGL(wgrad_final_kernel, dim3((d.rows_total + 255) / 256, d.K), dim3(256), 0, s, d, fa, sum, dw_dev);
+        launch_final(d, fa, sum, dw_dev, s);
         return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
     }
     // 2. dM = A dY A^T
@@ -777,7 +854,7 @@ dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const f
     if (attr != hipSuccess) return DWM_ERR_HIP;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(a.n_tiles * a.splits)), dim3(256), lds_bytes, s, a, dM, V, partial);
     // 4. dw = G^T (sum) G
-    hipLaunchKernelGGL(wgrad_final_kernel, dim3((d.rows_total + 255) / 256, d.K), dim3(256), 0, s, d, a, partial, dw_dev);
+    launch_final(d, a, partial, dw_dev, s);
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }
 
