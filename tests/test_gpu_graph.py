@@ -1,5 +1,5 @@
 """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation,
-no memset): a forward call can therefore be captured into a HIP graph and replayed.  Every replay
+no memset): a forward call, and either gradient, can therefore be captured into a HIP graph and replayed.  Every replay
 is checked against the eager result, with eager work and synchronisations between replays."""
 import numpy as np
 import pytest
@@ -58,3 +58,85 @@ def test_forward_replays_from_a_graph(shape, forward_variant):
     finally:
         torch.cuda.synchronize()
         dwm.dwm_plan_destroy(plan)
+
+
+def _replay_and_compare(g, out, eager, eager_again):
+    """Four replays, each checked against the eager result, with eager work on other data and
+    synchronisations in between."""
+    for rep in range(4):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d" % rep
+        eager_again()
+        torch.cuda.synchronize()
+        assert not torch.equal(out, eager)
+
+
+@pytest.mark.parametrize("shape", [
+    (2, 10, 20, 24, 150, 3, 3, 2, 1),    # four sub-convolutions, one merged input transform, one batched contraction
+    (2, 24, 14, 14, 40, 7, 7, 1, 3),     # one sub-convolution on the forward kernels (tiles cut into ranges)
+])
+def test_backward_data_replays_from_a_graph(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    rng = np.random.default_rng(6)
+    OH, OW = (H + 2 * P - R) // s + 1, (W + 2 * P - S) // s + 1
+    w = torch.from_numpy((rng.standard_normal((K, C, R, S)) * 0.1).astype(np.float32)).cuda()
+    dy = torch.from_numpy(rng.uniform(-1, 1, (N, K, OH, OW)).astype(np.float32)).cuda()
+    plan = dwm.dwm_bwd_data_plan_create(N, C, H, W, K, R, S, s, P)
+    try:
+        U = torch.empty(dwm.dwm_bwd_data_filter_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(dwm.dwm_bwd_data_workspace_bytes(plan) // 4, 64), dtype=torch.float32, device="cuda")
+        dwm.dwm_bwd_data_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+        dx = torch.zeros((N, C, H, W), dtype=torch.float32, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            st = side.cuda_stream
+            dwm.dwm_bwd_data_filter_transform(plan, w.data_ptr(), U.data_ptr(), st)
+            dwm.dwm_conv_backward_data(plan, dy.data_ptr(), U.data_ptr(), dx.data_ptr(), st)
+            side.synchronize()
+            eager = dx.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                dwm.dwm_conv_backward_data(plan, dy.data_ptr(), U.data_ptr(), dx.data_ptr(),
+                                           torch.cuda.current_stream().cuda_stream)
+        dy2 = dy * 0.5
+        _replay_and_compare(g, dx, eager, lambda: dwm.dwm_conv_backward_data(
+            plan, dy2.data_ptr(), U.data_ptr(), dx.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    finally:
+        torch.cuda.synchronize()
+        dwm.dwm_bwd_data_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("shape", [
+    (2, 66, 12, 12, 67, 3, 3, 1, 1),     # GEMM form: input transform, dy transform, GEMM over ranges, final
+    (16, 6, 130, 127, 16, 3, 3, 2, 1),   # short-reduction form: class kernels in one launch, reduce, final
+])
+def test_backward_filter_replays_from_a_graph(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    rng = np.random.default_rng(7)
+    OH, OW = (H + 2 * P - R) // s + 1, (W + 2 * P - S) // s + 1
+    x = torch.from_numpy(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)).cuda()
+    dy = torch.from_numpy(rng.uniform(-1, 1, (N, K, OH, OW)).astype(np.float32)).cuda()
+    plan = dwm.dwm_bwd_filter_plan_create(N, C, H, W, K, R, S, s, P)
+    try:
+        ws = torch.empty(dwm.dwm_bwd_filter_workspace_bytes(plan) // 4, dtype=torch.float32, device="cuda")
+        dwm.dwm_bwd_filter_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+        dw = torch.zeros((K, C, R, S), dtype=torch.float32, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            st = side.cuda_stream
+            dwm.dwm_conv_backward_filter(plan, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), st)
+            side.synchronize()
+            eager = dw.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                dwm.dwm_conv_backward_filter(plan, x.data_ptr(), dy.data_ptr(), dw.data_ptr(),
+                                             torch.cuda.current_stream().cuda_stream)
+        dy2 = dy * 0.5
+        _replay_and_compare(g, dw, eager, lambda: dwm.dwm_conv_backward_filter(
+            plan, x.data_ptr(), dy2.data_ptr(), dw.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    finally:
+        torch.cuda.synchronize()
+        dwm.dwm_bwd_filter_plan_destroy(plan)
