@@ -1,5 +1,5 @@
 """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation,
-no memset): a forward call, and either gradient, can therefore be captured into a HIP graph and replayed.  Every replay
+no memset): a forward call (single or half precision), and either gradient, can therefore be captured into a HIP graph and replayed.  Every replay
 is checked against the eager result, with eager work and synchronisations between replays."""
 import numpy as np
 import pytest
@@ -140,3 +140,38 @@ def test_backward_filter_replays_from_a_graph(shape):
     finally:
         torch.cuda.synchronize()
         dwm.dwm_bwd_filter_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("shape", [
+    (2, 64, 30, 30, 64, 3, 3, 1, 1),     # LDS-staged input transform, whole and split tiles
+    (2, 3, 37, 35, 33, 7, 7, 2, 3),      # three channels: eight-row items across parts and channels
+])
+def test_half_precision_forward_replays_from_a_graph(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    rng = np.random.default_rng(8)
+    x = torch.from_numpy(rng.uniform(-1, 1, (N, C, H, W)).astype(np.float16)).cuda()
+    w = torch.from_numpy((rng.standard_normal((K, C, R, S)) * 0.1).astype(np.float16)).cuda()
+    plan = dwm.dwm_f16_plan_create(N, C, H, W, K, R, S, s, P)
+    try:
+        info = dwm.dwm_f16_plan_info(plan)
+        U = torch.empty(dwm.dwm_f16_filter_bytes(plan) // 2, dtype=torch.float16, device="cuda")
+        ws = torch.empty(max(dwm.dwm_f16_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
+        dwm.dwm_f16_set_workspace(plan, ws.data_ptr(), ws.numel())
+        y = torch.zeros((N, K, info.OH, info.OW), dtype=torch.float16, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            st = side.cuda_stream
+            dwm.dwm_f16_filter_transform(plan, w.data_ptr(), U.data_ptr(), st)
+            dwm.dwm_f16_conv_forward(plan, x.data_ptr(), U.data_ptr(), y.data_ptr(), st)
+            side.synchronize()
+            eager = y.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                dwm.dwm_f16_conv_forward(plan, x.data_ptr(), U.data_ptr(), y.data_ptr(),
+                                         torch.cuda.current_stream().cuda_stream)
+        x2 = x * 0.5
+        _replay_and_compare(g, y, eager, lambda: dwm.dwm_f16_conv_forward(
+            plan, x2.data_ptr(), U.data_ptr(), y.data_ptr(), torch.cuda.current_stream().cuda_stream))
+    finally:
+        torch.cuda.synchronize()
+        dwm.dwm_f16_plan_destroy(plan)
