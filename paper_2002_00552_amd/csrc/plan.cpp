@@ -21,7 +21,7 @@ long long round_up(long long v, long long a) { return (v + a - 1) / a * a; }
 // 3+1 becomes 2+2, which costs the same number of multiplications (4+2 = 3+3) -- so that
 // one-tap pieces, which cannot share frequencies with the others, only arise from phases
 // that hold a single tap.
-int split_dimension(int r, int s, bool even_tail, DevPiece* out, int start[4], int count[4])
+int split_dimension(int r, int s, bool even_tail, bool widen2, DevPiece* out, int start[4], int count[4])
 {
     DevPiece tmp[kMaxPieces];
     int n = 0;
@@ -33,7 +33,7 @@ int split_dimension(int r, int s, bool even_tail, DevPiece* out, int start[4], i
             const int rest = taps - j;
             int len = rest < 3 ? rest : 3;
             if (even_tail && rest == 4) len = 2;
-            tmp[n++] = DevPiece{p, j, len};
+            tmp[n++] = DevPiece{p, j, (widen2 && len == 2) ? 3 : len, len};
             j += len;
         }
     }
@@ -160,7 +160,7 @@ bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out)
 extern "C" {
 
 // One planning pass with the given splitting policy; *out is set on DWM_OK only.
-static dwm_status_t plan_build(dwm_plan_t** out, const dwm::PlanSpec& sp, bool even_tail)
+static dwm_status_t plan_build(dwm_plan_t** out, const dwm::PlanSpec& sp, bool even_tail, bool widen2 = false)
 {
     const int N = sp.N, C = sp.C, H = sp.H, W = sp.W, K = sp.K, R = sp.R, S = sp.S, stride = sp.stride;
     if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || stride < 1 || sp.OH < 1 || sp.OW < 1)
@@ -186,8 +186,8 @@ static dwm_status_t plan_build(dwm_plan_t** out, const dwm::PlanSpec& sp, bool e
     const long long lim = (1LL << 31) - 1;
 
     int sh[4], ch[4], sw[4], cw[4];
-    d.nh = split_dimension(R, stride, even_tail, d.ph, sh, ch);
-    d.nw = split_dimension(S, stride, even_tail, d.pw, sw, cw);
+    d.nh = split_dimension(R, stride, even_tail, widen2, d.ph, sh, ch);
+    d.nw = split_dimension(S, stride, even_tail, widen2, d.pw, sw, cw);
     bool ok = d.nh > 0 && d.nw > 0 && Tpad < lim && (long long)N * K * d.om.YH * d.om.YW < lim && (long long)N * K * d.OH * d.OW < lim &&
               (long long)N * C * H * W < lim && (long long)K * C * R * S < lim;
 
@@ -325,6 +325,11 @@ dwm_status_t plan_from_spec(dwm_plan_t** out, const PlanSpec& sp)
 dwm_status_t plan_from_spec_as_printed(dwm_plan_t** out, const PlanSpec& sp)
 {
     return plan_build(out, sp, false);
+}
+
+dwm_status_t plan_from_spec_widened(dwm_plan_t** out, const PlanSpec& sp)
+{
+    return plan_build(out, sp, true, true);
 }
 }  // namespace dwm
 

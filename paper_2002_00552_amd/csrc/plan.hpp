@@ -19,7 +19,8 @@ constexpr int kLAlign = 16;     // Lpad is a multiple of this at least (smallest
 
 // A 1-D piece (Sec. 4.1): phase p, offset j inside the phase's tap list, length l.
 struct DevPiece {
-    int p, j, l;
+    int p, j, l;  // phase, first tap of the phase's tap list, length the transforms use
+    int lr;       // taps the piece really has (l, except where a plan widens two-tap pieces to three)
 };
 
 // A class: the parts made of an h-piece of length lh and a w-piece of length lw.
@@ -260,6 +261,11 @@ struct PlanSpec {
     OutMap om;
 };
 dwm_status_t plan_from_spec(dwm_plan_t** out, const PlanSpec& sp);
+// For the filter gradient of layers with few channels: phases cut 3,...,3,2,2 and every two-tap
+// piece transformed as a three-tap one (its third tap is a neighbour's, or lies past the kernel: the
+// gradient of that tap is computed and dropped), so that all parts share the 16 planes of F(2,3)^2.
+// Only the input transform and the tables of such a plan are used.
+dwm_status_t plan_from_spec_widened(dwm_plan_t** out, const PlanSpec& sp);
 // the same with the kernel cut exactly as eq. 8 writes it (3,3,...,remainder), staged path only
 dwm_status_t plan_from_spec_as_printed(dwm_plan_t** out, const PlanSpec& sp);
 // plan.cpp: geometry of a contraction variant for this plan; false if the variant does not apply

@@ -518,7 +518,7 @@ __global__ __launch_bounds__(256) void wgrad_final_kernel(DevPlan P, WgradArgs A
     for (int a = 0; a < 3; ++a)
 #pragma unroll
         for (int b = 0; b < 3; ++b)
-            if (a < q.lh && b < q.lw) {
+            if (a < hp.lr && b < wp.lr) {  // (a widened piece's third tap is not its own)
                 const int r = P.s * (hp.j + a) + hp.p, s2 = P.s * (wp.j + b) + wp.p;
                 dw[(((size_t)k * P.C + c) * P.R + r) * P.S + s2] = gt_col(q.lw, b, t[a]);
             }
@@ -575,7 +575,7 @@ __global__ __launch_bounds__(256) void wgrad_final_lds_kernel(DevPlan P, WgradAr
             for (int a = 0; a < 3; ++a)
 #pragma unroll
                 for (int b = 0; b < 3; ++b)
-                    if (a < q.lh && b < q.lw) {
+                    if (a < hp.lr && b < wp.lr) {  // (a widened piece's third tap is not its own)
                         const int r = P.s * (hp.j + a) + hp.p, s2 = P.s * (wp.j + b) + wp.p;
                         rec[lane * RS + r * P.S + s2] = gt_col(q.lw, b, t[a]);
                     }
@@ -592,6 +592,7 @@ __global__ __launch_bounds__(256) void wgrad_final_lds_kernel(DevPlan P, WgradAr
 
 struct dwm_bwd_filter_plan {
     dwm_plan_t* fwd;
+    double direct_flops, winograd_flops;  // of the layer as the paper splits it
     dwm::WgradArgs a;
     size_t fwd_ws_bytes, dm_bytes, partial_bytes;
     float* ws;
@@ -688,14 +689,10 @@ static void launch_final(const DevPlan& d, const WgradArgs& a, const float* part
 
 extern "C" {
 
-dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
-                                        int stride, int pad)
+// Everything the filter gradient derives from a forward plan (which it takes over, also on failure).
+static dwm_status_t wgrad_build(dwm_bwd_filter_plan_t** out, dwm_plan_t* fwd, int K)
 {
     using namespace dwm;
-    if (!out) return DWM_ERR_INVALID_ARG;
-    dwm_plan_t* fwd = nullptr;
-    const dwm_status_t st = dwm_plan_create(&fwd, N, C, H, W, K, R, S, stride, pad);
-    if (st != DWM_OK) return st;
     dwm_bwd_filter_plan* bp = new (std::nothrow) dwm_bwd_filter_plan;
     if (!bp) {
         dwm_plan_destroy(fwd);
@@ -703,6 +700,8 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
     }
     bp->fwd = fwd;
     bp->ws = nullptr;
+    bp->direct_flops = fwd->info.direct_flops;
+    bp->winograd_flops = fwd->info.winograd_flops;
     WgradArgs& a = bp->a;
     a = WgradArgs{};
     const DevPlan& d = fwd->d;
@@ -762,6 +761,51 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
     return DWM_OK;
 }
 
+// MFMAs per 16 tiles and 16 filters of the short-reduction form: planes x row blocks, summed over classes
+static int small_cost(const dwm_bwd_filter_plan& bp)
+{
+    const dwm::DevPlan& d = bp.fwd->d;
+    int c = 0;
+    for (int i = 0; i < d.ncls; ++i) c += (d.cls[i].lh + 1) * (d.cls[i].lw + 1) * (d.cls[i].Lpad / 16);
+    return c;
+}
+
+dwm_status_t dwm_bwd_filter_plan_destroy(dwm_bwd_filter_plan_t* plan);
+
+dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                                        int stride, int pad)
+{
+    using namespace dwm;
+    if (!out) return DWM_ERR_INVALID_ARG;
+    dwm_plan_t* fwd = nullptr;
+    dwm_status_t st = dwm_plan_create(&fwd, N, C, H, W, K, R, S, stride, pad);
+    if (st != DWM_OK) return st;
+    dwm_bwd_filter_plan* bp = nullptr;
+    st = wgrad_build(&bp, fwd, K);
+    if (st != DWM_OK) return st;
+    if (bp->small) {
+        // Short-reduction form: would all parts on the 16 planes of F(2,3)^2 -- two-tap pieces transformed
+        // as three-tap ones -- take fewer MFMAs?  Then dy is also read by one class instead of several.
+        PlanSpec sp{};
+        sp.N = N; sp.C = C; sp.H = H; sp.W = W; sp.K = K; sp.R = R; sp.S = S; sp.stride = stride;
+        sp.pad_h = sp.pad_w = pad;
+        sp.OH = bp->fwd->d.OH; sp.OW = bp->fwd->d.OW;
+        sp.om = bp->fwd->d.om;
+        dwm_plan_t* wide = nullptr;
+        dwm_bwd_filter_plan* bw = nullptr;
+        if (plan_from_spec_widened(&wide, sp) == DWM_OK && wgrad_build(&bw, wide, K) == DWM_OK) {
+            if (bw->small && small_cost(*bw) < small_cost(*bp)) {
+                bw->direct_flops = bp->direct_flops;
+                bw->winograd_flops = bp->winograd_flops;
+                std::swap(bp, bw);
+            }
+            dwm_bwd_filter_plan_destroy(bw);
+        }
+    }
+    *out = bp;
+    return DWM_OK;
+}
+
 dwm_status_t dwm_bwd_filter_plan_destroy(dwm_bwd_filter_plan_t* plan)
 {
     if (!plan) return DWM_ERR_INVALID_ARG;
@@ -776,8 +820,8 @@ dwm_status_t dwm_bwd_filter_plan_info(const dwm_bwd_filter_plan_t* plan, dwm_bwd
     info->n_planes = plan->a.n_planes;
     info->n_tiles = plan->a.n_tiles;
     info->splits = plan->a.splits;
-    info->direct_flops = plan->fwd->info.direct_flops;
-    info->winograd_flops = plan->fwd->info.winograd_flops;
+    info->direct_flops = plan->direct_flops;
+    info->winograd_flops = plan->winograd_flops;
     return DWM_OK;
 }
 
