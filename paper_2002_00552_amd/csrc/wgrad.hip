@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradArgs A, const f
 // v_mfma_f32_16x16x4_f32 for every plane; the B operand, V[l][four tiles], is one 16-byte load
 // per plane.  Which tile sits in which of the MFMA's four reduction slots is free, so slot q
 // of step m takes tile 4q+m: a lane's four steps use exactly its four tiles.  dM never exists.
-// Every workgroup writes its own partial dU (compact: [plane][k][16*LB]); a second kernel adds
+// Every workgroup writes its own partial dU (compact: [plane][k][Lpad]); a second kernel adds
 // the partials in a fixed order.
 // ---------------------------------------------------------------------------------
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -254,6 +254,7 @@ struct SmallArgs {
     int K, Kp, T, OH, OW, TH, TW;
     int vblock_rows, vrow0, Lpad;  // rows of a V block, the class's first row in it, rows per plane
     int L;                         // of which real (the others are zeros, supplied here, not read)
+    int r0;                        // first row of a plane this pass covers (a class of more than 32 rows takes two passes)
     int tiles_per_split;           // a multiple of 16
     int poff;                      // floats from the start of a split's partial to this class's planes
     long long split_floats;
@@ -293,9 +294,10 @@ __device__ __forceinline__ void wgrad_small_body(const SmallArgs& A, const float
 #pragma unroll
     for (int it = 0; it < VITEMS; ++it) {
         const int idx = min((int)threadIdx.x + 256 * it, VROWS * 4 - 1);  // spare threads repeat the last item
-        vsrc[it] = (idx >> 2) * 64 + 4 * (idx & 3);
+        const int row = idx >> 2, pl = row / (16 * LB), r = A.r0 + row - pl * (16 * LB);  // plane, row of the plane
+        vsrc[it] = (pl * A.Lpad + r) * 64 + 4 * (idx & 3);
         vdst[it] = idx * 4;
-        vreal[it] = ((idx >> 2) % (16 * LB)) < A.L;
+        vreal[it] = r < A.L;
     }
 #define DWM_LOAD_V(t0_)                                                                                     \
     {                                                                                                       \
@@ -386,13 +388,13 @@ __device__ __forceinline__ void wgrad_small_body(const SmallArgs& A, const float
     }
     // lane (ln, q) holds dU[k = 4q + e][l = ln] of its wave's 16 filters
     float* out = partial + (size_t)split * A.split_floats + A.poff +
-                 ((size_t)(kt * 64 + wave * 16 + 4 * q)) * (16 * LB) + ln;
+                 ((size_t)(kt * 64 + wave * 16 + 4 * q)) * A.Lpad + A.r0 + ln;
 #pragma unroll
     for (int p = 0; p < NH * NW; ++p)
 #pragma unroll
         for (int lb = 0; lb < LB; ++lb)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) out[((size_t)p * A.Kp + e) * (16 * LB) + lb * 16] = acc[p][lb][e];
+            for (int e = 0; e < 4; ++e) out[((size_t)p * A.Kp + e) * A.Lpad + lb * 16] = acc[p][lb][e];
 }
 
 #undef DWM_LOAD_V
@@ -600,7 +602,9 @@ struct dwm_bwd_filter_plan {
     bool small;
     int small_kt;                      // 64-filter tiles
     size_t sum_bytes;                  // the summed dU after the partials
-    dwm::SmallArgs sc[dwm::kMaxClasses];
+    int n_pass;                        // passes: (class, rows r0 .. r0 + 16 * lb) with lb in {1, 2}
+    int pass_lb[2 * dwm::kMaxClasses], pass_code[2 * dwm::kMaxClasses];
+    dwm::SmallArgs sc[2 * dwm::kMaxClasses];
 };
 
 namespace dwm {
@@ -625,16 +629,23 @@ static dwm_status_t launch_small_all(int lb, const SmallAllArgs& aa, hipStream_t
     return DWM_OK;
 }
 
-// The short-reduction form applies when every class has at most 32 (padded) rows and there are
-// enough tiles to fill the chip (on a small layer the GEMM form's four launches are faster).  The
-// tiles are cut into ranges so that the workgroups of ONE class would put two workgroups on every CU;
-// all classes go out in one launch, several rounds deep.
-static bool small_setup(dwm_bwd_filter_plan& bp)
+// The short-reduction form applies when every class has at most max_rows (padded) rows -- 32, or 64 in two
+// passes for the plan that puts all parts in one class -- and there are enough tiles to fill the chip (on a
+// small layer the GEMM form's four launches are faster).  The tiles are cut into ranges so that the
+// workgroups of ONE class would put two workgroups on every CU; all passes of one row-block count go out
+// in one launch, several rounds deep.
+static bool small_setup(dwm_bwd_filter_plan& bp, int max_rows)
 {
     const DevPlan& d = bp.fwd->d;
     if (d.T < 16384) return false;
-    for (int c = 0; c < d.ncls; ++c)
-        if (d.cls[c].Lpad > 32) return false;
+    int n1 = 0, n2 = 0;  // passes of one / two row blocks
+    for (int c = 0; c < d.ncls; ++c) {
+        const int blocks = d.cls[c].Lpad / 16;
+        if (blocks * 16 > max_rows) return false;
+        n2 += blocks / 2;
+        n1 += blocks & 1;
+    }
+    if (n1 > kMaxClasses || n2 > kMaxClasses) return false;
     WgradArgs& a = bp.a;
     bp.small_kt = a.Kp / 64;
     const long long t16 = ((long long)d.T + 15) / 16 * 16;
@@ -644,25 +655,31 @@ static bool small_setup(dwm_bwd_filter_plan& bp)
     const long long nsplit = (t16 + per - 1) / per;
     if (per > 0x7fffffffLL || nsplit > 65535 * 16) return false;
     long long off = 0;
+    bp.n_pass = 0;
     for (int c = 0; c < d.ncls; ++c) {
         const DevClass& q = d.cls[c];
-        const int lb = q.Lpad / 16, planes = (q.lh + 1) * (q.lw + 1);
-        SmallArgs& sa = bp.sc[c];
-        sa = SmallArgs{};
-        sa.K = d.K; sa.Kp = a.Kp; sa.T = d.T; sa.OH = d.OH; sa.OW = d.OW; sa.TH = d.TH; sa.TW = d.TW;
-        sa.vblock_rows = d.vblock_rows; sa.vrow0 = q.v_row0; sa.Lpad = q.Lpad; sa.L = q.L;
-        sa.tiles_per_split = (int)per;
-        sa.poff = (int)off;
-        sa.div_tiles.init((unsigned)(d.TH * d.TW));
-        sa.div_tw.init((unsigned)d.TW);
-        for (int pl = 0; pl < planes; ++pl) {
-            a.poff64[q.plane0 + pl] = (int)((off + (long long)pl * a.Kp * 16 * lb) / 64);
-            a.lstride[q.plane0 + pl] = 16 * lb;
+        const int planes = (q.lh + 1) * (q.lw + 1);
+        for (int r0 = 0; r0 < q.Lpad; r0 += 32) {  // rows r0 .. r0+31, or the last 16
+            SmallArgs& sa = bp.sc[bp.n_pass];
+            sa = SmallArgs{};
+            sa.K = d.K; sa.Kp = a.Kp; sa.T = d.T; sa.OH = d.OH; sa.OW = d.OW; sa.TH = d.TH; sa.TW = d.TW;
+            sa.vblock_rows = d.vblock_rows; sa.vrow0 = q.v_row0; sa.Lpad = q.Lpad; sa.L = q.L; sa.r0 = r0;
+            sa.tiles_per_split = (int)per;
+            sa.poff = (int)off;
+            sa.div_tiles.init((unsigned)(d.TH * d.TW));
+            sa.div_tw.init((unsigned)d.TW);
+            bp.pass_lb[bp.n_pass] = q.Lpad - r0 >= 32 ? 2 : 1;
+            bp.pass_code[bp.n_pass] = q.lh * 4 + q.lw;
+            ++bp.n_pass;
         }
-        off += (long long)planes * a.Kp * 16 * lb;
+        for (int pl = 0; pl < planes; ++pl) {
+            a.poff64[q.plane0 + pl] = (int)((off + (long long)pl * a.Kp * q.Lpad) / 64);
+            a.lstride[q.plane0 + pl] = q.Lpad;
+        }
+        off += (long long)planes * a.Kp * q.Lpad;
     }
     if (off * nsplit > (1LL << 40)) return false;
-    for (int c = 0; c < d.ncls; ++c) bp.sc[c].split_floats = off;
+    for (int c = 0; c < bp.n_pass; ++c) bp.sc[c].split_floats = off;
     a.split_floats = off;
     a.splits = (int)nsplit;  // what the plan reports; the final kernel reads the summed dU (one "split")
     bp.dm_bytes = 0;
@@ -690,7 +707,7 @@ static void launch_final(const DevPlan& d, const WgradArgs& a, const float* part
 extern "C" {
 
 // Everything the filter gradient derives from a forward plan (which it takes over, also on failure).
-static dwm_status_t wgrad_build(dwm_bwd_filter_plan_t** out, dwm_plan_t* fwd, int K)
+static dwm_status_t wgrad_build(dwm_bwd_filter_plan_t** out, dwm_plan_t* fwd, int K, int small_max_rows)
 {
     using namespace dwm;
     dwm_bwd_filter_plan* bp = new (std::nothrow) dwm_bwd_filter_plan;
@@ -756,7 +773,7 @@ static dwm_status_t wgrad_build(dwm_bwd_filter_plan_t** out, dwm_plan_t* fwd, in
     bp->dm_bytes = ((size_t)a.tblocks * a.dm_rows * 64 * sizeof(float) + 255) / 256 * 256;
     bp->partial_bytes = (size_t)a.splits * a.split_floats * sizeof(float);
     bp->sum_bytes = 0;
-    bp->small = small_setup(*bp);
+    bp->small = small_setup(*bp, small_max_rows);
     *out = bp;
     return DWM_OK;
 }
@@ -781,7 +798,7 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
     dwm_status_t st = dwm_plan_create(&fwd, N, C, H, W, K, R, S, stride, pad);
     if (st != DWM_OK) return st;
     dwm_bwd_filter_plan* bp = nullptr;
-    st = wgrad_build(&bp, fwd, K);
+    st = wgrad_build(&bp, fwd, K, 32);
     if (st != DWM_OK) return st;
     if (bp->small) {
         // Short-reduction form: would all parts on the 16 planes of F(2,3)^2 -- two-tap pieces transformed
@@ -793,7 +810,7 @@ dwm_status_t dwm_bwd_filter_plan_create(dwm_bwd_filter_plan_t** out, int N, int 
         sp.om = bp->fwd->d.om;
         dwm_plan_t* wide = nullptr;
         dwm_bwd_filter_plan* bw = nullptr;
-        if (plan_from_spec_widened(&wide, sp) == DWM_OK && wgrad_build(&bw, wide, K) == DWM_OK) {
+        if (plan_from_spec_widened(&wide, sp) == DWM_OK && wgrad_build(&bw, wide, K, 64) == DWM_OK) {
             if (bw->small && small_cost(*bw) < small_cost(*bp)) {
                 bw->direct_flops = bp->direct_flops;
                 bw->winograd_flops = bp->winograd_flops;
@@ -866,9 +883,9 @@ dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan, const f
             SmallAllArgs aa{};
             aa.nkt = plan->small_kt;
             aa.splits = a.splits;
-            for (int c = 0; c < d.ncls; ++c)
-                if (d.cls[c].Lpad / 16 == lb) {
-                    aa.code[aa.ncls] = d.cls[c].lh * 4 + d.cls[c].lw;
+            for (int c = 0; c < plan->n_pass; ++c)
+                if (plan->pass_lb[c] == lb) {
+                    aa.code[aa.ncls] = plan->pass_code[c];
                     aa.c[aa.ncls++] = plan->sc[c];
                 }
             if (aa.ncls > 0 && launch_small_all(lb, aa, s, dy_dev, V, partial) != DWM_OK) return DWM_ERR_HIP;
