@@ -7,10 +7,18 @@ timed region (it is a function of the weights only).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu-baseline]
 
---config picks one of the five layers of dwm_workloads.CONFIGS (default 1, the stride-2
-downsampling layer the headline metric is quoted on).  --paper-layer KERNEL,HW,STRIDE runs one
-of the paper's own single-layer shapes instead (Sec. 5: batch 256, same padding, 14x14 maps
-with 256 channels/filters or 28x28 with 128, standard-normal inputs AND weights).
+--config picks one of the five layers of dwm_workloads.CONFIGS (default 2: the 7x7 stride-1
+layer with 256 channels, the largest of the five, 161 GFLOP of direct convolution per step).
+The headline line also carries `per_config`: every one of the five layers measured the same
+way in the same run (the paper's runtime table, Table 4, is per layer as well).
+--paper-layer KERNEL,HW,STRIDE runs one of the paper's own single-layer shapes instead
+(Sec. 5: batch 256, same padding, 14x14 maps with 256 channels/filters or 28x28 with 128,
+standard-normal inputs AND weights).
+
+Stage times: each stage is timed as ONE pair of HIP events around `steps` back-to-back launches
+of that stage on the stream the kernels run on, so the figure is the kernel's own average
+duration (what a rocprofv3 kernel trace of the same command reports), not a launch plus the
+idle gap before a dependent launch.
 """
 import argparse
 import json
@@ -27,16 +35,20 @@ PEAK_MFMA_F32 = 157.3  # TFLOP/s, dense fp32 MFMA, MI355X
 PEAK_HBM = 8000.0      # GB/s
 
 
-# HBM-side bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, each scaled by what the
-# counter reads for the copy probe of known size (factors 2.00 and 1.00); see profiles/.
-TRAFFIC = {
-    ("cfg2_3x3s2_c128k256_56", "contract_kernel"): 332.9e6,
-    ("cfg2_3x3s2_c128k256_56", "input_transform_kernel"): 132.3e6,
-    ("cfg3_7x7s1_c256k256_28", "contract_kernel"): 2.473e9,
-    ("cfg3_7x7s1_c256k256_28", "input_transform_kernel"): 672.2e6,
-    ("cfg4_7x7s2_c3k64_224", "fused_forward_kernel"): 326.9e6,
-    ("cfg5_11x11s4_c3k96_227", "fused_forward_kernel"): 328.4e6,
-}
+def hbm_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    summary under profiles/ (each counter scaled by what it reads for a plain copy of known
+    size; the file states the build and commands it came from), or None if it has no such line."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) >= 5 and not line.startswith("#") and t[0] == workload and t[1] == kernel:
+                    return float(t[4])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(x, w, L, target_s=12.0):
@@ -60,9 +72,23 @@ def cpu_baseline(x, w, L, target_s=12.0):
     t0 = time.perf_counter()
     oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
     dt = time.perf_counter() - t0
-    return {"value": per_out * n / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(dt, 2),
-            "sample": "%d of %d outputs of %s drawn uniformly, FP64 direct convolution" % (n, total, L.name)}
+    out = {"value": per_out * n / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+           "kind": "oracle", "seconds": round(dt, 2),
+           "sample": "%d of %d outputs of %s drawn uniformly, FP64 direct convolution" % (n, total, L.name)}
+    # the oracle's FP64 DWM (the paper's five steps, part by part) beside it: whole images of the
+    # same layer, as many as fit the time
+    per_img = 2.0 * L.K * L.C * L.R * L.S * OH * OW
+    t0 = time.perf_counter()
+    oracle.dwm_f64(x[:1], w, L.stride, L.pad)
+    dt1 = time.perf_counter() - t0
+    nimg = int(max(1, min(L.N, target_s / 2 / max(dt1, 1e-6))))
+    if nimg > 1:
+        t0 = time.perf_counter()
+        oracle.dwm_f64(x[:nimg], w, L.stride, L.pad)
+        dt1 = time.perf_counter() - t0
+    out["dwm_f64"] = {"value": per_img * nimg / dt1 / 1e12, "unit": "TFLOP/s", "seconds": round(dt1, 2),
+                      "sample": "%d of %d images of %s, FP64 DWM reference (direct-equivalent flops)" % (nimg, L.N, L.name)}
+    return out
 
 
 def bench_backward_data(args, L, x, w):
@@ -253,56 +279,18 @@ def bench_half(args, L, x, w):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1)
-    ap.add_argument("--paper-layer", type=str, default="", help="KERNEL,HW,STRIDE[,BATCH] e.g. 7,14,1")
-    ap.add_argument("--contract-variant", type=int, default=-1)
-    ap.add_argument("--input-variant", type=int, default=-1)
-    ap.add_argument("--split-mode", type=int, default=-1)
-    ap.add_argument("--input-cg", type=int, default=-1)
-    ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
-    ap.add_argument("--backward-data", action="store_true",
-                    help="time the gradient with respect to the input of the same layer instead of the forward pass")
-    ap.add_argument("--backward-filter", action="store_true",
-                    help="time the gradient with respect to the filter of the same layer instead of the forward pass")
-    ap.add_argument("--half", action="store_true",
-                    help="time the half-precision forward path (dwm_f16_*) of the same layer")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-check", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-                 "use --gpus 1. The forward path would shard over the batch with no exchange.")
-
+def measure_forward(L, index, steps, warmup, args, check=True):
+    """One layer through dwm_conv_forward: whole-step time, per-stage kernel times, accuracy."""
     import numpy as np
     import torch
 
     import dwm_workloads as wl
     import paper_2002_00552_amd as dwm
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    torch.cuda.set_device(0)
     if args.paper_layer:
-        vals = [int(v) for v in args.paper_layer.split(",")]
-        kern, hw, stride = vals[:3]
-        L = wl.paper_layer(kern, hw, stride, *vals[3:4])  # optional fourth value: batch size (the paper's is 256)
-        x, w = wl.make_layer_tensors(L, 100 * kern + hw + stride)
+        x, w = wl.make_layer_tensors(L, index)
     else:
-        L = wl.CONFIGS[args.config]
-        x, w = wl.make_layer_tensors(L, args.config)
-
-    if args.backward_data:
-        return bench_backward_data(args, L, x, w)
-    if args.backward_filter:
-        return bench_backward_filter(args, L, x, w)
-    if args.half:
-        return bench_half(args, L, x, w)
-
+        x, w = wl.make_layer_tensors(L, index)
     plan = dwm.dwm_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     info = dwm.dwm_plan_info(plan)
     if args.contract_variant >= 0:
@@ -323,40 +311,38 @@ def main():
     st = torch.cuda.current_stream().cuda_stream
     xp, Up, yp = xd.data_ptr(), U.data_ptr(), y.data_ptr()
 
-    dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st)  # first call: code object load
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    ev[0].record()
-    dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st)
-    ev[1].record()
-    torch.cuda.synchronize()
-    filter_ms = ev[0].elapsed_time(ev[1])
+    def event():
+        return torch.cuda.Event(enable_timing=True)
 
-    for _ in range(args.warmup):
+    def timed(fn, n):
+        """average ms of n back-to-back calls of fn between one pair of events on the kernels' stream"""
+        e0, e1 = event(), event()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st)  # first call: code object load
+    filter_ms = timed(lambda: dwm.dwm_filter_transform(plan, wd.data_ptr(), Up, st), 1)
+
+    for _ in range(warmup):
         dwm.dwm_conv_forward(plan, xp, Up, yp, st)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         dwm.dwm_conv_forward(plan, xp, Up, yp, st)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = info.direct_flops / (dt / args.steps) / 1e12
+    ms_per_step = dt / steps * 1e3
 
-    # Per-kernel durations: the same K steps again, each kernel bracketed by HIP events on the
-    # stream the kernels run on (torch's current stream is the one handed to the library).
     path = dwm.dwm_plan_info(plan).forward_path
-    fused = path != 0
-    kname = {1: "fused_forward_kernel"}.get(path)
     v_bytes = 4.0 * info.mults_per_tile * L.C * info.T
     x_bytes, y_bytes = 4.0 * x.size, 4.0 * y.numel()
-    e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    if fused:
-        for i in range(args.steps):
-            e[i][0].record()
-            dwm.dwm_conv_forward(plan, xp, Up, yp, st)
-            e[i][1].record()
-        torch.cuda.synchronize()
-        f_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
+    if path != 0:
+        kname = "fused_forward_kernel"
+        f_ms = timed(lambda: dwm.dwm_conv_forward(plan, xp, Up, yp, st), steps)
         stages = {
             "fused_forward": {"ms": f_ms, "algorithmic_flops": info.winograd_flops,
                               "achieved_TFLOPs": info.winograd_flops / f_ms / 1e9,
@@ -368,17 +354,10 @@ def main():
         roofline = {"kernel": kname, "bound": "mfma",
                     "achieved": info.winograd_flops / f_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
                     "frac": info.winograd_flops / f_ms / 1e9 / PEAK_MFMA_F32,
-                    "traffic": TRAFFIC.get((L.name, kname))}
+                    "traffic": hbm_traffic(L.name, kname)}
     else:
-        for i in range(args.steps):
-            e[i][0].record()
-            dwm.dwm_input_transform(plan, xp, st)
-            e[i][1].record()
-            dwm.dwm_contract_output(plan, Up, yp, st)
-            e[i][2].record()
-        torch.cuda.synchronize()
-        in_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
-        ct_ms = sum(b.elapsed_time(c) for _, b, c in e) / args.steps
+        in_ms = timed(lambda: dwm.dwm_input_transform(plan, xp, st), steps)
+        ct_ms = timed(lambda: dwm.dwm_contract_output(plan, Up, yp, st), steps)
         stages = {
             "input_transform": {"ms": in_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + v_bytes,
                                 "achieved_GBps": (x_bytes + v_bytes) / in_ms / 1e6,
@@ -393,17 +372,15 @@ def main():
             roofline = {"kernel": "contract_kernel", "bound": "mfma",
                         "achieved": info.winograd_flops / ct_ms / 1e9, "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
                         "frac": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F32,
-                        "traffic": TRAFFIC.get((L.name, "contract_kernel"))}
+                        "traffic": hbm_traffic(L.name, "contract_kernel")}
         else:
-            roofline = {"kernel": "input_transform_kernel", "bound": "hbm",
+            roofline = {"kernel": "input_transform_lds_kernel", "bound": "hbm",
                         "achieved": (x_bytes + v_bytes) / in_ms / 1e6, "peak": PEAK_HBM, "unit": "GB/s",
                         "frac": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM,
-                        "traffic": TRAFFIC.get((L.name, "input_transform_kernel"))}
-
-    out = {
-        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                        "traffic": hbm_traffic(L.name, "input_transform_lds_kernel")}
+    res = {
+        "workload": L.name, "ms_per_step": ms_per_step,
+        "value": info.direct_flops / (dt / steps) / 1e12,
         "config": {"workload": L.name, "N": L.N, "C": L.C, "H": L.H, "W": L.W, "K": L.K, "R": L.R, "S": L.S,
                    "stride": L.stride, "pad": L.pad, "parts": info.n_parts,
                    "mults_per_tile": info.mults_per_tile, "direct_GFLOP": info.direct_flops / 1e9,
@@ -411,21 +388,106 @@ def main():
         "roofline": roofline, "stages": stages,
         "path": ["input transform + contraction", "single kernel (V in registers)"][path],
     }
-
-    if not args.no_check:
+    if check:
         import oracle
+        y.fill_(float("nan"))
+        dwm.dwm_conv_forward(plan, xp, Up, yp, st)
+        torch.cuda.synchronize()
         yh = y.cpu().numpy()
         rng = np.random.default_rng(99)
         idx = rng.choice(yh.size, min(yh.size, 40000), replace=False)
         ref = oracle.direct_f64_at(x, w, L.stride, L.pad, idx)
         got = yh.ravel()[idx].astype(np.float64)
         mse = float(np.mean((got - ref) ** 2))
-        out["accuracy"] = {"max_rel_err": float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))),
+        res["accuracy"] = {"max_rel_err": float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))),
                            "mse_vs_fp64_direct": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
                            "sampled_outputs": int(idx.size)}
+    dwm.dwm_plan_destroy(plan)
+    del xd, wd, U, ws, y
+    torch.cuda.empty_cache()
+    return res, x, w
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--paper-layer", type=str, default="", help="KERNEL,HW,STRIDE[,BATCH] e.g. 7,14,1")
+    ap.add_argument("--contract-variant", type=int, default=-1)
+    ap.add_argument("--input-variant", type=int, default=-1)
+    ap.add_argument("--split-mode", type=int, default=-1)
+    ap.add_argument("--input-cg", type=int, default=-1)
+    ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
+    ap.add_argument("--backward-data", action="store_true",
+                    help="time the gradient with respect to the input of the same layer instead of the forward pass")
+    ap.add_argument("--backward-filter", action="store_true",
+                    help="time the gradient with respect to the filter of the same layer instead of the forward pass")
+    ap.add_argument("--half", action="store_true",
+                    help="time the half-precision forward path (dwm_f16_*) of the same layer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="measure the chosen layer only (the default also measures the other four)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "use --gpus 1. The forward path would shard over the batch with no exchange.")
+
+    import torch
+
+    import dwm_workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    if args.paper_layer:
+        vals = [int(v) for v in args.paper_layer.split(",")]
+        kern, hw, stride = vals[:3]
+        L = wl.paper_layer(kern, hw, stride, *vals[3:4])  # optional fourth value: batch size (the paper's is 256)
+        index = 100 * kern + hw + stride
+    else:
+        L = wl.CONFIGS[args.config]
+        index = args.config
+
+    if args.backward_data or args.backward_filter or args.half:
+        x, w = wl.make_layer_tensors(L, index)
+        if args.backward_data:
+            return bench_backward_data(args, L, x, w)
+        if args.backward_filter:
+            return bench_backward_filter(args, L, x, w)
+        return bench_half(args, L, x, w)
+
+    res, x, w = measure_forward(L, index, args.steps, args.warmup, args, check=not args.no_check)
+    out = {
+        "metric": METRIC, "value": res["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": res["config"], "roofline": res["roofline"], "stages": res["stages"], "path": res["path"],
+    }
+    if "accuracy" in res:
+        out["accuracy"] = res["accuracy"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, w, L)
-    dwm.dwm_plan_destroy(plan)
+    del x, w
+    if not args.no_per_config and not args.paper_layer:
+        # all five layers, each measured like the headline one (its own entry is repeated here)
+        per = []
+        for i, Li in enumerate(wl.CONFIGS):
+            r = res if i == args.config else measure_forward(Li, i, min(args.steps, 100), min(args.warmup, 30), args,
+                                                             check=not args.no_check)[0]
+            e = {"workload": r["workload"], "ms_per_step": r["ms_per_step"], "direct_equiv_TFLOPs": r["value"],
+                 "path": r["path"], "kernel": r["roofline"]["kernel"], "bound": r["roofline"]["bound"],
+                 "frac": r["roofline"]["frac"],
+                 "stage_ms": {k: v["ms"] for k, v in r["stages"].items()}}
+            if "input_transform" in r["stages"]:
+                e["input_transform_frac_of_hbm_peak"] = r["stages"]["input_transform"]["frac_of_hbm_peak"]
+            if "accuracy" in r:
+                e["max_rel_err"] = r["accuracy"]["max_rel_err"]
+                e["log10_mse_plus_10"] = r["accuracy"]["log10_mse_plus_10"]
+            per.append(e)
+        out["per_config"] = per
     print(json.dumps(out))
 
 

@@ -1,21 +1,38 @@
 """Peak probes of libdwm_probe.so: streaming copy / fill / read and an fp32 MFMA loop.
 
-Not part of the convolution path.  `python paper_2002_00552_amd/probe.py` prints what the
-box reaches; run under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE) the copy of a known
-size (256 MiB read + 256 MiB written per launch) calibrates those counters.
+Not part of the convolution path or of the library package: they sit beside bench.py.
+`python bench_probes.py` prints what the box reaches; run under `rocprofv3 --pmc FETCH_SIZE`
+(or WRITE_SIZE) the copy of a known size (256 MiB read + 256 MiB written per launch)
+calibrates those counters.  `python bench_probes.py build` compiles bench_probes.hip into
+libdwm_probe.so next to this file (hipcc, gfx950; no GPU needed).
 """
 import ctypes
 import os
+import subprocess
 import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _P = ctypes.c_void_p
+PROBE_LIB = os.path.join(_HERE, "libdwm_probe.so")
+
+
+def build():
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = PROBE_LIB + ".%d.tmp" % os.getpid()
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-x", "hip",
+           os.path.join(_HERE, "bench_probes.hip"), "-o", tmp]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
 
 
 def lib():
-    path = os.path.join(_HERE, "libdwm_probe.so")
+    path = PROBE_LIB
     if not os.path.exists(path):
-        raise ImportError("libdwm_probe.so is not built: run `python -m paper_2002_00552_amd.build`")
+        raise ImportError("libdwm_probe.so is not built: run `python bench_probes.py build`")
     L = ctypes.CDLL(path)
     L.dwm_probe_copy.argtypes = [_P, _P, ctypes.c_size_t, ctypes.c_int, _P]
     L.dwm_probe_fill.argtypes = [_P, ctypes.c_size_t, ctypes.c_int, _P]
@@ -57,4 +74,7 @@ def measure(mib=256, reps=10, blocks=4096):
 
 if __name__ == "__main__":
     import json
+    if sys.argv[1:2] == ["build"]:
+        print(build())
+        sys.exit(0)
     print(json.dumps(measure(int(sys.argv[1]) if len(sys.argv) > 1 else 256)))
