@@ -20,8 +20,9 @@
  * Memory and streams.  Every pointer named *_dev is DEVICE memory owned by the caller;
  * the library never allocates or frees device memory, never synchronises, and enqueues
  * all kernels on the hipStream_t passed as `stream` (a `void*`; NULL = default stream).
- * A plan is host memory owned by the library (create/destroy).  A plan is immutable
- * after dwm_plan_set_workspace, so it may be reused for any number of calls; two calls
+ * A plan is host memory owned by the library (create/destroy).  Kernel variants that move
+ * the workspace layout ("contract", "split") can only be chosen BEFORE dwm_plan_set_workspace;
+ * afterwards the layout is fixed and the plan may be reused for any number of calls.  Two calls
  * that use the same plan (hence the same workspace) must be ordered on one stream.
  *
  * Errors are return codes, never exceptions or aborts.  Launch errors reported by the
@@ -152,8 +153,11 @@ DWM_API size_t dwm_plan_workspace_bytes(const dwm_plan_t* plan);
  * dwm_plan_workspace_bytes(plan) long, alive as long as the plan is used.  No GPU call. */
 DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size_t bytes);
 
-/* Pick a kernel variant for a stage; variant < 0 restores the planner's own choice.
- *   "contract": tile shape / chunk depth of the contraction kernel (ids in csrc/plan.hpp);
+/* Pick a kernel variant for a stage (for tuning and tests; the planner's own choice is the
+ * default and variant < 0 restores it).
+ *   "contract": tile shape / chunk depth of the contraction kernel: 10..19, the ids of the
+ *               library's internal table of variants (a variant whose chunk depth does not divide
+ *               the plan's reduction padding does not apply);
  *   "forward":  0 = input transform + contraction, 1 = single kernel (layers with few input channels
  *               only; the planner's choice where it applies);
  *   "input":    0, 1 = gather form of the input transform (blocks-fast / rows-fast workgroup order),
@@ -165,11 +169,10 @@ DWM_API dwm_status_t dwm_plan_set_workspace(dwm_plan_t* plan, void* ws_dev, size
  *               tile per CU, every tile cut into 2..8 ranges of its own), 1 = one round and a
  *               remainder are cut into equal ranges altogether, 2 = whole tiles only.  For tuning
  *               and tests; results are the same up to fp32 rounding.
- * The workspace size depends on the contraction variant: choose it BEFORE asking
+ * The workspace size and layout depend on "contract" and "split": choose them BEFORE asking
  * dwm_plan_workspace_bytes.  DWM_ERR_INVALID_ARG for an unknown stage or a variant that does
- * not apply to this plan; DWM_ERR_WORKSPACE (variant unchanged) if a workspace was already
- * handed over and is too small for the new variant.  After a change of the contraction
- * variant, dwm_input_transform must run again before dwm_contract_output. */
+ * not apply to this plan; DWM_ERR_WORKSPACE (nothing changed) for "contract" or "split" once
+ * a workspace has been handed over. */
 DWM_API dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int variant);
 
 /*
@@ -298,7 +301,7 @@ DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan,
  * are return codes.  Workspace: dwm_f16_workspace_bytes, 256-byte aligned (V in binary16, partial
  * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes.
  * dwm_f16_set_variant(plan, "contract", v): v in 30..47 selects the contraction's tile shape
- * (v < 0: the planner's choice); (plan, "input", v): 0 = gather form of the input transform,
+ * (v < 0: the planner's choice; before dwm_f16_set_workspace only); (plan, "input", v): 0 = gather form of the input transform,
  * 1 = LDS-staged form (C a multiple of 8, or at most 64, and a staged region that fits), v < 0: the planner's
  * choice; DWM_ERR_INVALID_ARG if the variant does not apply to the layer.
  * dwm_f16_conv_forward_f32out is the same computation with y left in FP32 (not rounded): it

@@ -1017,16 +1017,12 @@ dwm_status_t dwm_f16_set_variant(dwm_f16_plan_t* plan, const char* stage, int va
         return DWM_OK;
     }
     if (std::strcmp(stage, "contract")) return DWM_ERR_INVALID_ARG;
+    if (plan->ws) return DWM_ERR_WORKSPACE;  // the variant moves the partial outputs and counters inside the workspace
     if (variant < 0) variant = dwm::default_variant16(plan->fwd->lgran, plan->fwd->d.K);
     if (variant < dwm::kFirstHalfVariant || variant > dwm::kLastHalfVariant) return DWM_ERR_INVALID_ARG;
     dwm::ContractGeometry g;
     if (!dwm::contract_geometry(*plan->fwd, variant, &g)) return DWM_ERR_INVALID_ARG;
-    const dwm::ContractGeometry old = plan->fwd->geo;
     plan->fwd->geo = g;
-    if (plan->ws && plan->ws_bytes < plan->need_bytes()) {
-        plan->fwd->geo = old;  // the workspace already handed over cannot hold this variant's partial outputs
-        return DWM_ERR_WORKSPACE;
-    }
     return DWM_OK;
 }
 

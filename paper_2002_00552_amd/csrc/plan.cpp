@@ -452,6 +452,8 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
         plan->variant_forward = variant;
         return DWM_OK;
     }
+    // what follows moves the partial outputs and the arrival counters inside the workspace
+    if (plan->ws) return std::strcmp(stage, "split") && std::strcmp(stage, "contract") ? DWM_ERR_INVALID_ARG : DWM_ERR_WORKSPACE;
     if (!std::strcmp(stage, "split")) {  // 0: whole tiles + split remainder, 1: all tiles split evenly
         const int old_mode = plan->sk_mode;
         plan->sk_mode = variant == 1 ? 1 : variant == 2 ? 2 : 0;
@@ -463,12 +465,7 @@ dwm_status_t dwm_plan_set_variant(dwm_plan_t* plan, const char* stage, int varia
     dwm::ContractGeometry g;
     if (!dwm::contract_geometry(*plan, variant < 0 ? default_contract_variant(plan->lgran, plan->d.K, plan->d.T) : variant, &g))
         return DWM_ERR_INVALID_ARG;
-    const dwm::ContractGeometry old = plan->geo;
     plan->geo = g;
-    if (plan->ws && plan->ws_bytes < plan->ws_need_bytes()) {
-        plan->geo = old;  // the workspace already handed over cannot hold this variant's partial outputs
-        return DWM_ERR_WORKSPACE;
-    }
     return DWM_OK;
 }
 
