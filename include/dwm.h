@@ -192,6 +192,23 @@ DWM_API dwm_status_t dwm_filter_transform(const dwm_plan_t* plan, const float* w
 DWM_API dwm_status_t dwm_conv_forward(const dwm_plan_t* plan, const float* x_dev, const float* Ugw_dev,
                               float* y_dev, void* stream);
 
+/*
+ * dwm_conv_forward for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * plan's workspace is replaced by a fixed array of DWM_STATIC_SCRATCH_BYTES that lives in the
+ * library's code object (one copy per GPU the library runs on, held until the process ends);
+ * the plan needs no dwm_plan_set_workspace.  Nothing is allocated, on the device or the host.
+ * DWM_ERR_WORKSPACE if dwm_plan_workspace_bytes(plan) exceeds DWM_STATIC_SCRATCH_BYTES
+ * (dwm_static_scratch_bytes() returns the same figure at run time).  Layers that take the single-kernel
+ * path use no scratch and are never refused.  All calls on one GPU share that GPU's array:
+ * calls that may overlap (different streams, different threads) race; order them on one stream.
+ * Results are those of dwm_conv_forward, bit for bit.
+ */
+#define DWM_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+DWM_API size_t dwm_static_scratch_bytes(void);
+DWM_API dwm_status_t dwm_conv_forward_static(const dwm_plan_t* plan, const float* x_dev, const float* Ugw_dev,
+                                             float* y_dev, void* stream);
+
 /* The two stages of dwm_conv_forward on their own (for per-stage tests and timing):
  * dwm_input_transform fills the workspace with V (Sec. 4.1 "Splitting" of the input and
  * "Transformation"); dwm_contract_output reads V from the workspace and does the

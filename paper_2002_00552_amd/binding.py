@@ -81,6 +81,8 @@ _SIGNATURES = {
     "dwm_plan_set_variant": (_I, [_P, ctypes.c_char_p, _I]),
     "dwm_filter_transform": (_I, [_P, _P, _P, _P]),
     "dwm_conv_forward": (_I, [_P, _P, _P, _P, _P]),
+    "dwm_static_scratch_bytes": (ctypes.c_size_t, []),
+    "dwm_conv_forward_static": (_I, [_P, _P, _P, _P, _P]),
     "dwm_input_transform": (_I, [_P, _P, _P]),
     "dwm_contract_output": (_I, [_P, _P, _P, _P]),
     "dwm_status_string": (ctypes.c_char_p, [_I]),
@@ -209,6 +211,14 @@ def dwm_filter_transform(plan, w_dev, Ugw_dev, stream=None):
 
 def dwm_conv_forward(plan, x_dev, Ugw_dev, y_dev, stream=None):
     _check(lib().dwm_conv_forward(plan, x_dev, Ugw_dev, y_dev, stream), "dwm_conv_forward")
+
+
+def dwm_static_scratch_bytes():
+    return int(lib().dwm_static_scratch_bytes())
+
+
+def dwm_conv_forward_static(plan, x_dev, Ugw_dev, y_dev, stream=None):
+    _check(lib().dwm_conv_forward_static(plan, x_dev, Ugw_dev, y_dev, stream), "dwm_conv_forward_static")
 
 
 def dwm_input_transform(plan, x_dev, stream=None):

@@ -406,7 +406,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
 // Launcher
 // ---------------------------------------------------------------------------------
 template <int WGM, int WGN, int WM, int WN, int LC, int NS>
-static dwm_status_t launch_variant(const dwm_plan& p, const float* U, const float* V, float* y, void* stream)
+static dwm_status_t launch_variant(const dwm_plan& p, const float* U, float* V, float* y, void* stream)
 {
     constexpr int KT = 32 * WM * WGM, TT = 32 * WN * WGN;
     static_assert(kKAlign % KT == 0 && kTAlign % TT == 0, "padding must cover the tile");
@@ -433,11 +433,11 @@ static dwm_status_t launch_variant(const dwm_plan& p, const float* U, const floa
         if (attr_d != hipSuccess || attr_m != hipSuccess) return DWM_ERR_HIP;
     }
     hipLaunchKernelGGL(dense ? kd : km, dim3((unsigned)blocks), dim3(64 * WGM * WGN), lds_bytes, (hipStream_t)stream,
-                       a, p.planes, U, V, y, p.sk_partial(), p.sk_counters());
+                       a, p.planes, U, static_cast<const float*>(V), y, p.sk_partial(V), p.sk_counters(V));
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }
 
-dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const float* V, float* y, void* stream)
+dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, float* V, float* y, void* stream)
 {
     switch (p.geo.variant) {
         case 10: return launch_variant<2, 2, 1, 1, 16, 4>(p, U, V, y, stream);

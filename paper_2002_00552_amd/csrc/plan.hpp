@@ -247,8 +247,12 @@ struct dwm_plan {
     // workspace layout: [ V | partial outputs | arrival counters ]
     size_t ws_need_bytes() const { return (v_floats + geo.partial_floats) * sizeof(float) + counters_bytes(); }
     size_t counters_bytes() const { return ((size_t)geo.n_sk_tiles * sizeof(int) + 255) / 256 * 256; }
-    float* sk_partial() const { return ws ? ws + v_floats : nullptr; }
-    int* sk_counters() const { return ws ? reinterpret_cast<int*>(ws + v_floats + geo.partial_floats) : nullptr; }
+    // (given the workspace's base, so that a call may run on a workspace other than the plan's own)
+    float* sk_partial(float* base) const { return base ? base + v_floats : nullptr; }
+    int* sk_counters(float* base) const
+    {
+        return base ? reinterpret_cast<int*>(base + v_floats + geo.partial_floats) : nullptr;
+    }
 };
 
 namespace dwm {
@@ -272,8 +276,10 @@ dwm_status_t plan_from_spec_as_printed(dwm_plan_t** out, const PlanSpec& sp);
 bool contract_geometry(const dwm_plan& p, int variant, ContractGeometry* out);
 // transforms.hip, contract.hip
 dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U, void* stream);
-dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream);
-dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, const float* V, float* y, void* stream);
+// `ws` is the base of a workspace laid out as the plan says: V first, then the partial outputs and
+// the arrival counters of the contraction's split tiles
+dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* ws, void* stream);
+dwm_status_t launch_contract_output(const dwm_plan& p, const float* U, float* ws, float* y, void* stream);
 bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish);
 // contract_batch.hip
 dwm_status_t launch_contract_batch(const BatchArgs& a, const PlaneTable& pt, int lc, const float* U, const float* V,

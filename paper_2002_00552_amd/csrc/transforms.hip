@@ -394,14 +394,14 @@ dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V,
             if (attr != hipSuccess) return DWM_ERR_HIP;
         }
         hipLaunchKernelGGL(kernel, dim3((unsigned)(nb * a.ncg)), block, a.lds_bytes, (hipStream_t)stream, d, a, x, V,
-                           p.sk_counters(), p.geo.n_sk_tiles, variant == 2, p.skip_pad_rows ? 0 : 1);
+                           p.sk_counters(V), p.geo.n_sk_tiles, variant == 2, p.skip_pad_rows ? 0 : 1);
         return check_launch();
     }
     int rows_fast = variant;
     if ((rows_fast ? nb : nr) > 65535) rows_fast = !rows_fast;
     if ((rows_fast ? nb : nr) > 65535) return DWM_ERR_UNSUPPORTED;
     dim3 grid(rows_fast ? nr : nb, rows_fast ? nb : nr);
-    hipLaunchKernelGGL(input_transform_kernel, grid, block, 0, (hipStream_t)stream, d, x, V, p.sk_counters(),
+    hipLaunchKernelGGL(input_transform_kernel, grid, block, 0, (hipStream_t)stream, d, x, V, p.sk_counters(V),
                        p.geo.n_sk_tiles, rows_fast);
     return check_launch();
 }
