@@ -26,6 +26,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "plan.hpp"
 
@@ -146,7 +147,7 @@ __device__ __forceinline__ void fused_at(const floatx4 m[4], floatx4 o[2])
 }
 
 // Y[a][b][half] += sum AT_h[a][fh] AT_w[b][fw] acc[fh][fw][half]
-template <int WH, int WW>
+template <int WH, int WW, bool ADD>
 __device__ __forceinline__ void fused_output(const floatx4 (&acc)[WH ? 4 : 2][WW ? 4 : 2][2], floatx4 (&Y)[2][2][2])
 {
     constexpr int NH = WH ? 4 : 2, NW = WW ? 4 : 2;
@@ -168,8 +169,8 @@ __device__ __forceinline__ void fused_output(const floatx4 (&acc)[WH ? 4 : 2][WW
 #pragma unroll
             for (int fh = 0; fh < 4; ++fh) m[fh] = t[fh < NH ? fh : 0][b];
             fused_at<WH>(m, o);
-            Y[0][b][half] += o[0];
-            Y[1][b][half] += o[1];
+            Y[0][b][half] = ADD ? Y[0][b][half] + o[0] : o[0];
+            Y[1][b][half] = ADD ? Y[1][b][half] + o[1] : o[1];
         }
     }
 }
@@ -192,44 +193,79 @@ __device__ __forceinline__ void fused_read_patch(const float* __restrict__ xt, c
     }
 }
 
-// uf: the class's filter copy for this slice (the same for the whole wave); voff = 8 * lane.
-template <int WH, int WW>
+// The same from two offsets per patch row: columns 0,2 and 1,3 of a patch are 2*stride input columns
+// apart, which is one word in the de-interleaved staged row, so a patch row is two reads of two
+// adjacent words (ri: [row][2] offsets of patch rows 0..3 for column 0 and for column 1).
+__device__ __forceinline__ void fused_read_patch_pairs(const float* __restrict__ xt, const int4* __restrict__ ri,
+                                                       float (&d)[4][4])
+{
+    const char* xb = reinterpret_cast<const char*>(xt);
+    const int4 o0 = ri[0], o1 = ri[1];
+    const int a0[4] = {o0.x, o0.y, o0.z, o0.w}, a1[4] = {o1.x, o1.y, o1.z, o1.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float* p0 = reinterpret_cast<const float*>(xb + a0[i]);
+        const float* p1 = reinterpret_cast<const float*>(xb + a1[i]);
+        d[i][0] = p0[0];
+        d[i][2] = p0[1];
+        d[i][1] = p1[0];
+        d[i][3] = p1[1];
+    }
+}
+
+// rsrc: raw buffer over the class's filter copy, soff: byte offset of this slice in it; voff = 8 * lane.
+// PAIRS: the table holds two offsets per patch row (see above; only with WH = WW = 1), and the
+// operands of the class's FIRST step come in through a and d0, fetched by the caller or by the
+// previous slice: the last step fetches the first step's operands of the slice at soff_next.  A
+// slice's loads are then older than the previous slice's stores to y, so that waiting for them
+// (the counter of vector-memory operations runs in issue order) does not wait for those stores.
+// ADD: the class's output is added to Y; otherwise it is stored there.
+template <int WH, int WW, bool PAIRS, bool ADD>
 __device__ __forceinline__ void fused_class(const FusedArgs& F, const FusedClass& fc, const float* __restrict__ xt,
-                                         const int4* __restrict__ ri, const float* __restrict__ uf, unsigned voff,
-                                         floatx4 (&Y)[2][2][2])
+                                         const int4* __restrict__ ri, __amdgpu_buffer_rsrc_t rsrc, unsigned soff,
+                                         unsigned soff_next, unsigned voff, float2 (&a)[WH ? 4 : 2][WW ? 4 : 2],
+                                         float (&d0)[WH ? 4 : 2][WW ? 4 : 2], floatx4 (&Y)[2][2][2])
 {
     constexpr int NH = WH ? 4 : 2, NW = WW ? 4 : 2;
-    floatx4 acc[NH][NW][2];
-#pragma unroll
-    for (int i = 0; i < NH; ++i)
-#pragma unroll
-        for (int j = 0; j < NW; ++j) {
-            acc[i][j][0] = floatx4{0.f, 0.f, 0.f, 0.f};
-            acc[i][j][1] = floatx4{0.f, 0.f, 0.f, 0.f};
-        }
+    static_assert(!PAIRS || (WH && WW), "pairs of adjacent words: four-column patches only");
+    floatx4 acc[NH][NW][2];  // never cleared: the first step multiplies into zero
     const unsigned plane_bytes = (unsigned)fc.rows * 32u * (unsigned)sizeof(float);
-    // raw buffer over the class's copy for this slice (at most nfh*nfw*rows*128 bytes)
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float*>(uf), 0, (int)(plane_bytes * (unsigned)(NH * NW)), 0x00020000);
     // A operands travel one step ahead: a plane's registers are refilled for the next step as
-    // soon as its MFMAs of this step are issued (the last step refills with itself).
-    float2 a[NH][NW];
+    // soon as its MFMAs of this step are issued (the last step refills with itself, or with the next
+    // slice's first step).
+    float d1[NH][NW];
+    auto read_patch = [&](int st, float (&d)[NH][NW]) {
+        if constexpr (PAIRS) fused_read_patch_pairs(xt, ri + 8 * st, d);
+        else fused_read_patch<NH, NW>(xt, ri + 16 * st, d);
+    };
+    if (!PAIRS) {
 #pragma unroll
-    for (int i = 0; i < NH; ++i)
+        for (int i = 0; i < NH; ++i)
 #pragma unroll
-        for (int j = 0; j < NW; ++j) a[i][j] = fused_load_a(rsrc, voff, (unsigned)(i * NW + j) * plane_bytes);
+            for (int j = 0; j < NW; ++j) a[i][j] = fused_load_a(rsrc, voff, soff + (unsigned)(i * NW + j) * plane_bytes);
+        // the patch of the NEXT step is read from LDS before this step's MFMAs are issued; a row's
+        // 16 patch offsets (bytes, channel included) come from the table, the lane's tile base is added
+        // (two patch buffers that swap roles from step to step: the loop body is written twice)
+        read_patch(0, d0);
+    }
     int type = F.step_type[fc.step0];
-    // the patch of the NEXT step is read from LDS before this step's MFMAs are issued; a row's
-    // 16 patch offsets (bytes, channel included) come from the table, the lane's tile base is added
-    // (two patch buffers that swap roles from step to step: the loop body is written twice)
-    float d0[NH][NW], d1[NH][NW];
-    fused_read_patch<NH, NW>(xt, ri, d0);
-    auto step = [&](int st, const float (&d)[NH][NW], float (&dn)[NH][NW]) {
+    const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    // one plane of a step: both filter halves; FIRST: the class's first step starts the accumulators
+    auto mfma = [&](auto first_tag, int i, int j, float bv, bool on) {
+        if constexpr (decltype(first_tag)::value) {
+            acc[i][j][0] = on ? __builtin_amdgcn_mfma_f32_16x16x4f32(a[i][j].x, bv, zero4, 0, 0, 0) : zero4;
+            acc[i][j][1] = on ? __builtin_amdgcn_mfma_f32_16x16x4f32(a[i][j].y, bv, zero4, 0, 0, 0) : zero4;
+        } else {
+            if (on) fused_mfma(a[i][j], bv, acc[i][j]);
+        }
+    };
+    auto step = [&](auto first_tag, int st, const float (&d)[NH][NW], float (&dn)[NH][NW]) {
         const bool h3 = !WH || (type >> 2) == 3, w3 = !WW || (type & 3) == 3;  // fourth frequency present
-        const int nst = st + 1 < fc.nsteps ? st + 1 : st;
+        const bool last = st + 1 >= fc.nsteps;
+        const int nst = !last ? st + 1 : PAIRS ? 0 : st;
         type = F.step_type[fc.step0 + nst];
-        const unsigned un = (unsigned)nst * 512u;
-        fused_read_patch<NH, NW>(xt, ri + 16 * nst, dn);
+        const unsigned un = (last && PAIRS ? soff_next : soff) + (unsigned)nst * 512u;
+        read_patch(nst, dn);
         float tmp[NH][NW];
 #pragma unroll
         for (int j = 0; j < NW; ++j) {
@@ -255,54 +291,59 @@ __device__ __forceinline__ void fused_class(const FusedArgs& F, const FusedClass
         for (int i = 0; i < CH; ++i)
 #pragma unroll
             for (int j = 0; j < CW; ++j) {
-                fused_mfma(a[i][j], v[i][j], acc[i][j]);
+                mfma(first_tag, i, j, v[i][j], true);
                 a[i][j] = fused_load_a(rsrc, voff, un + (unsigned)(i * NW + j) * plane_bytes);
             }
         if (WW) {
-            if (w3) {
+            if (decltype(first_tag)::value || w3) {
 #pragma unroll
-                for (int i = 0; i < CH; ++i) fused_mfma(a[i][NW - 1], v[i][NW - 1], acc[i][NW - 1]);
+                for (int i = 0; i < CH; ++i) mfma(first_tag, i, NW - 1, v[i][NW - 1], w3);
             }
 #pragma unroll
             for (int i = 0; i < CH; ++i) a[i][NW - 1] = fused_load_a(rsrc, voff, un + (unsigned)(i * NW + 3) * plane_bytes);
         }
         if (WH) {
-            if (h3) {
+            if (decltype(first_tag)::value || h3) {
 #pragma unroll
-                for (int j = 0; j < CW; ++j) fused_mfma(a[NH - 1][j], v[NH - 1][j], acc[NH - 1][j]);
-                if (WW && w3) fused_mfma(a[NH - 1][NW - 1], v[NH - 1][NW - 1], acc[NH - 1][NW - 1]);
+                for (int j = 0; j < CW; ++j) mfma(first_tag, NH - 1, j, v[NH - 1][j], h3);
+                if (WW) mfma(first_tag, NH - 1, NW - 1, v[NH - 1][NW - 1], h3 && w3);
             }
 #pragma unroll
             for (int j = 0; j < NW; ++j) a[NH - 1][j] = fused_load_a(rsrc, voff, un + (unsigned)(3 * NW + j) * plane_bytes);
         }
     };
-    int st = 0;
+    step(std::true_type{}, 0, d0, d1);
+    int st = 1;
     for (; st + 1 < fc.nsteps; st += 2) {
-        step(st, d0, d1);
-        step(st + 1, d1, d0);
+        step(std::false_type{}, st, d1, d0);
+        step(std::false_type{}, st + 1, d0, d1);
     }
-    if (st < fc.nsteps) step(st, d0, d1);
-    fused_output<WH, WW>(acc, Y);
+    if (st < fc.nsteps) step(std::false_type{}, st, d1, d0);
+    if (PAIRS && (fc.nsteps & 1)) {  // the next slice's first patch was read into d1
+#pragma unroll
+        for (int i = 0; i < NH; ++i)
+#pragma unroll
+            for (int j = 0; j < NW; ++j) d0[i][j] = d1[i][j];
+    }
+    fused_output<WH, WW, ADD>(acc, Y);
 }
 
 // MULTI: the layer has more than one class, so their outputs are summed in Y; with a single
 // class (no one-tap pieces) the registers of Y are saved: the class's output is the result.
-template <bool MULTI>
+// PAIRS (single class of two- and three-tap pieces): patch rows are read as pairs of adjacent words.
+template <bool MULTI, bool PAIRS>
 __global__ __launch_bounds__(256, 2) void fused_forward_kernel(DevPlan P, FusedArgs F, const float* __restrict__ x,
                                                             const float* __restrict__ U, float* __restrict__ y)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     // LDS: per-row patch offsets | staged input
-    int4* rowinfo = reinterpret_cast<int4*>(lds);                      // [rows_total][4]: byte offsets [i][j]
-    float* xs = reinterpret_cast<float*>(rowinfo + 4 * F.rows_total);  // [C][nrows][nphase][lwp]
+    constexpr int RI = PAIRS ? 2 : 4;
+    int4* rowinfo = reinterpret_cast<int4*>(lds);  // [rows_total][4]: byte offsets [i][j]; PAIRS: [rows_total][2]: [j][i]
+    float* xs = reinterpret_cast<float*>(rowinfo + RI * F.rows_total);  // [C][nrows][nphase][lwp]
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int ln = lane & 15, lq = lane >> 4;
-
-    const int b = blockIdx.x;
-    const int btx = b % F.nbw, bty = (b / F.nbw) % F.nbh, n = b / (F.nbw * F.nbh);
-    const int ty0 = bty * F.BH, tx0 = btx * F.BW;
 
     // ---- 0. per-row patch offsets (row = part x channel), looked up once ----
     for (int r = tid; r < F.rows_total; r += 256) {
@@ -310,10 +351,43 @@ __global__ __launch_bounds__(256, 2) void fused_forward_kernel(DevPlan P, FusedA
         const int base = (int)((desc >> 8) & 127) * F.chan_floats;
         const int* rr = F.roff[desc & 15];
         const int* cc = F.coff[(desc >> 4) & 15];
+        if (PAIRS) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                rowinfo[2 * r + j] = make_int4(4 * (base + rr[0] + cc[j]), 4 * (base + rr[1] + cc[j]),
+                                               4 * (base + rr[2] + cc[j]), 4 * (base + rr[3] + cc[j]));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                rowinfo[4 * r + i] = make_int4(4 * (base + rr[i] + cc[0]), 4 * (base + rr[i] + cc[1]),
+                                               4 * (base + rr[i] + cc[2]), 4 * (base + rr[i] + cc[3]));
+        }
+    }
+
+    // Workgroups are persistent: each takes every gridDim.x-th block of tiles (the table above is built
+    // once, and a workgroup's last stores need not drain before the CU gets new work).
+    const int nblocks = P.N * F.nbh * F.nbw;
+    for (int b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    if (b != (int)blockIdx.x) __syncthreads();  // every wave is done with the staged input of the block before
+    const int btx = b % F.nbw, bty = (b / F.nbw) % F.nbh, n = b / (F.nbw * F.nbh);
+    const int ty0 = bty * F.BH, tx0 = btx * F.BW;
+
+    // PAIRS: the first slice's first A operands are asked for before the input is staged (one memory
+    // latency instead of two); later slices get theirs from the slice before
+    const int slice0 = blockIdx.y * F.slices_per_wg;
+    const int slice1 = min(slice0 + F.slices_per_wg, F.nslices);
+    const unsigned voff = (unsigned)lane * 8u;
+    const FusedClass fc0 = F.fc[0];
+    const __amdgpu_buffer_rsrc_t rsrc0 = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(U + fc0.uf_off), 0, (int)((unsigned)(fc0.nfh * fc0.nfw * fc0.rows) * 128u * (unsigned)F.nslices),
+        0x00020000);
+    float2 a0[4][4];
+    if constexpr (PAIRS) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            rowinfo[4 * r + i] = make_int4(4 * (base + rr[i] + cc[0]), 4 * (base + rr[i] + cc[1]),
-                                           4 * (base + rr[i] + cc[2]), 4 * (base + rr[i] + cc[3]));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                a0[i][j] = fused_load_a(rsrc0, voff, (unsigned)(slice0 * 16 + i * 4 + j) * ((unsigned)fc0.rows * 128u));
     }
 
     // ---- 1. stage the block's input region (padded coordinates).  A unit is (channel, 8 rows);
@@ -367,153 +441,90 @@ __global__ __launch_bounds__(256, 2) void fused_forward_kernel(DevPlan P, FusedA
     const bool tile_ok = by < F.BH && ty < P.TH && tx < P.TW;
     const float* xt = xs + (by < F.BH ? by * F.tile_row_step + bx : 0);
 
-    const int slice0 = blockIdx.y * F.slices_per_wg;
-    const int slice1 = min(slice0 + F.slices_per_wg, F.nslices);
+    // dense y with an even row length: a uniform base per filter plus the lane's two row offsets
+    const int oh = 2 * ty, ow = 2 * tx;
+    const bool dense = P.om.sy == 1 && P.om.sx == 1 && P.om.oy == 0 && P.om.ox == 0 && P.om.YH == P.OH &&
+                       P.om.YW == P.OW && (P.OW & 1) == 0;
+    const unsigned yoff0 = (unsigned)(((lq * 4) * P.OH + oh) * P.OW + ow) * 4u, yoff1 = yoff0 + (unsigned)P.OW * 4u;
+    const bool row1 = oh + 1 < P.OH;
+    float p0[4][4];
+    if constexpr (PAIRS) fused_read_patch_pairs(xt, rowinfo + 2 * lq, p0);
     for (int ks = slice0; ks < slice1; ++ks) {
         floatx4 Y[2][2][2];
+        if (MULTI) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+                for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) Y[a][c][h] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    for (int h = 0; h < 2; ++h) Y[a][c][h] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
 
-        for (int fi = 0; fi < (MULTI ? F.nfc : 1); ++fi) {
-            const FusedClass fc = F.fc[fi];
-            const float* uf = U + fc.uf_off + (size_t)ks * fc.nfh * fc.nfw * fc.rows * 32;
-            const int4* ri = rowinfo + 4 * (fc.row0 + lq);
-            const unsigned voff = (unsigned)lane * 8u;
-            if (fc.wide_h) {
-                if (fc.wide_w) fused_class<1, 1>(F, fc, xt, ri, uf, voff, Y);
-                else fused_class<1, 0>(F, fc, xt, ri, uf, voff, Y);
-            } else {
-                if (fc.wide_w) fused_class<0, 1>(F, fc, xt, ri, uf, voff, Y);
-                else fused_class<0, 0>(F, fc, xt, ri, uf, voff, Y);
+        if constexpr (PAIRS) {
+            const unsigned sbytes = 16u * (unsigned)fc0.rows * 128u;  // one slice of the filter copy
+            fused_class<1, 1, true, false>(F, fc0, xt, rowinfo + 2 * lq, rsrc0, (unsigned)ks * sbytes,
+                                           (unsigned)(ks + 1 < slice1 ? ks + 1 : ks) * sbytes, voff, a0, p0, Y);
+        } else {
+            for (int fi = 0; fi < (MULTI ? F.nfc : 1); ++fi) {
+                const FusedClass fc = F.fc[fi];
+                const unsigned sbytes = (unsigned)(fc.nfh * fc.nfw * fc.rows) * 128u;
+                const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<float*>(U + fc.uf_off), 0, (int)(sbytes * (unsigned)F.nslices), 0x00020000);
+                const int4* ri = rowinfo + 4 * (fc.row0 + lq);
+                const unsigned so = (unsigned)ks * sbytes;
+                if (fc.wide_h) {
+                    float2 a[4][4];
+                    float d[4][4];
+                    if (fc.wide_w) fused_class<1, 1, false, MULTI>(F, fc, xt, ri, rsrc, so, so, voff, a, d, Y);
+                    else {
+                        float2 a2[4][2];
+                        float d2[4][2];
+                        fused_class<1, 0, false, MULTI>(F, fc, xt, ri, rsrc, so, so, voff, a2, d2, Y);
+                    }
+                } else {
+                    if (fc.wide_w) {
+                        float2 a2[2][4];
+                        float d2[2][4];
+                        fused_class<0, 1, false, MULTI>(F, fc, xt, ri, rsrc, so, so, voff, a2, d2, Y);
+                    } else {
+                        float2 a2[2][2];
+                        float d2[2][2];
+                        fused_class<0, 0, false, MULTI>(F, fc, xt, ri, rsrc, so, so, voff, a2, d2, Y);
+                    }
+                }
             }
         }
 
         // ---- scatter: lane (ln, lq) holds tile ln and filters 32*ks + 16*half + 4*lq + r ----
         if (tile_ok) {
-            const int oh = 2 * ty, ow = 2 * tx;
+            if (dense) {
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
+                for (int half = 0; half < 2; ++half)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int k = ks * 32 + half * 16 + lq * 4 + r;
-                    if (k >= P.K) continue;
-                    store_tile(y, P.om, P.OH, P.OW, (size_t)n * P.K + k, oh, ow, Y[0][0][half][r], Y[0][1][half][r],
-                               Y[1][0][half][r], Y[1][1][half][r]);
-                }
+                    for (int r = 0; r < 4; ++r) {
+                        const int ku = ks * 32 + half * 16 + r;  // + 4*lq is in the lane's offsets
+                        if (ku + 4 * lq >= P.K) continue;
+                        char* yk = reinterpret_cast<char*>(y + ((size_t)n * P.K + ku) * P.OH * P.OW);
+                        // (y is not read again by this kernel: streaming stores)
+                        typedef float f2v __attribute__((ext_vector_type(2)));
+                        const f2v r0v = {Y[0][0][half][r], Y[0][1][half][r]}, r1v = {Y[1][0][half][r], Y[1][1][half][r]};
+                        __builtin_nontemporal_store(r0v, reinterpret_cast<f2v*>(yk + yoff0));
+                        if (row1) __builtin_nontemporal_store(r1v, reinterpret_cast<f2v*>(yk + yoff1));
+                    }
+            } else {
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int k = ks * 32 + half * 16 + lq * 4 + r;
+                        if (k >= P.K) continue;
+                        store_tile(y, P.om, P.OH, P.OW, (size_t)n * P.K + k, oh, ow, Y[0][0][half][r], Y[0][1][half][r],
+                                   Y[1][0][half][r], Y[1][1][half][r]);
+                    }
+            }
         }
     }
-}
-
-// ---------------------------------------------------------------------------------
-// Host: does the path apply, and with which block of tiles
-// ---------------------------------------------------------------------------------
-bool fused_setup(const dwm_plan& p, FusedArgs* out)
-{
-    const DevPlan& d = p.d;
-    FusedArgs f{};
-    if (d.C > 127 || d.nh > 15 || d.nw > 15) return false;
-    // classes = pairs of families; inside a class the rows (part, channel) follow each other sorted by
-    // (len_h, len_w), longest first, and only the class's end is padded to a multiple of four.  A step
-    // whose four rows mix piece lengths runs the planes of the longest: the shorter pieces' rows hold
-    // zeros in the filter copy for the frequencies they lack.
-    int rows = 0, steps = 0;
-    int row_lh[kFusedMaxRows], row_lw[kFusedMaxRows];
-    for (int wh = 1; wh >= 0; --wh)
-        for (int ww = 1; ww >= 0; --ww) {
-            FusedClass fc{};
-            fc.wide_h = wh; fc.wide_w = ww;
-            fc.nfh = wh ? 4 : 2; fc.nfw = ww ? 4 : 2;
-            fc.step0 = steps; fc.row0 = rows;
-            for (int lh = 3; lh >= 1; --lh)
-                for (int lw = 3; lw >= 1; --lw) {
-                    if ((lh >= 2) != (wh == 1) || (lw >= 2) != (ww == 1)) continue;
-                    for (int a = 0; a < d.nh; ++a)
-                        for (int b = 0; b < d.nw; ++b) {
-                            if (d.ph[a].l != lh || d.pw[b].l != lw) continue;
-                            for (int c = 0; c < d.C; ++c) {
-                                if (rows >= kFusedMaxRows) return false;
-                                f.rowdesc[rows] = (unsigned short)(a | b << 4 | c << 8 | 1 << 15);
-                                row_lh[rows] = lh; row_lw[rows] = lw;
-                                ++rows;
-                            }
-                        }
-                }
-            if (rows == fc.row0) continue;
-            while ((rows - fc.row0) & 3) {  // padding rows: a real row's offsets, zero filter rows
-                if (rows >= kFusedMaxRows) return false;
-                f.rowdesc[rows] = (unsigned short)(f.rowdesc[rows - 1] & 0x7fff);
-                row_lh[rows] = row_lh[rows - 1]; row_lw[rows] = row_lw[rows - 1];
-                ++rows;
-            }
-            for (int r0 = fc.row0; r0 < rows; r0 += 4) {
-                if (steps >= kFusedMaxSteps) return false;
-                int mh = 0, mw = 0;
-                for (int r = r0; r < r0 + 4; ++r) { mh = std::max(mh, row_lh[r]); mw = std::max(mw, row_lw[r]); }
-                f.step_type[steps++] = mh * 4 + mw;
-            }
-            fc.nsteps = steps - fc.step0;
-            fc.rows = rows - fc.row0;
-            f.fc[f.nfc++] = fc;
-        }
-    f.rows_total = rows;
-
-    int max_oh = 0, max_ow = 0;
-    for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
-    for (int i = 0; i < d.nw; ++i) max_ow = std::max(max_ow, d.s * (d.pw[i].j + d.pw[i].l) + d.pw[i].p);
-    f.nphase = 2 * d.s;
-    const size_t table_bytes = (size_t)rows * 64;
-    const size_t budget = 72 * 1024;  // two workgroups per CU
-
-    // block of tiles: most useful lanes first, then the smallest staged region
-    double best_eff = 0.0;
-    size_t best_x = 0;
-    for (int bw = 1; bw <= 64 && bw <= d.TW; ++bw) {
-        int bh = 64 / bw;
-        if (bh > d.TH) bh = d.TH;
-        if (bh < 1) continue;
-        const int nbh = (d.TH + bh - 1) / bh, nbw = (d.TW + bw - 1) / bw;
-        const double eff = (double)d.TH * d.TW / ((double)nbh * nbw * 64);
-        const long long nrows = 2LL * d.s * (bh - 1) + max_oh + 1;
-        const long long lw_in = 2LL * d.s * (bw - 1) + max_ow + 1;
-        const long long lwp = ((lw_in + f.nphase - 1) / f.nphase) | 1;
-        const long long x_bytes = (long long)d.C * nrows * f.nphase * lwp * (long long)sizeof(float);
-        if (x_bytes + (long long)table_bytes > (long long)budget) continue;
-        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && (size_t)x_bytes < best_x)) {
-            best_eff = eff; best_x = (size_t)x_bytes;
-            f.BH = bh; f.BW = bw; f.nbh = nbh; f.nbw = nbw;
-            f.nrows = (int)nrows; f.lw_in = (int)lw_in; f.lwp = (int)lwp;
-        }
-    }
-    if (best_eff < 0.5) return false;
-    const long long blocks = (long long)d.N * f.nbh * f.nbw;
-    if (blocks > 0x7fffffffLL) return false;
-    f.row_floats = f.nphase * f.lwp;
-    f.chan_floats = f.nrows * f.row_floats;
-    f.tile_row_step = 2 * d.s * f.row_floats;
-    f.nslices = (d.K + 31) / 32;
-    // with few blocks the filter slices are spread over workgroups as well
-    f.slices_per_wg = blocks >= 2 * kNumCUs ? f.nslices : 1;
-    f.nkw = (f.nslices + f.slices_per_wg - 1) / f.slices_per_wg;
-    if (f.nkw > 65535) return false;
-    f.div_bw.init((unsigned)f.BW);
-    f.div_nphase.init((unsigned)f.nphase);
-    for (int i = 0; i < kMaxPieces; ++i)
-        for (int k = 0; k < 4; ++k) {
-            // offsets past a piece's own patch (k > its length) repeat its last element: they are read
-            // (the patch is always read 4 wide) and only ever multiplied by zeros, but must be finite
-            const int kh = i < d.nh ? std::min(k, d.ph[i].l) : 0, kw = i < d.nw ? std::min(k, d.pw[i].l) : 0;
-            const int oh = i < d.nh ? d.s * (d.ph[i].j + kh) + d.ph[i].p : 0;
-            const int ow = i < d.nw ? d.s * (d.pw[i].j + kw) + d.pw[i].p : 0;
-            f.roff[i][k] = oh * f.row_floats;
-            f.coff[i][k] = (ow % f.nphase) * f.lwp + ow / f.nphase;
-        }
-    f.lds_bytes = table_bytes + best_x;
-    *out = f;
-    return true;
+    }  // blocks of this workgroup
 }
 
 dwm_status_t launch_fused_filter(const dwm_plan& p, const float* w, float* U, void* stream)
@@ -529,19 +540,26 @@ dwm_status_t launch_fused_forward(const dwm_plan& p, const float* x, const float
 {
     if (!p.fused_ok) return DWM_ERR_INVALID_ARG;
     const FusedArgs& f = p.fused;
-    auto kernel = f.nfc > 1 ? fused_forward_kernel<true> : fused_forward_kernel<false>;
+    auto kernel = f.nfc > 1 ? fused_forward_kernel<true, false>
+                            : f.wide ? fused_forward_kernel<false, true> : fused_forward_kernel<false, false>;
     if (f.lds_bytes > 64 * 1024) {
         // once for each instantiation, whichever of them the first plan happens to use
         static const hipError_t attr = [] {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<true>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<true, false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return e;
-            return hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<false>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<false, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(fused_forward_kernel<false, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         }();
         if (attr != hipSuccess) return DWM_ERR_HIP;
     }
-    dim3 grid((unsigned)(p.d.N * f.nbh * f.nbw), (unsigned)f.nkw), block(256);
+    // persistent workgroups, two per CU (fewer where there are fewer blocks)
+    const long long nblocks = (long long)p.d.N * f.nbh * f.nbw;
+    const long long per_k = std::max<long long>(1, 2 * kNumCUs / f.nkw);
+    dim3 grid((unsigned)std::min(nblocks, per_k), (unsigned)f.nkw), block(256);
     hipLaunchKernelGGL(kernel, grid, block, f.lds_bytes, (hipStream_t)stream, p.d, f, x, U, y);
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }

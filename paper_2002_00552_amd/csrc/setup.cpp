@@ -1,0 +1,210 @@
+// Host-side geometry of two kernels of libdwm: which block of tiles a workgroup of the
+// single-kernel forward path owns and how its input region is staged in LDS (fused.hip), and how
+// the LDS-staged input transform stages its rows (transforms.hip).  Pure integer logic, no GPU
+// call: this file and plan.cpp also build with a plain host compiler (sanitizer builds).
+#include <algorithm>
+
+#include "plan.hpp"
+
+namespace dwm {
+
+// ---------------------------------------------------------------------------------
+// Single-kernel forward path: does it apply, and with which block of tiles
+// ---------------------------------------------------------------------------------
+bool fused_setup(const dwm_plan& p, FusedArgs* out)
+{
+    const DevPlan& d = p.d;
+    FusedArgs f{};
+    if (d.C > 127 || d.nh > 15 || d.nw > 15) return false;
+    // classes = pairs of families; inside a class the rows (part, channel) follow each other sorted by
+    // (len_h, len_w), longest first, and only the class's end is padded to a multiple of four.  A step
+    // whose four rows mix piece lengths runs the planes of the longest: the shorter pieces' rows hold
+    // zeros in the filter copy for the frequencies they lack.
+    int rows = 0, steps = 0;
+    int row_lh[kFusedMaxRows], row_lw[kFusedMaxRows];
+    for (int wh = 1; wh >= 0; --wh)
+        for (int ww = 1; ww >= 0; --ww) {
+            FusedClass fc{};
+            fc.wide_h = wh; fc.wide_w = ww;
+            fc.nfh = wh ? 4 : 2; fc.nfw = ww ? 4 : 2;
+            fc.step0 = steps; fc.row0 = rows;
+            for (int lh = 3; lh >= 1; --lh)
+                for (int lw = 3; lw >= 1; --lw) {
+                    if ((lh >= 2) != (wh == 1) || (lw >= 2) != (ww == 1)) continue;
+                    for (int a = 0; a < d.nh; ++a)
+                        for (int b = 0; b < d.nw; ++b) {
+                            if (d.ph[a].l != lh || d.pw[b].l != lw) continue;
+                            for (int c = 0; c < d.C; ++c) {
+                                if (rows >= kFusedMaxRows) return false;
+                                f.rowdesc[rows] = (unsigned short)(a | b << 4 | c << 8 | 1 << 15);
+                                row_lh[rows] = lh; row_lw[rows] = lw;
+                                ++rows;
+                            }
+                        }
+                }
+            if (rows == fc.row0) continue;
+            while ((rows - fc.row0) & 3) {  // padding rows: a real row's offsets, zero filter rows
+                if (rows >= kFusedMaxRows) return false;
+                f.rowdesc[rows] = (unsigned short)(f.rowdesc[rows - 1] & 0x7fff);
+                row_lh[rows] = row_lh[rows - 1]; row_lw[rows] = row_lw[rows - 1];
+                ++rows;
+            }
+            for (int r0 = fc.row0; r0 < rows; r0 += 4) {
+                if (steps >= kFusedMaxSteps) return false;
+                int mh = 0, mw = 0;
+                for (int r = r0; r < r0 + 4; ++r) { mh = std::max(mh, row_lh[r]); mw = std::max(mw, row_lw[r]); }
+                f.step_type[steps++] = mh * 4 + mw;
+            }
+            fc.nsteps = steps - fc.step0;
+            fc.rows = rows - fc.row0;
+            f.fc[f.nfc++] = fc;
+        }
+    f.rows_total = rows;
+
+    // One class of two- and three-tap pieces only: the pipelined kernel applies.  It reads a patch row
+    // as two pairs of adjacent LDS words (columns 0,2 and 1,3 of the patch lie 2*stride input columns
+    // apart, i.e. one word apart in the de-interleaved row), also for two-tap pieces, whose fourth
+    // column is then the input's real next element (it only meets zeros of the filter copy): the
+    // staged region is as wide as if every piece had three taps.
+    f.wide = f.nfc == 1 && f.fc[0].wide_h && f.fc[0].wide_w;
+    int max_oh = 0, max_ow = 0;
+    for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
+    for (int i = 0; i < d.nw; ++i) max_ow = std::max(max_ow, d.s * (d.pw[i].j + (f.wide ? 3 : d.pw[i].l)) + d.pw[i].p);
+    f.nphase = 2 * d.s;
+    const size_t table_bytes = (size_t)rows * 64;
+    const size_t budget = 72 * 1024;  // two workgroups per CU
+
+    // block of tiles: most useful lanes first, then the smallest staged region
+    double best_eff = 0.0;
+    size_t best_x = 0;
+    for (int bw = 1; bw <= 64 && bw <= d.TW; ++bw) {
+        int bh = 64 / bw;
+        if (bh > d.TH) bh = d.TH;
+        if (bh < 1) continue;
+        const int nbh = (d.TH + bh - 1) / bh, nbw = (d.TW + bw - 1) / bw;
+        const double eff = (double)d.TH * d.TW / ((double)nbh * nbw * 64);
+        const long long nrows = 2LL * d.s * (bh - 1) + max_oh + 1;
+        const long long lw_in = 2LL * d.s * (bw - 1) + max_ow + 1;
+        const long long lwp = ((lw_in + f.nphase - 1) / f.nphase) | 1;
+        const long long x_bytes = (long long)d.C * nrows * f.nphase * lwp * (long long)sizeof(float);
+        if (x_bytes + (long long)table_bytes > (long long)budget) continue;
+        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && (size_t)x_bytes < best_x)) {
+            best_eff = eff; best_x = (size_t)x_bytes;
+            f.BH = bh; f.BW = bw; f.nbh = nbh; f.nbw = nbw;
+            f.nrows = (int)nrows; f.lw_in = (int)lw_in; f.lwp = (int)lwp;
+        }
+    }
+    if (best_eff < 0.5) return false;
+    const long long blocks = (long long)d.N * f.nbh * f.nbw;
+    if (blocks > 0x7fffffffLL) return false;
+    f.row_floats = f.nphase * f.lwp;
+    f.chan_floats = f.nrows * f.row_floats;
+    f.tile_row_step = 2 * d.s * f.row_floats;
+    f.nslices = (d.K + 31) / 32;
+    // with few blocks the filter slices are spread over workgroups as well
+    f.slices_per_wg = blocks >= 2 * kNumCUs ? f.nslices : 1;
+    f.nkw = (f.nslices + f.slices_per_wg - 1) / f.slices_per_wg;
+    if (f.nkw > 65535) return false;
+    // The pipelined kernel: units (block, slice of 32 filters), block major, dealt in contiguous ranges
+    // to persistent workgroups, two per CU.  A second input buffer -- the next block's input is staged
+    // while this one is multiplied -- where two workgroups with two buffers each fit in a CU's 160 KB
+    // and a staged row is at most 64 columns (one load per lane and row).
+    const long long units = blocks * f.nslices;
+    if (units > 0x7fffffffLL) f.wide = 0;
+    f.n_units = (int)std::min<long long>(units, 0x7fffffffLL);
+    f.n_wg = (int)std::min<long long>(units, 2 * kNumCUs);
+    f.x_floats = d.C * f.nrows * f.row_floats;
+    f.nbuf = (table_bytes / 2 + 2 * best_x <= 78 * 1024 && f.lw_in <= 64) ? 2 : 1;
+    f.stage_items = (d.C * f.nrows + 3) / 4;
+    {
+        // rows a wave loads per step so that a block's worth is in LDS three steps before the block ends
+        const int steps_per_block = f.nslices * f.fc[0].nsteps;
+        const int room = steps_per_block - 4;
+        f.stage_per_step = room > 0 ? (f.stage_items + room - 1) / room : 0;
+        if (room <= 0 || f.stage_per_step > 4) f.nbuf = 1;
+    }
+    f.lds_bytes_wide = table_bytes / 2 + (size_t)f.nbuf * best_x;
+    f.div_bw.init((unsigned)f.BW);
+    f.div_nphase.init((unsigned)f.nphase);
+    f.div_nrows.init((unsigned)f.nrows);
+    for (int i = 0; i < kMaxPieces; ++i)
+        for (int k = 0; k < 4; ++k) {
+            // offsets past a piece's own patch (k > its length) repeat its last element: they are read
+            // (the patch is always read 4 wide) and only ever multiplied by zeros, but must be finite
+            // (the pipelined kernel reads the real fourth column instead: see above)
+            const int kh = i < d.nh ? std::min(k, d.ph[i].l) : 0, kw = i < d.nw ? (f.wide ? k : std::min(k, d.pw[i].l)) : 0;
+            const int oh = i < d.nh ? d.s * (d.ph[i].j + kh) + d.ph[i].p : 0;
+            const int ow = i < d.nw ? d.s * (d.pw[i].j + kw) + d.pw[i].p : 0;
+            f.roff[i][k] = oh * f.row_floats;
+            f.coff[i][k] = (ow % f.nphase) * f.lwp + ow / f.nphase;
+        }
+    for (int i = 0; i < d.nw; ++i)  // columns two apart are one word apart in a de-interleaved row
+        if (f.wide && (f.coff[i][2] != f.coff[i][0] + 1 || f.coff[i][3] != f.coff[i][1] + 1)) return false;
+    f.lds_bytes = table_bytes + best_x;
+    *out = f;
+    return true;
+}
+
+
+// Does the LDS-staged form apply, and with how many channels per workgroup: the rows a block
+// stages must fit in LDS.  The row count depends on where a block of 64 tiles starts; the
+// pattern repeats after at most TH*TW blocks, so the maximum is found by walking them.
+bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish)
+{
+    const DevPlan& d = p.d;
+    InLdsArgs a{};
+    int max_oh = 0, max_ow = 0;
+    for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
+    for (int i = 0; i < d.nw; ++i) max_ow = std::max(max_ow, d.s * (d.pw[i].j + d.pw[i].l) + d.pw[i].p);
+    if (d.s > 4096 || max_oh > (1 << 20) || max_ow > (1 << 20)) return false;
+    a.nphase = 2 * d.s;
+    a.foot_h = max_oh + 1;
+    const long long lw_in = 2LL * d.s * (d.TW - 1) + max_ow + 1;
+    const long long rows_full = 2LL * d.s * (d.TH - 1) + a.foot_h;
+    if (lw_in > (1 << 16) || rows_full > (1 << 24)) return false;
+    a.lw_in = (int)lw_in;
+    a.lwp = ((a.lw_in + a.nphase - 1) / a.nphase) | 1;
+    a.row_floats = a.nphase * a.lwp;
+    a.rows_full = (int)rows_full;
+    const long long per = (long long)d.TH * d.TW;
+    const long long nb = (d.T + 63) / 64, scan = std::min(nb, per);
+    long long max_rows = 0;
+    const int s2 = 2 * d.s;
+    for (long long bt = 0; bt < scan; ++bt) {
+        const long long t0 = bt * 64, t1 = std::min<long long>(t0 + 63, d.T - 1);
+        const long long g0 = t0 / d.TW, g1 = t1 / d.TW, n0 = g0 / d.TH, n1 = g1 / d.TH;
+        const long long ty_a0 = g0 - n0 * d.TH, ty_b1 = g1 - n1 * d.TH;
+        const long long rows0 = s2 * ((n1 == n0 ? ty_b1 : d.TH - 1) - ty_a0) + a.foot_h;
+        const long long total = n1 == n0 ? rows0 : rows0 + (n1 - n0 - 1) * rows_full + s2 * ty_b1 + a.foot_h;
+        max_rows = std::max(max_rows, total);
+        if (max_rows * a.row_floats * 4 > 64 * 1024) return false;
+    }
+    a.max_rows = (int)max_rows;
+    a.chan_floats = a.max_rows * a.row_floats;
+    const size_t chan_bytes = (size_t)a.chan_floats * sizeof(float);
+    if (chan_bytes > 64 * 1024) return false;
+    // channels per workgroup: one per wave (measured best: many small workgroups keep more loads
+    // and stores in flight than fewer large ones)
+    int cg = d.C < 4 ? d.C : 4;
+    if (cg_wish > 0 && cg_wish <= d.C && cg_wish * chan_bytes <= 150 * 1024) cg = cg_wish;
+    a.cg = cg;
+    a.ncg = (d.C + cg - 1) / cg;
+    if ((long long)a.ncg * (d.Tpad / 64) > 0x7fffffffLL) return false;
+    a.div_tw.init((unsigned)d.TW);
+    a.div_th.init((unsigned)d.TH);
+    a.div_lw.init((unsigned)a.lw_in);
+    a.div_nphase.init((unsigned)a.nphase);
+    a.div_rows_full.init((unsigned)a.rows_full);
+    for (int i = 0; i < kMaxPieces; ++i)
+        for (int k = 0; k < 4; ++k) {
+            const int oh = i < d.nh ? d.s * (d.ph[i].j + k) + d.ph[i].p : 0;
+            const int ow = i < d.nw ? d.s * (d.pw[i].j + k) + d.pw[i].p : 0;
+            a.roff[i][k] = oh * a.row_floats;
+            a.coff[i][k] = (ow % a.nphase) * a.lwp + ow / a.nphase;
+        }
+    a.lds_bytes = (size_t)cg * chan_bytes;
+    *out = a;
+    return true;
+}
+
+}  // namespace dwm

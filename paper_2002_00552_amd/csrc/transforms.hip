@@ -5,8 +5,6 @@
 // two-multiplication forms for 2-tap and 1-tap pieces.
 #include <hip/hip_runtime.h>
 
-#include <algorithm>
-
 #include "plan.hpp"
 #include "xform.hpp"
 
@@ -312,67 +310,6 @@ dwm_status_t launch_filter_transform(const dwm_plan& p, const float* w, float* U
     dim3 grid((p.d.rows_total + 255) / 256, p.d.Kpad), block(256);
     hipLaunchKernelGGL(filter_transform_kernel, grid, block, 0, (hipStream_t)stream, p.d, w, U);
     return check_launch();
-}
-
-// Does the LDS-staged form apply, and with how many channels per workgroup: the rows a block
-// stages must fit in LDS.  The row count depends on where a block of 64 tiles starts; the
-// pattern repeats after at most TH*TW blocks, so the maximum is found by walking them.
-bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish)
-{
-    const DevPlan& d = p.d;
-    InLdsArgs a{};
-    int max_oh = 0, max_ow = 0;
-    for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
-    for (int i = 0; i < d.nw; ++i) max_ow = std::max(max_ow, d.s * (d.pw[i].j + d.pw[i].l) + d.pw[i].p);
-    if (d.s > 4096 || max_oh > (1 << 20) || max_ow > (1 << 20)) return false;
-    a.nphase = 2 * d.s;
-    a.foot_h = max_oh + 1;
-    const long long lw_in = 2LL * d.s * (d.TW - 1) + max_ow + 1;
-    const long long rows_full = 2LL * d.s * (d.TH - 1) + a.foot_h;
-    if (lw_in > (1 << 16) || rows_full > (1 << 24)) return false;
-    a.lw_in = (int)lw_in;
-    a.lwp = ((a.lw_in + a.nphase - 1) / a.nphase) | 1;
-    a.row_floats = a.nphase * a.lwp;
-    a.rows_full = (int)rows_full;
-    const long long per = (long long)d.TH * d.TW;
-    const long long nb = (d.T + 63) / 64, scan = std::min(nb, per);
-    long long max_rows = 0;
-    const int s2 = 2 * d.s;
-    for (long long bt = 0; bt < scan; ++bt) {
-        const long long t0 = bt * 64, t1 = std::min<long long>(t0 + 63, d.T - 1);
-        const long long g0 = t0 / d.TW, g1 = t1 / d.TW, n0 = g0 / d.TH, n1 = g1 / d.TH;
-        const long long ty_a0 = g0 - n0 * d.TH, ty_b1 = g1 - n1 * d.TH;
-        const long long rows0 = s2 * ((n1 == n0 ? ty_b1 : d.TH - 1) - ty_a0) + a.foot_h;
-        const long long total = n1 == n0 ? rows0 : rows0 + (n1 - n0 - 1) * rows_full + s2 * ty_b1 + a.foot_h;
-        max_rows = std::max(max_rows, total);
-        if (max_rows * a.row_floats * 4 > 64 * 1024) return false;
-    }
-    a.max_rows = (int)max_rows;
-    a.chan_floats = a.max_rows * a.row_floats;
-    const size_t chan_bytes = (size_t)a.chan_floats * sizeof(float);
-    if (chan_bytes > 64 * 1024) return false;
-    // channels per workgroup: one per wave (measured best: many small workgroups keep more loads
-    // and stores in flight than fewer large ones)
-    int cg = d.C < 4 ? d.C : 4;
-    if (cg_wish > 0 && cg_wish <= d.C && cg_wish * chan_bytes <= 150 * 1024) cg = cg_wish;
-    a.cg = cg;
-    a.ncg = (d.C + cg - 1) / cg;
-    if ((long long)a.ncg * (d.Tpad / 64) > 0x7fffffffLL) return false;
-    a.div_tw.init((unsigned)d.TW);
-    a.div_th.init((unsigned)d.TH);
-    a.div_lw.init((unsigned)a.lw_in);
-    a.div_nphase.init((unsigned)a.nphase);
-    a.div_rows_full.init((unsigned)a.rows_full);
-    for (int i = 0; i < kMaxPieces; ++i)
-        for (int k = 0; k < 4; ++k) {
-            const int oh = i < d.nh ? d.s * (d.ph[i].j + k) + d.ph[i].p : 0;
-            const int ow = i < d.nw ? d.s * (d.pw[i].j + k) + d.pw[i].p : 0;
-            a.roff[i][k] = oh * a.row_floats;
-            a.coff[i][k] = (ow % a.nphase) * a.lwp + ow / a.nphase;
-        }
-    a.lds_bytes = (size_t)cg * chan_bytes;
-    *out = a;
-    return true;
 }
 
 dwm_status_t launch_input_transform(const dwm_plan& p, const float* x, float* V, void* stream)
