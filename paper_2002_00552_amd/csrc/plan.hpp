@@ -180,15 +180,11 @@ struct FusedArgs {
     int tile_row_step;              // LDS floats between vertically adjacent tiles' patches
     int nslices;                    // ceil(K / 32)
     int slices_per_wg, nkw;         // K slices per workgroup, workgroups along K
-    // the pipelined kernel for layers whose parts all have two or three taps per dimension (one class):
-    int wide;                       // 1: it applies
-    int n_units, n_wg;              // units (block, slice) in block-major order; persistent workgroups
-    int x_floats, nbuf;             // floats of one staged input buffer; buffers in LDS (1 or 2)
-    int stage_items, stage_per_step;  // staged rows (channel, row) per wave and block; rows a wave loads per step
-    size_t lds_bytes_wide;
+    int wide;                       // 1: one class of two- and three-tap pieces only: patch rows are read as
+                                    // pairs of adjacent words and operands are carried from slice to slice
     int nfc, rows_total;
     FusedClass fc[4];
-    FastDiv div_bw, div_nphase, div_nrows;
+    FastDiv div_bw, div_nphase;
     int roff[kMaxPieces][4], coff[kMaxPieces][4];  // LDS offset of patch row a / column b of a piece
     int step_type[kFusedMaxSteps];                    // len_h * 4 + len_w of the step's four rows
     unsigned short rowdesc[kFusedMaxRows];            // h piece | w piece << 4 | channel << 8 | real row << 15

@@ -61,7 +61,7 @@ bool fused_setup(const dwm_plan& p, FusedArgs* out)
         }
     f.rows_total = rows;
 
-    // One class of two- and three-tap pieces only: the pipelined kernel applies.  It reads a patch row
+    // One class of two- and three-tap pieces only: the kernel then reads a patch row
     // as two pairs of adjacent LDS words (columns 0,2 and 1,3 of the patch lie 2*stride input columns
     // apart, i.e. one word apart in the de-interleaved row), also for two-tap pieces, whose fourth
     // column is then the input's real next element (it only meets zeros of the filter copy): the
@@ -105,33 +105,13 @@ bool fused_setup(const dwm_plan& p, FusedArgs* out)
     f.slices_per_wg = blocks >= 2 * kNumCUs ? f.nslices : 1;
     f.nkw = (f.nslices + f.slices_per_wg - 1) / f.slices_per_wg;
     if (f.nkw > 65535) return false;
-    // The pipelined kernel: units (block, slice of 32 filters), block major, dealt in contiguous ranges
-    // to persistent workgroups, two per CU.  A second input buffer -- the next block's input is staged
-    // while this one is multiplied -- where two workgroups with two buffers each fit in a CU's 160 KB
-    // and a staged row is at most 64 columns (one load per lane and row).
-    const long long units = blocks * f.nslices;
-    if (units > 0x7fffffffLL) f.wide = 0;
-    f.n_units = (int)std::min<long long>(units, 0x7fffffffLL);
-    f.n_wg = (int)std::min<long long>(units, 2 * kNumCUs);
-    f.x_floats = d.C * f.nrows * f.row_floats;
-    f.nbuf = (table_bytes / 2 + 2 * best_x <= 78 * 1024 && f.lw_in <= 64) ? 2 : 1;
-    f.stage_items = (d.C * f.nrows + 3) / 4;
-    {
-        // rows a wave loads per step so that a block's worth is in LDS three steps before the block ends
-        const int steps_per_block = f.nslices * f.fc[0].nsteps;
-        const int room = steps_per_block - 4;
-        f.stage_per_step = room > 0 ? (f.stage_items + room - 1) / room : 0;
-        if (room <= 0 || f.stage_per_step > 4) f.nbuf = 1;
-    }
-    f.lds_bytes_wide = table_bytes / 2 + (size_t)f.nbuf * best_x;
     f.div_bw.init((unsigned)f.BW);
     f.div_nphase.init((unsigned)f.nphase);
-    f.div_nrows.init((unsigned)f.nrows);
     for (int i = 0; i < kMaxPieces; ++i)
         for (int k = 0; k < 4; ++k) {
             // offsets past a piece's own patch (k > its length) repeat its last element: they are read
             // (the patch is always read 4 wide) and only ever multiplied by zeros, but must be finite
-            // (the pipelined kernel reads the real fourth column instead: see above)
+            // (with a single class of two- and three-tap pieces the real fourth column is read instead: see above)
             const int kh = i < d.nh ? std::min(k, d.ph[i].l) : 0, kw = i < d.nw ? (f.wide ? k : std::min(k, d.pw[i].l)) : 0;
             const int oh = i < d.nh ? d.s * (d.ph[i].j + kh) + d.ph[i].p : 0;
             const int ow = i < d.nw ? d.s * (d.pw[i].j + kw) + d.pw[i].p : 0;

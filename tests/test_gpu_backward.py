@@ -126,29 +126,20 @@ def test_backward_data_phases_cover_the_image_once():
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
 def test_backward_data_benchmark_layers_full_size(index):
-    """Whole layer on the GPU; the oracle computes 20 000 sampled pixels of dx one by one plus the
-    image border, where the padding and the ragged ends of every phase live."""
+    """Whole layer on the GPU, EVERY pixel of dx compared with the FP64 definition."""
     L = wl.CONFIGS[index]
     _, w = wl.make_layer_tensors(L, index)
     OH, OW = wl.out_hw(L)
     dy = np.random.default_rng(3100 + index).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
+    print("data gradient, whole image:", L.name, flush=True)
     r = BwdRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     dx = r.run(dy, w)
     r.close()
     assert dx.shape == (L.N, L.C, L.H, L.W) and np.all(np.isfinite(dx))
-    rng = np.random.default_rng(5200 + index)
-    if dx.size <= 100000:
-        idx = np.arange(dx.size)
-    else:
-        idx = rng.choice(dx.size, 20000, replace=False)
-        n, c = L.N - 1, L.C - 1
-        edge = [((n * L.C + c) * L.H + L.H - 1) * L.W + j for j in range(L.W)]
-        edge += [((n * L.C + c) * L.H + i) * L.W + L.W - 1 for i in range(L.H)]
-        edge += list(range(L.W))
-        idx = np.unique(np.concatenate([idx, np.array(edge)]))
-    ref = oracle.backward_data_f64_at(dy, w, (L.N, L.C, L.H, L.W), L.stride, L.pad, idx)
-    got = dx.ravel()[idx].astype(np.float64)
-    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= TOL, L.name
+    ref = oracle.backward_data_f64(dy, w, (L.N, L.C, L.H, L.W), L.stride, L.pad)
+    err = np.abs(dx - ref)
+    worst = np.unravel_index(np.argmax(err), err.shape)
+    assert err[worst] / np.max(np.abs(ref)) <= TOL, (L.name, worst)
 
 
 # ---- gradient with respect to the filter ----
@@ -223,18 +214,17 @@ def test_backward_filter_is_deterministic_and_plan_reusable():
 
 @pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
 def test_backward_filter_benchmark_layers_full_size(index):
-    """Whole layer on the GPU.  The oracle's definition costs the layer's full flop count, so it
-    computes the filter gradient of a handful of filters only (dw of filter k needs dy[:, k] alone),
-    the first and the last among them."""
+    """Whole layer on the GPU, EVERY tap of every filter compared with the FP64 definition."""
     L = wl.CONFIGS[index]
     x, _ = wl.make_layer_tensors(L, index)
     OH, OW = wl.out_hw(L)
     dy = np.random.default_rng(4100 + index).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
+    print("filter gradient, all filters:", L.name, flush=True)
     r = WgradRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     dw = r.run(x, dy)
     r.close()
     assert dw.shape == (L.K, L.C, L.R, L.S) and np.all(np.isfinite(dw))
-    ks = sorted({0, L.K - 1, L.K // 2})[: (3 if index != 2 else 2)]
-    ref = oracle.backward_filter_f64(x, np.ascontiguousarray(dy[:, ks]), (len(ks), L.C, L.R, L.S), L.stride, L.pad)
-    got = dw[ks].astype(np.float64)
-    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= TOL, L.name
+    ref = oracle.backward_filter_f64(x, dy, (L.K, L.C, L.R, L.S), L.stride, L.pad)
+    err = np.abs(dw - ref)
+    worst = np.unravel_index(np.argmax(err), err.shape)
+    assert err[worst] / np.max(np.abs(ref)) <= TOL, (L.name, worst)
