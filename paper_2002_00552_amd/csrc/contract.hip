@@ -361,12 +361,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
                                                                mine + (unsigned)(((blk * 4 + q) * 4 + e4) * NT * 16),
                                                                kDeviceScope);
                     }
-            // waiting for the device-scope stores -- not a flush of the whole L2 -- is all the
-            // release that the arrival count below needs
+            // Release without a flush of the whole L2.  The partial sums were written with device
+            // scope (sc1: the store is complete, i.e. counted off vmcnt, once it has reached the level
+            // all XCDs share -- it is what a relaxed device-scope atomic store compiles to); every
+            // wave waits for its own stores, the barrier collects the workgroup, and only then one
+            // lane bumps the tile's arrival counter with a device-scope atomic.  Atomics on one
+            // address are totally ordered, so whoever reads "all others have arrived" does so after
+            // every other contributor's stores completed, and its own device-scope loads (below;
+            // they do not hit in the local L2) then find them.  The workgroup-scope fences only
+            // keep the compiler from moving the accesses across the barriers.
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             wait_vmcnt<0>();
             __syncthreads();
-            if (tid == 0) s_last = atomicAdd(&counters[trel], 1) == nc - 1;
+            if (tid == 0)
+                s_last = __hip_atomic_fetch_add(&counters[trel], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nc - 1;
             __syncthreads();
             store = s_last != 0;
             __syncthreads();  // s_last may be rewritten for the next segment

@@ -759,11 +759,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract16_ke
                                                                kDeviceScope);
                     }
             // waiting for the device-scope stores -- not a flush of the whole L2 -- is all the
-            // release that the arrival count below needs
+            // release that the device-scope arrival count below needs (the argument is spelled out at
+            // the same place of the single-precision contraction)
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             wait_vmcnt<0>();
             __syncthreads();
-            if (tid == 0) s_last = atomicAdd(&counters[trel], 1) == nc - 1;
+            if (tid == 0)
+                s_last = __hip_atomic_fetch_add(&counters[trel], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nc - 1;
             __syncthreads();
             store = s_last != 0;
             __syncthreads();  // s_last may be rewritten for the next segment

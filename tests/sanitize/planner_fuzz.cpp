@@ -1,0 +1,165 @@
+// Host-only fuzz of the planner behind the C ABI, built with -fsanitize=address,undefined by
+// tests/test_sanitize.py: plans are created for random and for extreme shapes, every introspection
+// call is walked, variants are switched, and the decomposition's invariants are checked.  The
+// kernel launchers are stubbed: nothing here touches a GPU.
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "../../paper_2002_00552_amd/csrc/plan.hpp"
+
+namespace dwm {
+dwm_status_t launch_filter_transform(const dwm_plan&, const float*, float*, void*) { return DWM_OK; }
+dwm_status_t launch_input_transform(const dwm_plan&, const float*, float*, void*) { return DWM_OK; }
+dwm_status_t launch_contract_output(const dwm_plan&, const float*, float*, float*, void*) { return DWM_OK; }
+dwm_status_t launch_fused_filter(const dwm_plan&, const float*, float*, void*) { return DWM_OK; }
+dwm_status_t launch_fused_forward(const dwm_plan&, const float*, const float*, float*, void*) { return DWM_OK; }
+}  // namespace dwm
+
+static uint64_t g_state = 0x9E3779B97F4A7C15ull;
+static uint32_t rnd()
+{
+    g_state ^= g_state << 13;
+    g_state ^= g_state >> 7;
+    g_state ^= g_state << 17;
+    return (uint32_t)(g_state >> 32);
+}
+static int pick(int lo, int hi) { return lo + (int)(rnd() % (uint32_t)(hi - lo + 1)); }
+
+#define CHECK(c)                                                              \
+    do {                                                                      \
+        if (!(c)) {                                                           \
+            std::fprintf(stderr, "%s:%d: check failed: %s\n", __FILE__, __LINE__, #c); \
+            std::exit(2);                                                     \
+        }                                                                     \
+    } while (0)
+
+static int walk(int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    dwm_plan_t* p = nullptr;
+    const dwm_status_t st = dwm_plan_create(&p, N, C, H, W, K, R, S, s, P);
+    if (st != DWM_OK) {
+        CHECK(p == nullptr);
+        CHECK(st == DWM_ERR_INVALID_ARG || st == DWM_ERR_UNSUPPORTED);
+        return 0;
+    }
+    dwm_plan_info_t in;
+    CHECK(dwm_plan_info(p, &in) == DWM_OK);
+    CHECK(in.OH == (H + 2 * P - R) / s + 1 && in.OW == (W + 2 * P - S) / s + 1);
+    CHECK(in.T == (long long)N * in.TH * in.TW);
+    // every tap belongs to exactly one part; the multiplication count is the sum over the parts
+    std::vector<int> seen((size_t)R * S, 0);
+    long long mults = 0;
+    for (int i = 0; i < in.n_parts; ++i) {
+        dwm_part_t pt;
+        CHECK(dwm_plan_part(p, i, &pt) == DWM_OK);
+        CHECK(pt.len_h >= 1 && pt.len_h <= 3 && pt.len_w >= 1 && pt.len_w <= 3);
+        CHECK(pt.cls >= 0 && pt.cls < in.n_classes);
+        mults += (pt.len_h + 1) * (pt.len_w + 1);
+        for (int a = 0; a < pt.len_h; ++a)
+            for (int b = 0; b < pt.len_w; ++b) {
+                const int r = s * (pt.off_h + a) + pt.phase_h, q = s * (pt.off_w + b) + pt.phase_w;
+                CHECK(r >= 0 && r < R && q >= 0 && q < S);
+                ++seen[(size_t)r * S + q];
+            }
+    }
+    for (int v : seen) CHECK(v == 1);
+    CHECK(mults == in.mults_per_tile);
+    dwm_part_t bad;
+    CHECK(dwm_plan_part(p, in.n_parts, &bad) == DWM_ERR_INVALID_ARG);
+    CHECK(dwm_plan_part(p, -1, &bad) == DWM_ERR_INVALID_ARG);
+    int planes = 0;
+    for (int i = 0; i < in.n_classes; ++i) {
+        dwm_class_t c;
+        CHECK(dwm_plan_class(p, i, &c) == DWM_OK);
+        CHECK(c.L == c.n_parts * C && c.Lpad >= c.L && c.Lpad % 16 == 0);
+        planes += (c.len_h + 1) * (c.len_w + 1);
+    }
+    CHECK(planes == in.n_planes);
+    dwm_class_t cbad;
+    CHECK(dwm_plan_class(p, in.n_classes, &cbad) == DWM_ERR_INVALID_ARG);
+    int nfc, nrows, nslices;
+    CHECK(dwm_plan_fused_info(p, &nfc, &nrows, &nslices) == DWM_OK);
+    int rows_seen = 0;
+    for (int i = 0; i < nfc; ++i) {
+        dwm_fused_class_t fc;
+        CHECK(dwm_plan_fused_class(p, i, &fc) == DWM_OK);
+        CHECK(fc.first_row == rows_seen && fc.rows % 4 == 0);
+        rows_seen += fc.rows;
+    }
+    CHECK(rows_seen == nrows);
+    int real_rows = 0;
+    for (int r = 0; r < nrows; ++r) {
+        dwm_fused_row_t fr;
+        CHECK(dwm_plan_fused_row(p, r, &fr) == DWM_OK);
+        CHECK(fr.part >= 0 && fr.part < in.n_parts && fr.channel >= 0 && fr.channel < C);
+        real_rows += fr.real;
+    }
+    if (nfc) CHECK(real_rows == in.n_parts * C);
+    dwm_fused_row_t frbad;
+    CHECK(dwm_plan_fused_row(p, nrows, &frbad) == DWM_ERR_INVALID_ARG);
+    // variants: whatever is accepted must leave the sizes sane; nonsense is refused
+    static const char* stages[] = {"contract", "split", "input", "input_cg", "forward", "nonsense"};
+    for (const char* stage : stages)
+        for (int v = -2; v <= 20; ++v) {
+            const dwm_status_t sv = dwm_plan_set_variant(p, stage, v);
+            CHECK(sv == DWM_OK || sv == DWM_ERR_INVALID_ARG);
+            CHECK(dwm_plan_workspace_bytes(p) >= 256 || dwm_plan_workspace_bytes(p) % 4 == 0);
+        }
+    CHECK(dwm_plan_set_variant(p, "contract", -1) == DWM_OK);
+    CHECK(dwm_plan_set_variant(p, "split", 0) == DWM_OK);
+    CHECK(dwm_plan_set_variant(p, "forward", -1) == DWM_OK);
+    const size_t need = dwm_plan_workspace_bytes(p);
+    CHECK(dwm_plan_filter_bytes(p) >= (size_t)4 * in.mults_per_tile * (size_t)C * (size_t)K);
+    // the workspace: too small, misaligned, then a (never dereferenced) address that fits
+    void* fake = reinterpret_cast<void*>((uintptr_t)1 << 20);
+    if (need > 0) CHECK(dwm_plan_set_workspace(p, fake, need - 1) == DWM_ERR_WORKSPACE);
+    CHECK(dwm_plan_set_workspace(p, reinterpret_cast<void*>(((uintptr_t)1 << 20) + 4), need) == DWM_ERR_WORKSPACE);
+    CHECK(dwm_plan_set_workspace(p, nullptr, need) == DWM_ERR_WORKSPACE);
+    float dummy = 0.f;
+    CHECK(dwm_conv_forward(p, &dummy, &dummy, &dummy, nullptr) == DWM_ERR_WORKSPACE);
+    CHECK(dwm_plan_set_workspace(p, fake, need) == DWM_OK);
+    // once the workspace is set its layout is fixed
+    CHECK(dwm_plan_set_variant(p, "contract", 10) == DWM_ERR_WORKSPACE);
+    CHECK(dwm_plan_set_variant(p, "split", 1) == DWM_ERR_WORKSPACE);
+    CHECK(dwm_plan_set_variant(p, "input", 0) == DWM_OK);
+    CHECK(dwm_conv_forward(p, &dummy, &dummy, &dummy, nullptr) == DWM_OK);  // the stubs: no launch
+    CHECK(dwm_conv_forward(p, nullptr, &dummy, &dummy, nullptr) == DWM_ERR_INVALID_ARG);
+    CHECK(dwm_plan_destroy(p) == DWM_OK);
+    return 1;
+}
+
+int main(int argc, char** argv)
+{
+    const int iters = argc > 1 ? std::atoi(argv[1]) : 3000;
+    int ok = 0, tried = 0;
+    // the benchmark layers and corner shapes first
+    const int fixed[][9] = {
+        {1, 16, 32, 32, 16, 5, 5, 1, 2},   {32, 128, 56, 56, 256, 3, 3, 2, 1}, {32, 256, 28, 28, 256, 7, 7, 1, 3},
+        {64, 3, 224, 224, 64, 7, 7, 2, 3}, {128, 3, 227, 227, 96, 11, 11, 4, 0}, {1, 1, 1, 1, 1, 1, 1, 1, 0},
+        {1, 1, 48, 48, 1, 48, 48, 1, 0},   {1, 1, 49, 49, 1, 49, 49, 1, 0},      {1, 1, 7, 7, 1, 1, 1, 9, 0},
+        {1, 1, 3, 3, 1, 5, 5, 1, 0},       {0, 1, 3, 3, 1, 3, 3, 1, 0},          {1, 1, 3, 3, 1, 3, 3, 0, 0},
+        {1, 1, 3, 3, 1, 3, 3, 1, -1},      {1, 127, 64, 64, 1, 3, 3, 1, 1},      {1, 128, 64, 64, 1, 3, 3, 1, 1},
+        {1, 1, 1 << 20, 2, 1, 3, 1, 1, 1}, {1, 1, 2, (1 << 20) + 1, 1, 1, 3, 1, 1}, {4096, 1, 1024, 1024, 1, 3, 3, 1, 1},
+        {1, 2, 12, 6000, 3, 3, 3, 1, 1},   {1, 3, 300, 300, 8, 33, 3, 16, 5},    {2, 5, 40, 40, 33, 47, 47, 1, 23},
+    };
+    for (const auto& f : fixed) {
+        ++tried;
+        ok += walk(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
+    }
+    CHECK(dwm_plan_create(nullptr, 1, 1, 3, 3, 1, 3, 3, 1, 1) == DWM_ERR_INVALID_ARG);
+    CHECK(dwm_plan_destroy(nullptr) == DWM_ERR_INVALID_ARG);
+    CHECK(dwm_plan_filter_bytes(nullptr) == 0 && dwm_plan_workspace_bytes(nullptr) == 0);
+    for (int it = 0; it < iters; ++it) {
+        const int R = pick(1, 13), S = pick(1, 13), s = pick(1, 5), P = pick(0, 6);
+        const int big = rnd() % 8 == 0;
+        const int H = pick(1, big ? 400 : 40), W = pick(1, big ? 400 : 40);
+        const int C = pick(1, rnd() % 4 == 0 ? 300 : 20), K = pick(1, rnd() % 4 == 0 ? 300 : 40);
+        const int N = pick(1, big ? 3 : 70);
+        ++tried;
+        ok += walk(N, C, H, W, K, R, S, s, P);
+    }
+    std::printf("planner fuzz: %d shapes tried, %d planned\n", tried, ok);
+    return ok > tried / 2 ? 0 : 3;
+}
