@@ -153,6 +153,31 @@ def dwm_half_f64(x, w, stride, pad):
     return y
 
 
+def round_bfloat16(a):
+    """Each double rounded to the nearest bfloat16 value (ties to even), as float64."""
+    a = np.ascontiguousarray(a, np.float64)
+    out = np.empty_like(a)
+    _load().oracle_round_bfloat16(_dp(a), _dp(out), ctypes.c_longlong(a.size))
+    return out
+
+
+def dwm_bf16_f64(x, w, stride, pad):
+    """O2 with bfloat16 storage: x and w are float32 arrays holding bfloat16 values; U and V are
+    rounded to bfloat16 before the products; sums in FP64; the FP64 result is returned unrounded."""
+    x = _f32(np.asarray(x).astype(np.float32))
+    w = _f32(np.asarray(w).astype(np.float32))
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C == C2
+    y = np.empty((N, K, out_size(H, R, stride, pad), out_size(W, S, stride, pad)), np.float64)
+    rc = _load().oracle_dwm_bf16_f64(_fp(x), _fp(w), _dp(y), N, C, H, W, K, R, S, stride, pad)
+    if rc == 3:
+        raise ValueError("oracle_dwm_bf16_f64: x and w must hold bfloat16 values")
+    if rc:
+        raise ValueError("oracle_dwm_bf16_f64: bad shape (rc=%d)" % rc)
+    return y
+
+
 def _bwd(fn, dy, w, x_shape, stride, pad):
     dy, w = _f32(dy), _f32(w)
     N, C, H, W = x_shape

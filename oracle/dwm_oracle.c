@@ -27,6 +27,9 @@
  *                              unrounded.  The paper does not say where its FP16
  *                              implementation rounds; this reading is the one a matrix
  *                              unit with FP16 operands and a wide accumulator computes.
+ *   O2b oracle_dwm_bf16_f64    the same reading with bfloat16 storage (8 significant bits,
+ *                              binary32's exponent range): the other 16-bit format such
+ *                              matrix units take.
  *
  * and, for the gradient with respect to the input (the paper's backward pass, Sec. 3.1
  * eq. 5 and Sec. 4.2 eq. 16-17):
@@ -358,6 +361,31 @@ int oracle_round_binary16(const double* in, double* out, long long n)
     return 0;
 }
 
+/*
+ * The nearest bfloat16 value (ties to even): the format of the same reduced-precision setting
+ * on hardware whose matrix units take it -- 8 significant bits, the exponent range of binary32
+ * (-126..127), subnormals in steps of 2^-133, overflow to infinity from (2 - 2^-8) * 2^127 up
+ * (half a step past the largest finite value (2 - 2^-7) * 2^127).  Returned as a double.
+ */
+static double round_bfloat16(double v)
+{
+    if (v == 0.0 || v != v || isinf(v)) return v;
+    const double a = fabs(v);
+    if (a >= (2.0 - ldexp(1.0, -8)) * ldexp(1.0, 127)) return v > 0 ? INFINITY : -INFINITY;
+    int e;
+    (void)frexp(a, &e);            /* a lies in [2^(e-1), 2^e) */
+    int lsb = (e - 1) - 7;         /* weight of the last of 8 significant bits */
+    if (lsb < -133) lsb = -133;    /* subnormal range */
+    const double ulp = ldexp(1.0, lsb);
+    return copysign(nearbyint(a / ulp) * ulp, v); /* default rounding mode: ties to even */
+}
+
+int oracle_round_bfloat16(const double* in, double* out, long long n)
+{
+    for (long long i = 0; i < n; ++i) out[i] = round_bfloat16(in[i]);
+    return 0;
+}
+
 static int dwm_forward(const float* x, const float* w, double* y,
                        int N, int C, int H, int W, int K, int R, int S, int s, int P, int half_storage)
 {
@@ -384,13 +412,15 @@ static int dwm_forward(const float* x, const float* w, double* y,
         /* Transformation (kernel side): U = G g G^T. */
         rc = oracle_part_filter_transform(w, K, C, R, S, s, pt, U);
         if (half_storage && !rc)
-            for (size_t i = 0; i < (size_t)K * C * th * tw; ++i) U[i] = round_binary16(U[i]);
+            for (size_t i = 0; i < (size_t)K * C * th * tw; ++i)
+                U[i] = half_storage == 2 ? round_bfloat16(U[i]) : round_binary16(U[i]);
         for (int n = 0; n < N && !rc; ++n) {
             /* Splitting (input side) + Transformation: V = B^T d B. */
             rc = oracle_part_input_transform(x, C, H, W, s, P, TH, TW, n, pt, V);
             if (rc) break;
             if (half_storage)
-                for (size_t i = 0; i < (size_t)C * TH * TW * th * tw; ++i) V[i] = round_binary16(V[i]);
+                for (size_t i = 0; i < (size_t)C * TH * TW * th * tw; ++i)
+                    V[i] = half_storage == 2 ? round_bfloat16(V[i]) : round_binary16(V[i]);
 #pragma omp parallel for schedule(static)
             for (int k = 0; k < K; ++k)
                 for (int ty = 0; ty < TH; ++ty)
@@ -444,6 +474,19 @@ int oracle_dwm_half_f64(const float* x, const float* w, double* y,
     for (size_t i = 0; i < (size_t)K * C * R * S; ++i)
         if (round_binary16((double)w[i]) != (double)w[i]) return 3;
     return dwm_forward(x, w, y, N, C, H, W, K, R, S, s, P, 1);
+}
+
+/* O2b: the same with bfloat16 storage -- x and w must hold bfloat16 values (checked); U and V are
+ * rounded once to bfloat16, sums in FP64, the result unrounded. */
+int oracle_dwm_bf16_f64(const float* x, const float* w, double* y,
+                        int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1) return 1;
+    for (size_t i = 0; i < (size_t)N * C * H * W; ++i)
+        if (round_bfloat16((double)x[i]) != (double)x[i]) return 3;
+    for (size_t i = 0; i < (size_t)K * C * R * S; ++i)
+        if (round_bfloat16((double)w[i]) != (double)w[i]) return 3;
+    return dwm_forward(x, w, y, N, C, H, W, K, R, S, s, P, 2);
 }
 
 /* ------------------------------------------------------------------------- */
