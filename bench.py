@@ -195,48 +195,53 @@ def bench_backward_filter(args, L, x, w):
     print(json.dumps(out))
 
 
-def bench_half(args, L, x, w):
-    """A step = one dwm_f16_conv_forward (binary16 x, U, V, y; FP16 MFMA with FP32 accumulation) on
-    resident buffers; the filter transform runs once before.  With binary16 operands the
-    contraction's arithmetic intensity (about 200 flop per byte of V, U and y) is below the chip's
-    balance of 2.5 PFLOP/s : 8 TB/s, so both stages are priced against the HBM roofline."""
+def bench_half(args, L, x, w, bf16=False):
+    """A step = one dwm_f16_conv_forward (binary16 x, U, V, y; FP16 MFMA with FP32 accumulation) or,
+    with bf16, one dwm_bf16_conv_forward (the same with bfloat16) on resident buffers; the filter
+    transform runs once before.  With 16-bit operands the contraction's arithmetic intensity (about
+    200 flop per byte of V, U and y) is below the chip's balance of 2.5 PFLOP/s : 8 TB/s, so both
+    stages are priced against the HBM roofline."""
     import numpy as np
     import torch
 
     import paper_2002_00552_amd as dwm
 
     PEAK_MFMA_F16 = 2500.0
-    x16, w16 = x.astype(np.float16), w.astype(np.float16)
-    plan = dwm.dwm_f16_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    tdt = torch.bfloat16 if bf16 else torch.float16
+    fn = lambda name: getattr(dwm, ("dwm_bf16_" if bf16 else "dwm_f16_") + name)  # noqa: E731
+    xd, wd = torch.from_numpy(x).to(tdt).cuda(), torch.from_numpy(w).to(tdt).cuda()
+    x16, w16 = xd.float().cpu().numpy(), wd.float().cpu().numpy()  # the 16-bit values, as float32
+    plan = fn("plan_create")(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     if args.contract_variant >= 0:
-        dwm.dwm_f16_set_variant(plan, "contract", args.contract_variant)
-    info = dwm.dwm_f16_plan_info(plan)
-    xd, wd = torch.from_numpy(x16).cuda(), torch.from_numpy(w16).cuda()
-    U = torch.empty(dwm.dwm_f16_filter_bytes(plan) // 2, dtype=torch.float16, device="cuda")
-    ws = torch.empty(max(dwm.dwm_f16_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
-    y = torch.empty((L.N, L.K, info.OH, info.OW), dtype=torch.float16, device="cuda")
-    dwm.dwm_f16_set_workspace(plan, ws.data_ptr(), ws.numel())
+        fn("set_variant")(plan, "contract", args.contract_variant)
+    info = fn("plan_info")(plan)
+    U = torch.empty(fn("filter_bytes")(plan) // 2, dtype=tdt, device="cuda")
+    ws = torch.empty(max(fn("workspace_bytes")(plan), 256), dtype=torch.uint8, device="cuda")
+    y = torch.empty((L.N, L.K, info.OH, info.OW), dtype=tdt, device="cuda")
+    fn("set_workspace")(plan, ws.data_ptr(), ws.numel())
     st = torch.cuda.current_stream().cuda_stream
     xp, Up, yp = xd.data_ptr(), U.data_ptr(), y.data_ptr()
-    dwm.dwm_f16_filter_transform(plan, wd.data_ptr(), Up, st)
+    fn("filter_transform")(plan, wd.data_ptr(), Up, st)
     for _ in range(args.warmup):
-        dwm.dwm_f16_conv_forward(plan, xp, Up, yp, st)
+        fn("conv_forward")(plan, xp, Up, yp, st)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        dwm.dwm_f16_conv_forward(plan, xp, Up, yp, st)
+        fn("conv_forward")(plan, xp, Up, yp, st)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / args.steps
-    e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for i in range(args.steps):
-        e[i][0].record()
-        dwm.dwm_f16_input_transform(plan, xp, st)
-        e[i][1].record()
-        dwm.dwm_f16_contract_output(plan, Up, yp, st)
-        e[i][2].record()
-    torch.cuda.synchronize()
-    in_ms = sum(a.elapsed_time(b) for a, b, _ in e) / args.steps
-    ct_ms = sum(b.elapsed_time(c) for _, b, c in e) / args.steps
+
+    def timed(call):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    in_ms = timed(lambda: fn("input_transform")(plan, xp, st))
+    ct_ms = timed(lambda: fn("contract_output")(plan, Up, yp, st))
     v_bytes = 2.0 * info.mults_per_tile * L.C * info.T
     u_bytes = 2.0 * info.mults_per_tile * L.C * L.K
     x_bytes, y_bytes = 2.0 * x.size, 2.0 * y.numel()
@@ -253,12 +258,12 @@ def bench_half(args, L, x, w):
     }
     dom = "contract_output" if ct_ms >= in_ms else "input_transform"
     out = {
-        "metric": "direct-conv-equivalent TFLOP/s of DWM conv (binary16 storage, FP32 accumulation, 1 GPU); "
-                  "MSE vs FP64 direct",
+        "metric": "direct-conv-equivalent TFLOP/s of DWM conv (%s storage, FP32 accumulation, 1 GPU); "
+                  "MSE vs FP64 direct" % ("bfloat16" if bf16 else "binary16"),
         "value": info.direct_flops / dt / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": L.name + "_half", "parts": info.n_parts, "mults_per_tile": info.mults_per_tile,
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f16", "data": "synthetic",
+        "config": {"workload": L.name + ("_bf16" if bf16 else "_half"), "parts": info.n_parts, "mults_per_tile": info.mults_per_tile,
                    "direct_GFLOP": info.direct_flops / 1e9, "winograd_GFLOP": info.winograd_flops / 1e9},
         "roofline": {"kernel": {"contract_output": "contract16_kernel", "input_transform": "input_transform_f16_kernel"}[dom],
                      "bound": "hbm", "achieved": stages[dom]["achieved_GBps"], "peak": PEAK_HBM, "unit": "GB/s",
@@ -267,7 +272,7 @@ def bench_half(args, L, x, w):
     }
     if not args.no_check:
         import oracle
-        yh = y.cpu().numpy()
+        yh = y.float().cpu().numpy()
         idx = np.random.default_rng(99).choice(yh.size, min(yh.size, 40000), replace=False)
         ref = oracle.direct_f64_at(x16.astype(np.float32), w16.astype(np.float32), L.stride, L.pad, idx)
         got = yh.ravel()[idx].astype(np.float64)
@@ -275,7 +280,7 @@ def bench_half(args, L, x, w):
         out["accuracy"] = {"max_rel_err": float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))),
                            "mse_vs_fp64_direct": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
                            "sampled_outputs": int(idx.size)}
-    dwm.dwm_f16_plan_destroy(plan)
+    fn("plan_destroy")(plan)
     print(json.dumps(out))
 
 
@@ -426,6 +431,8 @@ def main():
                     help="time the gradient with respect to the filter of the same layer instead of the forward pass")
     ap.add_argument("--half", action="store_true",
                     help="time the half-precision forward path (dwm_f16_*) of the same layer")
+    ap.add_argument("--bf16", action="store_true",
+                    help="time the bfloat16 forward path (dwm_bf16_*) of the same layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
@@ -451,13 +458,13 @@ def main():
         L = wl.CONFIGS[args.config]
         index = args.config
 
-    if args.backward_data or args.backward_filter or args.half:
+    if args.backward_data or args.backward_filter or args.half or args.bf16:
         x, w = wl.make_layer_tensors(L, index)
         if args.backward_data:
             return bench_backward_data(args, L, x, w)
         if args.backward_filter:
             return bench_backward_filter(args, L, x, w)
-        return bench_half(args, L, x, w)
+        return bench_half(args, L, x, w, bf16=args.bf16)
 
     res, x, w = measure_forward(L, index, args.steps, args.warmup, args, check=not args.no_check)
     out = {

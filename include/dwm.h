@@ -347,6 +347,36 @@ DWM_API dwm_status_t dwm_f16_input_transform(const dwm_f16_plan_t* plan, const d
 DWM_API dwm_status_t dwm_f16_contract_output(const dwm_f16_plan_t* plan, const dwm_half_t* U_dev,
                                              dwm_half_t* y_dev, void* stream);
 
+/*
+ * The same path with bfloat16 storage (8 significant bits, binary32's exponent range) -- the other
+ * 16-bit format the matrix cores take, and the one to use where binary16's range is too narrow.
+ * Everything said above for dwm_f16_* holds with "bfloat16" for "binary16": x, w, y, U and V are
+ * bfloat16 (dwm_bf16_t = the 16-bit pattern, the upper half of the binary32 pattern), U and V are
+ * rounded once (nearest, ties to even), products are summed in FP32 on the bfloat16 matrix cores,
+ * the output transform is FP32, y is rounded once; the kernel is cut as eq. 8 writes it.  Layouts,
+ * workspace rules, variants (30..47) and error codes are those of the dwm_f16_* calls.
+ */
+typedef struct dwm_bf16_plan dwm_bf16_plan_t;
+typedef unsigned short dwm_bf16_t;
+
+DWM_API dwm_status_t dwm_bf16_plan_create(dwm_bf16_plan_t** out, int N, int C, int H, int W, int K, int R, int S,
+                                          int stride, int pad);
+DWM_API dwm_status_t dwm_bf16_plan_destroy(dwm_bf16_plan_t* plan);
+DWM_API dwm_status_t dwm_bf16_plan_info(const dwm_bf16_plan_t* plan, dwm_plan_info_t* info);
+DWM_API size_t dwm_bf16_filter_bytes(const dwm_bf16_plan_t* plan);
+DWM_API size_t dwm_bf16_workspace_bytes(const dwm_bf16_plan_t* plan);
+DWM_API dwm_status_t dwm_bf16_set_workspace(dwm_bf16_plan_t* plan, void* ws_dev, size_t bytes);
+DWM_API dwm_status_t dwm_bf16_set_variant(dwm_bf16_plan_t* plan, const char* stage, int variant);
+DWM_API dwm_status_t dwm_bf16_filter_transform(const dwm_bf16_plan_t* plan, const dwm_bf16_t* w_dev,
+                                               dwm_bf16_t* U_dev, void* stream);
+DWM_API dwm_status_t dwm_bf16_conv_forward(const dwm_bf16_plan_t* plan, const dwm_bf16_t* x_dev,
+                                           const dwm_bf16_t* U_dev, dwm_bf16_t* y_dev, void* stream);
+DWM_API dwm_status_t dwm_bf16_conv_forward_f32out(const dwm_bf16_plan_t* plan, const dwm_bf16_t* x_dev,
+                                                  const dwm_bf16_t* U_dev, float* y_dev, void* stream);
+DWM_API dwm_status_t dwm_bf16_input_transform(const dwm_bf16_plan_t* plan, const dwm_bf16_t* x_dev, void* stream);
+DWM_API dwm_status_t dwm_bf16_contract_output(const dwm_bf16_plan_t* plan, const dwm_bf16_t* U_dev,
+                                              dwm_bf16_t* y_dev, void* stream);
+
 DWM_API const char* dwm_status_string(dwm_status_t status);
 
 #ifdef __cplusplus

@@ -113,6 +113,18 @@ _SIGNATURES = {
     "dwm_f16_conv_forward_f32out": (_I, [_P, _P, _P, _P, _P]),
     "dwm_f16_input_transform": (_I, [_P, _P, _P]),
     "dwm_f16_contract_output": (_I, [_P, _P, _P, _P]),
+    "dwm_bf16_plan_create": (_I, [ctypes.POINTER(_P)] + [_I] * 9),
+    "dwm_bf16_plan_destroy": (_I, [_P]),
+    "dwm_bf16_plan_info": (_I, [_P, ctypes.POINTER(dwm_plan_info_t)]),
+    "dwm_bf16_filter_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_bf16_workspace_bytes": (ctypes.c_size_t, [_P]),
+    "dwm_bf16_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
+    "dwm_bf16_set_variant": (_I, [_P, ctypes.c_char_p, _I]),
+    "dwm_bf16_filter_transform": (_I, [_P, _P, _P, _P]),
+    "dwm_bf16_conv_forward": (_I, [_P, _P, _P, _P, _P]),
+    "dwm_bf16_conv_forward_f32out": (_I, [_P, _P, _P, _P, _P]),
+    "dwm_bf16_input_transform": (_I, [_P, _P, _P]),
+    "dwm_bf16_contract_output": (_I, [_P, _P, _P, _P]),
 }
 EXPORTS = sorted(_SIGNATURES)
 
@@ -350,3 +362,55 @@ def dwm_f16_input_transform(plan, x_dev, stream=None):
 
 def dwm_f16_contract_output(plan, U_dev, y_dev, stream=None):
     _check(lib().dwm_f16_contract_output(plan, U_dev, y_dev, stream), "dwm_f16_contract_output")
+
+
+def dwm_bf16_plan_create(N, C, H, W, K, R, S, stride, pad):
+    h = _P()
+    _check(lib().dwm_bf16_plan_create(ctypes.byref(h), N, C, H, W, K, R, S, stride, pad), "dwm_bf16_plan_create")
+    return h
+
+
+def dwm_bf16_plan_destroy(plan):
+    _check(lib().dwm_bf16_plan_destroy(plan), "dwm_bf16_plan_destroy")
+
+
+def dwm_bf16_plan_info(plan):
+    info = dwm_plan_info_t()
+    _check(lib().dwm_bf16_plan_info(plan, ctypes.byref(info)), "dwm_bf16_plan_info")
+    return info
+
+
+def dwm_bf16_filter_bytes(plan):
+    return int(lib().dwm_bf16_filter_bytes(plan))
+
+
+def dwm_bf16_workspace_bytes(plan):
+    return int(lib().dwm_bf16_workspace_bytes(plan))
+
+
+def dwm_bf16_set_workspace(plan, ws_dev, nbytes):
+    _check(lib().dwm_bf16_set_workspace(plan, ws_dev, nbytes), "dwm_bf16_set_workspace")
+
+
+def dwm_bf16_set_variant(plan, stage, variant):
+    _check(lib().dwm_bf16_set_variant(plan, stage.encode(), variant), "dwm_bf16_set_variant")
+
+
+def dwm_bf16_filter_transform(plan, w_dev, U_dev, stream=None):
+    _check(lib().dwm_bf16_filter_transform(plan, w_dev, U_dev, stream), "dwm_bf16_filter_transform")
+
+
+def dwm_bf16_conv_forward(plan, x_dev, U_dev, y_dev, stream=None):
+    _check(lib().dwm_bf16_conv_forward(plan, x_dev, U_dev, y_dev, stream), "dwm_bf16_conv_forward")
+
+
+def dwm_bf16_conv_forward_f32out(plan, x_dev, U_dev, y_dev, stream=None):
+    _check(lib().dwm_bf16_conv_forward_f32out(plan, x_dev, U_dev, y_dev, stream), "dwm_bf16_conv_forward_f32out")
+
+
+def dwm_bf16_input_transform(plan, x_dev, stream=None):
+    _check(lib().dwm_bf16_input_transform(plan, x_dev, stream), "dwm_bf16_input_transform")
+
+
+def dwm_bf16_contract_output(plan, U_dev, y_dev, stream=None):
+    _check(lib().dwm_bf16_contract_output(plan, U_dev, y_dev, stream), "dwm_bf16_contract_output")
