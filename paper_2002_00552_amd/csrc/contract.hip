@@ -113,8 +113,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
 #pragma unroll
                     for (int e = 0; e < 16; ++e) Y[mi][nj][q][e] = 0.f;
             }
-        // plane and chunk of the first iteration
-        int p = 0, j = it0;
+        // plane and chunk of the first iteration; jf: chunks in the accumulator since the last fold
+        int p = 0, j = it0, jf = 0;
         int nch = PT.e[0].Lpad / LC;
         while (j >= nch) {
             j -= nch;
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
             const float* bs = smem + stage * STAGE + A_FLOATS + (4 * lh) * TT;
             const int bcol = (wave_n * 32 * WN + li) ^ (lh << 5);
             const int istage = (stage + NS - 1) % NS;
-            const bool fresh = j == 0 || it == 0;  // first chunk of a plane, or of the segment
+            const bool fresh = jf == 0;  // first chunk of a plane, of the segment, or after a fold
             const floatx16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             // operand fragments of group g+1 are read from LDS before the MFMAs of group g
             float4 av[2][WM];
@@ -213,7 +213,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, 8 / (WGM * WGN)) void contract_kern
             advance_issue();
 
             const bool plane_done = ++j == nch;
-            if (plane_done || it + 1 == nit) {
+            // Long reductions (several parts of a class, many channels) are folded every kFoldSteps
+            // steps: the output transform is linear, so it may be applied to partial sums, and an fp32
+            // accumulator that never holds more than a few hundred terms keeps the rounding error at
+            // the level of a per-part summation (the accuracy the paper's Table 1 reports).
+            if (plane_done || it + 1 == nit || ++jf == kFoldSteps / LC) {
+                jf = 0;
                 // fold M_p (or the part of it this segment covers) into the 2x2 outputs
                 const int coef = PT.e[p].coef;
 #pragma unroll

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
         for (int e = 0; e < 16; ++e) Y[q][e] = 0.f;
 
     const int nit = Q.n_iter;
-    int p = Q.plane0, j = 0;
+    int p = Q.plane0, j = 0, jf = 0;  // jf: chunks in the accumulator since the last fold
     int nch = PT.e[p].Lpad / LC;
 
     // issue cursor: the chunk whose loads go out next; parks on the last chunk.  A DMA address is
@@ -163,8 +163,11 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
         }
         advance_issue();
 
-        if (++j == nch) {
-            // fold M_p into the 2x2 outputs
+        const bool plane_done = ++j == nch;
+        if (plane_done || ++jf == kFoldSteps / LC) {
+            jf = 0;
+            // fold M_p (or what the accumulator holds of it: long reductions are folded every
+            // kFoldSteps steps to keep fp32 partial sums short) into the 2x2 outputs
             const int coef = PT.e[p].coef;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(256, 2) void contract_batch_kernel(BatchArgs A, Pla
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-            if (it + 1 < nit) {
+            if (plane_done && it + 1 < nit) {
                 ++p;
                 j = 0;
                 nch = PT.e[p].Lpad / LC;

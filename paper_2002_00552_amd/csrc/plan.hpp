@@ -97,6 +97,8 @@ constexpr ContractVariant kContractVariants[] = {
 constexpr int kFirstHalfVariant = 30, kLastHalfVariant = 47;
 constexpr int kNumContractVariants = sizeof(kContractVariants) / sizeof(kContractVariants[0]);
 constexpr int kNumCUs = 256;  // MI355X
+// reduction steps a contraction's fp32 accumulator collects at most before it is folded into the outputs
+constexpr int kFoldSteps = 256;
 
 // How the (K tile, T tile) grid is shared out for one variant.  Workgroups 0..n_full-1
 // each own one whole tile.  The remaining n_sk_tiles tiles (fewer than one per CU) are
