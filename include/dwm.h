@@ -264,6 +264,15 @@ DWM_API dwm_status_t dwm_bwd_data_plan_phase(const dwm_bwd_data_plan_t* plan, in
 DWM_API size_t dwm_bwd_data_filter_bytes(const dwm_bwd_data_plan_t* plan);
 DWM_API size_t dwm_bwd_data_workspace_bytes(const dwm_bwd_data_plan_t* plan);
 DWM_API dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void* ws_dev, size_t bytes);
+/* stage "path": 0 = the sub-convolutions described above, 1 = the whole gradient in one kernel (all
+ * phases and channels of dx as the columns of a single stride-1 correlation of dy whose window is
+ * cut by eq. 8; for layers with few input channels; needs no workspace; DWM_ERR_UNSUPPORTED where
+ * it does not apply: a window of fewer than two or more than eleven taps, more than 256 columns,
+ * an image of dy of 2 GiB or more, a filter slice that does not fit in LDS -- windows of seven taps
+ * and more), -1 = the planner's choice (1 where C <= 8, C*stride^2 <= 64, two workgroups fit a CU and at
+ * least half of a workgroup's lanes hold a tile).
+ * Both give the same dx up to fp32 summation order.  May be called at any time. */
+DWM_API dwm_status_t dwm_bwd_data_set_variant(dwm_bwd_data_plan_t* plan, const char* stage, int variant);
 /* w_dev is the forward layer's [K][C][R][S]; Ugw_dev (dwm_bwd_data_filter_bytes long) receives, per
  * phase, the transformed filter of that phase's flipped taps with filters and channels swapped. */
 DWM_API dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, const float* w_dev, float* Ugw_dev,

@@ -93,6 +93,7 @@ _SIGNATURES = {
     "dwm_bwd_data_filter_bytes": (ctypes.c_size_t, [_P]),
     "dwm_bwd_data_workspace_bytes": (ctypes.c_size_t, [_P]),
     "dwm_bwd_data_set_workspace": (_I, [_P, _P, ctypes.c_size_t]),
+    "dwm_bwd_data_set_variant": (_I, [_P, ctypes.c_char_p, _I]),
     "dwm_bwd_data_filter_transform": (_I, [_P, _P, _P, _P]),
     "dwm_conv_backward_data": (_I, [_P, _P, _P, _P, _P]),
     "dwm_bwd_filter_plan_create": (_I, [ctypes.POINTER(_P)] + [_I] * 9),
@@ -273,6 +274,10 @@ def dwm_bwd_data_workspace_bytes(plan):
 
 def dwm_bwd_data_set_workspace(plan, ws_dev, nbytes):
     _check(lib().dwm_bwd_data_set_workspace(plan, ws_dev, nbytes), "dwm_bwd_data_set_workspace")
+
+
+def dwm_bwd_data_set_variant(plan, stage, variant):
+    _check(lib().dwm_bwd_data_set_variant(plan, stage.encode(), variant), "dwm_bwd_data_set_variant")
 
 
 def dwm_bwd_data_filter_transform(plan, w_dev, Ugw_dev, stream=None):

@@ -13,7 +13,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdwm.so")
 SOURCES = ["plan.cpp", "setup.cpp", "transforms.hip", "contract.hip", "fused.hip", "contract_batch.hip",
-           "backward.hip", "wgrad.hip", "half.hip", "bf16.hip", "noalloc.hip"]
+           "backward.hip", "backward_small.hip", "wgrad.hip", "half.hip", "bf16.hip", "noalloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

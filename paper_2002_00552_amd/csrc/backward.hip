@@ -47,6 +47,14 @@ struct dwm_bwd_data_plan {
     // ... and, where their tile grids coincide, ONE input transform for all of them: a plan that
     // holds every sub-convolution's pieces and classes (used by the input transform only)
     dwm_plan_t* merged;
+    // few input channels: the whole gradient in one kernel (backward_small.hip), its filter copy
+    // u_small_off floats into Ugw; variant_path < 0: the planner's choice, 0: sub-convolutions, 1: that kernel
+    bool small_ok;
+    dwm::BwdSmallArgs small;
+    size_t u_small_off;
+    int variant_path;
+    bool use_small() const { return small_ok && (variant_path == 1 || (variant_path < 0 && small_default)); }
+    bool small_default;
 };
 
 namespace dwm {
@@ -317,6 +325,13 @@ dwm_status_t dwm_bwd_data_plan_create(dwm_bwd_data_plan_t** out, int N, int C, i
             ph.u_off = off;
             off += (dwm_plan_filter_bytes(ph.sub) / sizeof(float) + 63) / 64 * 64;
         }
+    // the single-kernel form: chosen where the sub-convolutions would have only a handful of filters
+    bp->small_ok = bwd_small_setup(N, C, H, W, K, R, S, stride, pad, &bp->small);
+    bp->small_default = bp->small_ok && C <= 8 && bp->small.nf <= 64 && bp->small.lds_bytes <= 78 * 1024 &&
+                        bp->small.eff_pct >= 50;
+    bp->variant_path = -1;
+    bp->u_small_off = off;
+    if (bp->small_ok) off += (bp->small.u_floats + 63) / 64 * 64;
     bp->filter_floats = off;
     setup_batch(*bp);
     *out = bp;
@@ -362,6 +377,16 @@ dwm_status_t dwm_bwd_data_plan_phase(const dwm_bwd_data_plan_t* plan, int i, dwm
     return DWM_OK;
 }
 
+dwm_status_t dwm_bwd_data_set_variant(dwm_bwd_data_plan_t* plan, const char* stage, int variant)
+{
+    if (!plan || !stage) return DWM_ERR_INVALID_ARG;
+    if (std::strcmp(stage, "path") != 0) return DWM_ERR_INVALID_ARG;
+    if (variant < -1 || variant > 1) return DWM_ERR_INVALID_ARG;
+    if (variant == 1 && !plan->small_ok) return DWM_ERR_UNSUPPORTED;
+    plan->variant_path = variant;
+    return DWM_OK;
+}
+
 size_t dwm_bwd_data_filter_bytes(const dwm_bwd_data_plan_t* plan) { return plan ? plan->filter_floats * sizeof(float) : 0; }
 size_t dwm_bwd_data_workspace_bytes(const dwm_bwd_data_plan_t* plan) { return plan ? plan->ws_bytes : 0; }
 
@@ -403,6 +428,8 @@ dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, cons
         const dwm_status_t st = dwm_filter_transform(ph.sub, Ugw_dev, Ugw_dev + ph.u_off, stream);
         if (st != DWM_OK) return st;
     }
+    if (plan->small_ok)
+        return dwm::launch_bwd_small_filter(plan->small, plan->R, plan->S, w_dev, Ugw_dev + plan->u_small_off, stream);
     return DWM_OK;
 }
 
@@ -410,6 +437,7 @@ dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float
                                     float* dx_dev, void* stream)
 {
     if (!plan || !dy_dev || !Ugw_dev || !dx_dev) return DWM_ERR_INVALID_ARG;
+    if (plan->use_small()) return dwm::launch_bwd_small(plan->small, dy_dev, Ugw_dev + plan->u_small_off, dx_dev, stream);
     for (const auto& ph : plan->phases) {
         if (ph.UH <= 0 || ph.UW <= 0) continue;
         if (!ph.sub) {  // no tap reaches these pixels

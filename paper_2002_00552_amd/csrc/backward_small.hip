@@ -1,0 +1,400 @@
+// Gradient with respect to the input for layers with few input channels (network stems), in
+// one kernel (gfx950).  What is computed is the paper's Sec. 4.2 eq. 16-17 (the parts' input
+// gradients summed = the gradient of the ordinary convolution); how:
+//
+// Pixel (stride*t + rho) of dx, for every residue rho of the pixel coordinate modulo the stride,
+// is a sum over ONE window of dy that does not depend on rho (the mirror image of the phase
+// grouping of Sec. 4.1, eq. 12-14); only the taps differ.  So all stride^2 phases and all C
+// channels of dx are the "filters" f = (c, rho_h, rho_w) of a single stride-1 correlation of dy
+// over that window, whose taps are cut into pieces of two and three (eq. 8) that run through
+// F(2,2) / F(2,3) (Sec. 3.2).  With C = 3 that gives 12 (stride 2) or 48 (stride 4) columns for
+// the matrix unit where a sub-convolution per phase has 3.
+//
+// A workgroup (four waves) owns a block of tiles of one image and 16 columns; a wave owns 16 tiles.
+// The K channels of dy pass through LDS eight at a time, double buffered: while a chunk is
+// multiplied, the next chunk's region of dy is on its way into registers and its slice of the
+// transformed filter into LDS (DMA).  Per step of four reduction rows (four channels of one pair
+// of pieces) a lane reads the patch of its (tile, channel) from LDS, applies B^T d B in registers
+// -- the result is its B operand for every plane -- and issues one v_mfma_f32_16x16x4_f32 per
+// plane; the A operands come from the LDS copy of the filter, four planes per 16-byte read.
+// Every plane keeps its own accumulator; A^T M A is applied once at the end, and a lane then
+// holds the pixels of its four columns (for stride 2: a 4 x 4 block of one channel), written once.
+// dx is fully overwritten (residues no tap reaches have zero filters), nothing is accumulated
+// in memory, results do not vary from run to run.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "dma.hpp"
+#include "plan.hpp"
+
+namespace dwm {
+
+typedef float bs_float4 __attribute__((ext_vector_type(4)));
+typedef float bs_float4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef float bs_float2u __attribute__((ext_vector_type(2), aligned(4)));
+
+// (G g)[i] of F(2,3) (Sec. 3.2); a two-tap piece is a three-tap piece whose third tap is zero.
+__device__ __forceinline__ float bs_g_row(int i, float v0, float v1, float v2)
+{
+    switch (i) {
+        case 0: return v0;
+        case 1: return 0.5f * (v0 + v1 + v2);
+        case 2: return 0.5f * (v0 - v1 + v2);
+        default: return v2;
+    }
+}
+
+// Position of (plane, lane) inside one step of the filter copy: planes in groups of four, a lane's
+// four planes adjacent (one 16-byte LDS read); the planes left over follow, 64 lanes each.
+__host__ __device__ __forceinline__ int bs_upos(int planes, int plane, int lane)
+{
+    const int g4 = planes / 4;
+    return plane < 4 * g4 ? (plane >> 2) * 256 + lane * 4 + (plane & 3) : g4 * 256 + (plane - 4 * g4) * 64 + lane;
+}
+
+// ---------------------------------------------------------------------------------
+// Filter copy UB[column block][chunk][step][plane, lane]: the A operands exactly as a chunk
+// lies in LDS (a chunk padded to whole KB; the padding is copied and never read).  Lane (i, q)
+// of a step holds column 16*cb + i and the step's row q; the rows of a chunk are (pair of
+// pieces, channel of the chunk).  One thread per (column, channel, pair).
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bwd_small_filter_kernel(BwdSmallArgs F, int R, int S, const float* __restrict__ w,
+                                                               float* __restrict__ U)
+{
+    const int kpad = F.nchunks * kBsChunk;
+    const long long total = (long long)F.ncb * 16 * kpad * F.npp;
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int pp = (int)(e % F.npp);
+    const int k = (int)((e / F.npp) % kpad);
+    const int f = (int)(e / ((long long)F.npp * kpad));
+    const int ph = pp / F.npw, pw = pp % F.npw;
+    const int rho_w = f % F.s, rho_h = (f / F.s) % F.s, c = f / (F.s * F.s);
+    const bool real = f < F.nf && k < F.K;
+    float g[3][3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            float v = 0.f;
+            if (real && i < F.lh[ph] && j < F.lw[pw]) {
+                // window position -> tap of this residue (none: zero)
+                const int ih = F.re_h[rho_h] + F.Lh - (F.jh[ph] + i), iw = F.re_w[rho_w] + F.Lw - (F.jw[pw] + j);
+                if (ih >= 0 && ih < F.rn_h[rho_h] && iw >= 0 && iw < F.rn_w[rho_w])
+                    v = w[(((size_t)k * F.C + c) * R + (F.s * ih + F.ra_h[rho_h])) * S + (F.s * iw + F.ra_w[rho_w])];
+            }
+            g[i][j] = v;
+        }
+    float t[4][3];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j) t[i][j] = bs_g_row(i, g[0][j], g[1][j], g[2][j]);
+    const int nfreq = F.four ? 4 : 3, planes = nfreq * nfreq;
+    const int chunk = k / kBsChunk, row = pp * kBsChunk + (k % kBsChunk);
+    const int step = row >> 2, lane = (row & 3) * 16 + (f & 15);
+    float* dst = U + ((size_t)(f >> 4) * F.nchunks + chunk) * (size_t)F.us_floats + (size_t)step * (planes * 64);
+#pragma unroll
+    for (int fh = 0; fh < 4; ++fh)
+#pragma unroll
+        for (int fw = 0; fw < 4; ++fw)
+            if (fh < nfreq && fw < nfreq) dst[bs_upos(planes, fh * nfreq + fw, lane)] = bs_g_row(fw, t[fh][0], t[fh][1], t[fh][2]);
+}
+
+// B^T of F(2,3) on a patch of four (Sec. 3.2), or its first three rows on a patch of three
+// (two-tap pieces only: the point at infinity is not needed).
+template <int NF>
+__device__ __forceinline__ void bs_bt(const float (&d)[NF], float (&o)[NF])
+{
+    o[0] = d[0] - d[2];
+    o[1] = d[1] + d[2];
+    o[2] = d[2] - d[1];
+    if constexpr (NF == 4) o[3] = d[1] - d[3];
+}
+
+// A^T over the frequencies of one dimension.
+template <int NF>
+__device__ __forceinline__ void bs_at(const bs_float4 (&m)[NF], bs_float4 (&o)[2])
+{
+    o[0] = m[0] + m[1] + m[2];
+    o[1] = m[1] - m[2];
+    if constexpr (NF == 4) o[1] -= m[3];
+}
+
+template <bool FOUR>
+__global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const float* __restrict__ dy,
+                                                           const float* __restrict__ U, float* __restrict__ dx)
+{
+    constexpr int NF = FOUR ? 4 : 3, PL = NF * NF, G4 = PL / 4, REM = PL - 4 * G4;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    // LDS: two staged chunks of dy [channel][row][column parity][lwp] | two chunks of the filter copy
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;  // LDS byte address of the array
+    const uint32_t xs_bytes = (uint32_t)F.xs_floats * 4u, us_bytes = (uint32_t)F.us_floats * 4u;
+    const uint32_t us0 = 2u * xs_bytes;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int ln = lane & 15, lq = lane >> 4;
+    const int tl = wave * 16 + ln;
+    const int by = F.div_bw.div(tl), bx = tl - by * F.BW;
+    const uint32_t lane_base = 4u * (uint32_t)(lq * F.chan_floats + (by < F.BH ? by * F.tile_row_step + bx : 0));
+    const uint32_t row_bytes = (uint32_t)F.row_floats * 4u, chan_bytes = (uint32_t)F.chan_floats * 4u;
+    const size_t img = (size_t)F.OH * F.OW;
+    const int region = F.nrows * F.lw_in;
+    const char* ldsb = reinterpret_cast<const char*>(lds);
+
+    const int nblocks = F.N * F.nbh * F.nbw;
+    for (int b = blockIdx.x; b < nblocks; b += gridDim.x) {
+        const int btx = b % F.nbw, bty = (b / F.nbw) % F.nbh, n = b / (F.nbw * F.nbh);
+        const int ty0 = bty * F.BH, tx0 = btx * F.BW;
+        const int ty = ty0 + by, tx = tx0 + bx;
+        const bool tile_ok = by < F.BH && ty < F.TH && tx < F.TW;
+
+        // what this thread stages of every channel: up to kBsMaxSlots elements of the block's region of
+        // dy; positions outside the image get an offset past the buffer's end, which reads as zero
+        uint32_t goff[kBsMaxSlots];
+        int loff[kBsMaxSlots];
+#pragma unroll
+        for (int e = 0; e < kBsMaxSlots; ++e) {
+            const int idx = tid + 256 * e;
+            const int r = F.div_lw.div(idx), c = idx - r * F.lw_in;
+            const int row = 2 * ty0 - F.Lh + r, col = 2 * tx0 - F.Lw + c;
+            const bool inb = idx < region && row >= 0 && row < F.OH && col >= 0 && col < F.OW;
+            goff[e] = inb ? (uint32_t)(row * F.OW + col) * 4u : 0x80000000u;
+            loff[e] = idx < region ? 4 * (r * F.row_floats + (c & 1) * F.lwp + (c >> 1)) : -1;
+        }
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(dy + (size_t)n * F.K * img), 0, (int)((size_t)F.K * img * 4), 0x00020000);
+
+        float sv[kBsChunk][kBsMaxSlots];
+        auto stage_load = [&](int chunk) {  // chunk's region of dy -> registers
+#pragma unroll
+            for (int ch = 0; ch < kBsChunk; ++ch) {
+                const int k = chunk * kBsChunk + ch;
+                const uint32_t koff = k < F.K ? 0u : 0x80000000u;  // channels past K: zeros
+                const uint32_t soff = (uint32_t)((size_t)min(k, F.K - 1) * img * 4);
+#pragma unroll
+                for (int e = 0; e < kBsMaxSlots; ++e)
+                    if (e < F.ne) sv[ch][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, goff[e] | koff, soff, 0));
+            }
+        };
+        auto stage_write = [&](int buf) {  // registers -> LDS
+            float* xb = lds + buf * F.xs_floats;
+#pragma unroll
+            for (int ch = 0; ch < kBsChunk; ++ch)
+#pragma unroll
+                for (int e = 0; e < kBsMaxSlots; ++e)
+                    if (e < F.ne && loff[e] >= 0)
+                        *reinterpret_cast<float*>(reinterpret_cast<char*>(xb) + (uint32_t)loff[e] + (uint32_t)ch * chan_bytes) = sv[ch][e];
+        };
+
+        for (int cb = 0; cb < F.ncb; ++cb) {
+            // a chunk of the filter copy -> LDS by DMA: 16 bytes per lane, 1 KB per wave and instruction
+            const float* ucb = U + (size_t)cb * F.nchunks * F.us_floats;
+            auto stage_u = [&](int chunk, int buf) {
+                const float* src = ucb + (size_t)chunk * F.us_floats;
+                const uint32_t dst = lds0 + us0 + (uint32_t)buf * us_bytes;
+                for (uint32_t o = (uint32_t)wave * 1024u; o < us_bytes; o += 4096u)  // us_bytes: a multiple of 1 KB
+                    dma16s(src, o + (uint32_t)lane * 16u, (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + o)));
+            };
+
+            bs_float4 acc[NF][NF];
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+#pragma unroll
+                for (int j = 0; j < NF; ++j) acc[i][j] = bs_float4{0.f, 0.f, 0.f, 0.f};
+
+            stage_load(0);
+            stage_u(0, 0);
+            wait_vmcnt<0>();
+            stage_write(0);
+            __syncthreads();
+
+            for (int ci = 0; ci < F.nchunks; ++ci) {
+                const int buf = ci & 1;
+                const bool more = ci + 1 < F.nchunks;
+                if (more) {
+                    stage_load(ci + 1);
+                    stage_u(ci + 1, buf ^ 1);
+                }
+                const char* xb = ldsb + (uint32_t)buf * xs_bytes + lane_base;
+                const char* ub = ldsb + us0 + (uint32_t)buf * us_bytes + (uint32_t)lane * 16u;
+                const char* ur = ldsb + us0 + (uint32_t)buf * us_bytes + (uint32_t)(G4 * 1024) + (uint32_t)lane * 4u;
+
+                auto read_patch = [&](int st, float (&d)[NF][NF]) {
+                    const char* p0 = xb + F.so0[st];
+                    const char* p1 = xb + F.so1[st];
+#pragma unroll
+                    for (int i = 0; i < NF; ++i) {
+                        const float* q0 = reinterpret_cast<const float*>(p0 + (uint32_t)i * row_bytes);
+                        const float* q1 = reinterpret_cast<const float*>(p1 + (uint32_t)i * row_bytes);
+                        d[i][0] = q0[0];
+                        d[i][2] = q0[1];
+                        d[i][1] = q1[0];
+                        if constexpr (FOUR) d[i][3] = q1[1];
+                    }
+                };
+                auto step = [&](int st, const float (&d)[NF][NF], float (&dn)[NF][NF], bool next) {
+                    // A operands of this step
+                    float a[PL];
+                    const char* us = ub + (uint32_t)st * (uint32_t)(PL * 256);
+#pragma unroll
+                    for (int g = 0; g < G4; ++g) {
+                        const bs_float4 v = *reinterpret_cast<const bs_float4*>(us + g * 1024);
+                        a[4 * g] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
+                    }
+#pragma unroll
+                    for (int r = 0; r < REM; ++r)
+                        a[4 * G4 + r] = *reinterpret_cast<const float*>(ur + (uint32_t)st * (uint32_t)(PL * 256) + r * 256);
+                    if (next) read_patch(st + 1, dn);
+                    float tmp[NF][NF], v[NF][NF];
+#pragma unroll
+                    for (int j = 0; j < NF; ++j) {
+                        float col[NF], o[NF];
+#pragma unroll
+                        for (int i = 0; i < NF; ++i) col[i] = d[i][j];
+                        bs_bt<NF>(col, o);
+#pragma unroll
+                        for (int i = 0; i < NF; ++i) tmp[i][j] = o[i];
+                    }
+#pragma unroll
+                    for (int i = 0; i < NF; ++i) bs_bt<NF>(tmp[i], v[i]);
+#pragma unroll
+                    for (int i = 0; i < NF; ++i)
+#pragma unroll
+                        for (int j = 0; j < NF; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i * NF + j], v[i][j], acc[i][j], 0, 0, 0);
+                };
+
+                float d0[NF][NF], d1[NF][NF];
+                read_patch(0, d0);
+                for (int st = 0; st < F.steps; st += 2) {  // steps per chunk: a multiple of two
+                    step(st, d0, d1, true);
+                    step(st + 1, d1, d0, st + 2 < F.steps);
+                }
+                if (more) {
+                    wait_vmcnt<0>();
+                    stage_write(buf ^ 1);
+                }
+                __syncthreads();
+            }
+
+            // ---- A^T M A, then the lane's pixels: columns 16*cb + 4*lq + r of tile (ty, tx) ----
+            bs_float4 Y[2][2];
+            {
+                bs_float4 t[NF][2];
+#pragma unroll
+                for (int i = 0; i < NF; ++i) bs_at<NF>(acc[i], t[i]);
+#pragma unroll
+                for (int bcol = 0; bcol < 2; ++bcol) {
+                    bs_float4 m[NF], o[2];
+#pragma unroll
+                    for (int i = 0; i < NF; ++i) m[i] = t[i][bcol];
+                    bs_at<NF>(m, o);
+                    Y[0][bcol] = o[0];
+                    Y[1][bcol] = o[1];
+                }
+            }
+            if (tile_ok) {
+                const int f0 = cb * 16 + lq * 4;
+                const int s = F.s, ss = s * s;
+                float* dxn = dx + (size_t)n * F.C * F.H * F.W;
+                if (s == 2) {
+                    // the four columns are the four residues of one channel: a 4 x 4 block of pixels
+                    const int c = f0 >> 2;
+                    if (c < F.C) {
+                        float* pc = dxn + (size_t)c * F.H * F.W;
+                        const int iw = 4 * tx;
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int rh = 0; rh < 2; ++rh) {
+                                const int ih = 4 * ty + 2 * i + rh;
+                                if (ih >= F.H) continue;
+                                float* pr = pc + (size_t)ih * F.W + iw;
+                                const float v0 = Y[i][0][2 * rh], v1 = Y[i][0][2 * rh + 1], v2 = Y[i][1][2 * rh], v3 = Y[i][1][2 * rh + 1];
+                                if (iw + 3 < F.W) {
+                                    __builtin_nontemporal_store(bs_float4u{v0, v1, v2, v3}, reinterpret_cast<bs_float4u*>(pr));
+                                } else {
+                                    if (iw < F.W) pr[0] = v0;
+                                    if (iw + 1 < F.W) pr[1] = v1;
+                                    if (iw + 2 < F.W) pr[2] = v2;
+                                }
+                            }
+                    }
+                } else if ((s & 3) == 0) {
+                    // the four columns are four adjacent pixels of one row residue
+                    const int c = f0 / ss, rh = (f0 / s) % s, rw0 = f0 % s;
+                    if (c < F.C) {
+                        float* pc = dxn + (size_t)c * F.H * F.W;
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            const int ih = s * (2 * ty + i) + rh;
+                            if (ih >= F.H) continue;
+#pragma unroll
+                            for (int j = 0; j < 2; ++j) {
+                                const int iw = s * (2 * tx + j) + rw0;
+                                float* pr = pc + (size_t)ih * F.W + iw;
+                                if (iw + 3 < F.W) {
+                                    __builtin_nontemporal_store(bs_float4u{Y[i][j][0], Y[i][j][1], Y[i][j][2], Y[i][j][3]},
+                                                                reinterpret_cast<bs_float4u*>(pr));
+                                } else {
+                                    if (iw < F.W) pr[0] = Y[i][j][0];
+                                    if (iw + 1 < F.W) pr[1] = Y[i][j][1];
+                                    if (iw + 2 < F.W) pr[2] = Y[i][j][2];
+                                }
+                            }
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int f = f0 + r;
+                        if (f >= F.nf) continue;
+                        const int c = f / ss, rh = (f / s) % s, rw = f % s;
+                        float* pc = dxn + (size_t)c * F.H * F.W;
+#pragma unroll
+                        for (int i = 0; i < 2; ++i)
+#pragma unroll
+                            for (int j = 0; j < 2; ++j) {
+                                const int ih = s * (2 * ty + i) + rh, iw = s * (2 * tx + j) + rw;
+                                if (ih < F.H && iw < F.W) pc[(size_t)ih * F.W + iw] = Y[i][j][r];
+                            }
+                    }
+                }
+            }
+        }
+    }
+}
+
+dwm_status_t launch_bwd_small_filter(const BwdSmallArgs& a, int R, int S, const float* w, float* U, void* stream)
+{
+    const long long total = (long long)a.ncb * 16 * a.nchunks * kBsChunk * a.npp;
+    if (total > 0x7fffffffLL * 256) return DWM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(bwd_small_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a,
+                       R, S, w, U);
+    return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
+}
+
+dwm_status_t launch_bwd_small(const BwdSmallArgs& a, const float* dy, const float* U, float* dx, void* stream)
+{
+    auto kernel = a.four ? bwd_small_kernel<true> : bwd_small_kernel<false>;
+    if (a.lds_bytes > 64 * 1024) {
+        static const hipError_t attr = [] {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_small_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_small_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        }();
+        if (attr != hipSuccess) return DWM_ERR_HIP;
+    }
+    // persistent workgroups, two per CU (fewer where there are fewer blocks)
+    const long long nblocks = (long long)a.N * a.nbh * a.nbw;
+    dim3 grid((unsigned)std::min<long long>(nblocks, 2 * kNumCUs)), block(256);
+    hipLaunchKernelGGL(kernel, grid, block, a.lds_bytes, (hipStream_t)stream, a, dy, U, dx);
+    return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
+}
+
+}  // namespace dwm

@@ -207,6 +207,39 @@ struct InLdsArgs {
     size_t lds_bytes;
 };
 
+// Geometry of the single-kernel data gradient for layers with few input channels
+// (backward_small.hip).  All phases of the gradient image are computed as ONE stride-1
+// correlation of dy: pixel (stride*t + rho) of dx, for every residue rho, is a sum over the same
+// window of dy, rows t - Lh .. t - Lh + nwh - 1, with the taps w[stride*(e_rho + Lh - j) + a_rho]
+// at window position j (zero where the residue has no such tap).  The "filters" of that
+// correlation are the columns f = (c*stride + rho_h)*stride + rho_w, its channels the K channels
+// of dy; the window is cut into pieces of two and three taps (Sec. 4.1, eq. 8) and a tile of 2x2
+// window positions produces a 2*stride x 2*stride block of every channel of dx.
+constexpr int kBsMaxPieces = 4;  // pieces per dimension of the window (at most 11 taps)
+constexpr int kBsMaxSteps = 32;  // MFMA steps (four reduction rows each) per chunk of channels
+constexpr int kBsChunk = 8;      // channels of dy staged per chunk
+constexpr int kBsMaxSlots = 4;   // staged elements per thread and channel
+struct BwdSmallArgs {
+    int N, C, H, W, K, OH, OW, s;
+    int nf, ncb;                                // columns C*s*s, blocks of 16 columns
+    int Lh, Lw, nwh, nww;                       // window offset and taps per dimension
+    int nph, npw, npp;                          // pieces per dimension, pairs of pieces
+    int jh[kBsMaxPieces], lh[kBsMaxPieces];     // first tap and length of the pieces
+    int jw[kBsMaxPieces], lw[kBsMaxPieces];
+    int ra_h[8], re_h[8], rn_h[8];              // per residue: tap residue a, shift e, taps n (0: none)
+    int ra_w[8], re_w[8], rn_w[8];
+    int four;                                   // some piece has three taps: four frequencies per dimension
+    int TH, TW, BH, BW, nbh, nbw;               // tiles per image, block of tiles of a workgroup, blocks per image
+    int eff_pct;                                // lanes of a workgroup that hold a tile, in percent
+    int nrows, lw_in, lwp, row_floats, chan_floats, tile_row_step;  // staged region of one channel
+    int nchunks, steps;                         // chunks of kBsChunk channels, MFMA steps per chunk
+    int ne;                                     // staged elements per thread and channel
+    int xs_floats, us_floats;                   // LDS floats of one staged chunk of dy / of the filter copy
+    int so0[kBsMaxSteps], so1[kBsMaxSteps];     // per step of a chunk: LDS byte offset of patch column 0 / 1, row 0
+    FastDiv div_bw, div_lw;
+    size_t lds_bytes, u_floats;
+};
+
 // Several stride-1 sub-convolutions contracted in one launch (contract_batch.hip): their planes
 // are concatenated in one PlaneTable, their (K tile, T tile) grids in one grid.
 constexpr int kMaxBatch = 16;
@@ -288,6 +321,10 @@ bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish);
 // contract_batch.hip
 dwm_status_t launch_contract_batch(const BatchArgs& a, const PlaneTable& pt, int lc, const float* U, const float* V,
                                    float* y, void* stream);
+// setup.cpp / backward_small.hip: the single-kernel data gradient
+bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, BwdSmallArgs* out);
+dwm_status_t launch_bwd_small_filter(const BwdSmallArgs& a, int R, int S, const float* w, float* U, void* stream);
+dwm_status_t launch_bwd_small(const BwdSmallArgs& a, const float* dy, const float* U, float* dx, void* stream);
 // fused.hip
 bool fused_setup(const dwm_plan& p, FusedArgs* out);
 dwm_status_t launch_fused_filter(const dwm_plan& p, const float* w, float* U, void* stream);

@@ -187,4 +187,114 @@ bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish)
     return true;
 }
 
+// ---------------------------------------------------------------------------------
+// Single-kernel data gradient (few input channels): window, pieces, block of tiles, LDS
+// ---------------------------------------------------------------------------------
+// One dimension: residues of the dx coordinate modulo the stride, the common window of dy and
+// its cut into pieces of three and two taps (3,...,3 then 2 or 2,2: never a single tap).
+static bool bwd_small_dim(int R, int s, int P, int* ra, int* re, int* rn, int* L, int* nwin, int* np, int* pj, int* pl)
+{
+    bool any = false;
+    int lmax = 0, emax = 0;
+    for (int rho = 0; rho < s; ++rho) {
+        const int a = (rho + P) % s, e = (rho + P) / s;
+        const int n = a < R ? (R - a + s - 1) / s : 0;
+        ra[rho] = a; re[rho] = e; rn[rho] = n;
+        if (n == 0) continue;
+        if (!any || n - 1 - e > lmax) lmax = n - 1 - e;
+        if (!any || e > emax) emax = e;
+        any = true;
+    }
+    if (!any) return false;
+    *L = lmax;
+    const int n = emax + lmax + 1;
+    *nwin = n;
+    if (n < 2 || n > 11) return false;
+    int cnt = 0, j = 0, left = n;
+    while (left > 0) {
+        const int l = (left == 2 || left == 4) ? 2 : 3;
+        if (cnt >= kBsMaxPieces) return false;
+        pj[cnt] = j; pl[cnt] = l;
+        ++cnt; j += l; left -= l;
+    }
+    *np = cnt;
+    return true;
+}
+
+bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, BwdSmallArgs* out)
+{
+    BwdSmallArgs f{};
+    const int s = stride;
+    if (s < 1 || s > 8 || N < 1 || C < 1 || K < 1 || pad < 0 || pad > (1 << 20) || H > (1 << 20) || W > (1 << 20)) return false;
+    f.N = N; f.C = C; f.H = H; f.W = W; f.K = K; f.s = s;
+    f.OH = (H + 2 * pad - R) / s + 1;
+    f.OW = (W + 2 * pad - S) / s + 1;
+    if (f.OH < 1 || f.OW < 1) return false;
+    // one image of dy is addressed through a 32-bit buffer offset, dx through 32-bit pixel offsets
+    if ((long long)K * f.OH * f.OW * 4 >= (1LL << 31) || (long long)H * W >= (1LL << 29)) return false;
+    const long long nf = (long long)C * s * s;
+    if (nf > 256) return false;
+    f.nf = (int)nf;
+    f.ncb = (f.nf + 15) / 16;
+    if (!bwd_small_dim(R, s, pad, f.ra_h, f.re_h, f.rn_h, &f.Lh, &f.nwh, &f.nph, f.jh, f.lh)) return false;
+    if (!bwd_small_dim(S, s, pad, f.ra_w, f.re_w, f.rn_w, &f.Lw, &f.nww, &f.npw, f.jw, f.lw)) return false;
+    f.npp = f.nph * f.npw;
+    f.four = 0;
+    for (int i = 0; i < f.nph; ++i) f.four |= f.lh[i] == 3;
+    for (int i = 0; i < f.npw; ++i) f.four |= f.lw[i] == 3;
+    const int nfreq = f.four ? 4 : 3, planes = nfreq * nfreq;
+    f.steps = kBsChunk * f.npp / 4;
+    if (f.steps > kBsMaxSteps) return false;
+    f.nchunks = (K + kBsChunk - 1) / kBsChunk;
+    f.us_floats = (f.steps * planes * 64 + 255) / 256 * 256;  // whole 1 KB pieces: one DMA instruction of a wave each
+    const int th = (H + s - 1) / s, tw = (W + s - 1) / s;  // window positions per dimension
+    f.TH = (th + 1) / 2; f.TW = (tw + 1) / 2;
+    // the patch of a piece is read nfreq wide whatever its length
+    const int max_oh = f.jh[f.nph - 1] + nfreq - 1, max_ow = f.jw[f.npw - 1] + nfreq - 1;
+    const size_t budget = 150 * 1024;  // (two workgroups per CU where it is at most half of that)
+    double best_eff = 0.0;
+    long long best_x = 0;
+    for (int bw = 1; bw <= 64 && bw <= f.TW; ++bw) {
+        int bh = 64 / bw;
+        if (bh > f.TH) bh = f.TH;
+        if (bh < 1) continue;
+        const int nbh = (f.TH + bh - 1) / bh, nbw = (f.TW + bw - 1) / bw;
+        const double eff = (double)f.TH * f.TW / ((double)nbh * nbw * 64);
+        const long long nrows = 2LL * (bh - 1) + max_oh + 1;
+        const long long lw_in = 2LL * (bw - 1) + max_ow + 1;
+        const long long lwp = ((lw_in + 1) / 2) | 1;
+        const long long chan = nrows * 2 * lwp;
+        if (nrows * lw_in > 256LL * kBsMaxSlots) continue;
+        const long long xs = (kBsChunk * chan + 3) / 4 * 4;
+        if (2 * (xs + f.us_floats) * (long long)sizeof(float) > (long long)budget) continue;
+        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && xs < best_x)) {
+            best_eff = eff; best_x = xs;
+            f.BH = bh; f.BW = bw; f.nbh = nbh; f.nbw = nbw;
+            f.nrows = (int)nrows; f.lw_in = (int)lw_in; f.lwp = (int)lwp;
+        }
+    }
+    if (best_eff <= 0.0) return false;
+    f.eff_pct = (int)(best_eff * 100.0);
+    if ((long long)N * f.nbh * f.nbw > 0x7fffffffLL) return false;
+    f.row_floats = 2 * f.lwp;
+    f.chan_floats = f.nrows * f.row_floats;
+    f.tile_row_step = 2 * f.row_floats;
+    f.xs_floats = (int)best_x;
+    f.ne = (f.nrows * f.lw_in + 255) / 256;
+    f.div_bw.init((unsigned)f.BW);
+    f.div_lw.init((unsigned)f.lw_in);
+    // rows of a chunk: (pair of pieces, channel); a step takes four channels of one pair
+    for (int st = 0; st < f.steps; ++st) {
+        const int pp = st / (kBsChunk / 4), chq = st % (kBsChunk / 4);
+        const int jh = f.jh[pp / f.npw], jw = f.jw[pp % f.npw];
+        const int base = chq * 4 * f.chan_floats + jh * f.row_floats;
+        f.so0[st] = 4 * (base + (jw & 1) * f.lwp + (jw >> 1));
+        f.so1[st] = 4 * (base + ((jw + 1) & 1) * f.lwp + ((jw + 1) >> 1));
+    }
+    f.lds_bytes = 2 * ((size_t)f.xs_floats + f.us_floats) * sizeof(float);
+    f.u_floats = (size_t)f.ncb * f.nchunks * f.us_floats;
+    *out = f;
+    return true;
+}
+
 }  // namespace dwm

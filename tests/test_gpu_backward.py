@@ -18,8 +18,9 @@ TOL = 1e-4
 
 
 class BwdRunner:
-    def __init__(self, N, C, H, W, K, R, S, stride, pad):
+    def __init__(self, N, C, H, W, K, R, S, stride, pad, path=-1):
         self.plan = dwm.dwm_bwd_data_plan_create(N, C, H, W, K, R, S, stride, pad)
+        dwm.dwm_bwd_data_set_variant(self.plan, "path", path)
         dev = torch.device("cuda:0")
         self.Ugw = torch.full((dwm.dwm_bwd_data_filter_bytes(self.plan) // 4,), float("nan"), dtype=torch.float32, device=dev)
         self.ws = torch.full((max(dwm.dwm_bwd_data_workspace_bytes(self.plan) // 4, 64),), float("nan"),
@@ -79,12 +80,55 @@ SHAPES = [  # N, C, H, W, K, R, S, stride, pad
 ]
 
 
+def _single_kernel_applies(shape):
+    """Host-side question to the plan: can the whole gradient run as one kernel?"""
+    p = dwm.dwm_bwd_data_plan_create(*shape)
+    try:
+        dwm.dwm_bwd_data_set_variant(p, "path", 1)
+        return True
+    except dwm.DwmError:
+        return False
+    finally:
+        dwm.dwm_bwd_data_plan_destroy(p)
+
+
+SMALL_SHAPES = [sh for sh in SHAPES if _single_kernel_applies(sh)] + [
+    # stems: few input channels, many filters, the window of dy cut 2+2 / 3 / 3+2
+    (3, 3, 64, 64, 64, 7, 7, 2, 3),      # 4x4 window, nine planes, 12 columns, several chunks of channels
+    (2, 3, 67, 67, 96, 11, 11, 4, 0),    # 3x3 window, sixteen planes, three blocks of 16 columns, odd image
+    (2, 3, 67, 67, 20, 11, 11, 4, 2),    # padding shifts the residues: a 4-tap window for an 11-tap kernel
+    (2, 3, 50, 46, 13, 3, 3, 2, 1),      # 2x2 window: one pair of pieces, K not a multiple of the chunk
+    (1, 1, 33, 35, 9, 5, 5, 2, 2),       # one channel: 4 of 16 columns in use
+    (2, 4, 30, 30, 10, 9, 9, 3, 4),      # stride 3: the general scatter of the columns
+    (1, 3, 40, 40, 7, 6, 6, 1, 2),       # stride 1, six taps: 3+3
+    (1, 2, 26, 30, 5, 10, 10, 2, 3),     # ten taps, stride 2: a window of six
+    (2, 3, 45, 41, 11, 9, 9, 2, 4),      # nine taps, stride 2: a window of five, 3+2
+    (1, 8, 24, 24, 12, 6, 6, 2, 2),      # 32 columns
+    (2, 3, 9, 200, 6, 7, 7, 2, 3),       # a wide, flat image: blocks of one row of tiles
+    (600, 3, 12, 12, 5, 5, 5, 2, 2),     # more blocks than persistent workgroups: each takes several
+]
+
+
 @pytest.mark.parametrize("shape", SHAPES)
 def test_backward_data_matches_fp64_definition(shape):
+    """The sub-convolution form (the planner's choice where the layer has many channels)."""
     N, C, H, W, K, R, S, s, P = shape
     w, dy = _rand(*shape, seed=300 + R * 7 + S)
     ref = oracle.backward_data_f64(dy, w, (N, C, H, W), s, P)
-    r = BwdRunner(*shape)
+    r = BwdRunner(*shape, path=0)
+    dx = r.run(dy, w)
+    r.close()
+    assert np.all(np.isfinite(dx))  # every pixel written, the untouched ones as zeros
+    assert _relerr(dx, ref) <= TOL, shape
+
+
+@pytest.mark.parametrize("shape", SMALL_SHAPES)
+def test_backward_data_single_kernel_matches_fp64_definition(shape):
+    """The whole gradient as one stride-1 correlation of dy in one kernel."""
+    N, C, H, W, K, R, S, s, P = shape
+    w, dy = _rand(*shape, seed=900 + R * 7 + S)
+    ref = oracle.backward_data_f64(dy, w, (N, C, H, W), s, P)
+    r = BwdRunner(*shape, path=1)
     dx = r.run(dy, w)
     r.close()
     assert np.all(np.isfinite(dx))  # every pixel written, the untouched ones as zeros
@@ -132,7 +176,7 @@ def test_backward_data_benchmark_layers_full_size(index):
     OH, OW = wl.out_hw(L)
     dy = np.random.default_rng(3100 + index).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
     print("data gradient, whole image:", L.name, flush=True)
-    r = BwdRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    r = BwdRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)  # the planner's choice of path
     dx = r.run(dy, w)
     r.close()
     assert dx.shape == (L.N, L.C, L.H, L.W) and np.all(np.isfinite(dx))
