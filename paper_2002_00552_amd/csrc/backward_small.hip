@@ -11,7 +11,7 @@
 // the matrix unit where a sub-convolution per phase has 3.
 //
 // A workgroup (four waves) owns a block of tiles of one image and 16 columns; a wave owns 16 tiles.
-// The K channels of dy pass through LDS eight at a time, double buffered: while a chunk is
+// The K channels of dy pass through LDS 8, 16 or 32 at a time, double buffered: while a chunk is
 // multiplied, the next chunk's region of dy is on its way into registers and its slice of the
 // transformed filter into LDS (DMA).  Per step of four reduction rows (four channels of one pair
 // of pieces) a lane reads the patch of its (tile, channel) from LDS, applies B^T d B in registers
@@ -24,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "dma.hpp"
 #include "plan.hpp"
@@ -62,7 +63,7 @@ __host__ __device__ __forceinline__ int bs_upos(int planes, int plane, int lane)
 __global__ __launch_bounds__(256) void bwd_small_filter_kernel(BwdSmallArgs F, int R, int S, const float* __restrict__ w,
                                                                float* __restrict__ U)
 {
-    const int kpad = F.nchunks * kBsChunk;
+    const int kpad = F.nchunks * F.ck;
     const long long total = (long long)F.ncb * 16 * kpad * F.npp;
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(256) void bwd_small_filter_kernel(BwdSmallArgs F, i
 #pragma unroll
         for (int j = 0; j < 3; ++j) t[i][j] = bs_g_row(i, g[0][j], g[1][j], g[2][j]);
     const int nfreq = F.four ? 4 : 3, planes = nfreq * nfreq;
-    const int chunk = k / kBsChunk, row = pp * kBsChunk + (k % kBsChunk);
+    const int chunk = k / F.ck, row = pp * F.ck + (k % F.ck);
     const int step = row >> 2, lane = (row & 3) * 16 + (f & 15);
     float* dst = U + ((size_t)(f >> 4) * F.nchunks + chunk) * (size_t)F.us_floats + (size_t)step * (planes * 64);
 #pragma unroll
@@ -128,21 +129,27 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
 {
     constexpr int NF = FOUR ? 4 : 3, PL = NF * NF, G4 = PL / 4, REM = PL - 4 * G4;
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    // LDS: two staged chunks of dy [channel][row][column parity][lwp] | two chunks of the filter copy
+    // LDS: two staged chunks of dy [group of 4 channels][row][column parity][lwp][4 channels] | two chunks of
+    // the filter copy | per pair of pieces the byte offsets of patch column 0 and 1
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;  // LDS byte address of the array
     const uint32_t xs_bytes = (uint32_t)F.xs_floats * 4u, us_bytes = (uint32_t)F.us_floats * 4u;
-    const uint32_t us0 = 2u * xs_bytes;
+    const uint32_t us0 = 2u * xs_bytes, tab0 = us0 + 2u * us_bytes;
+    const char* ldsb = reinterpret_cast<const char*>(lds);
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int ln = lane & 15, lq = lane >> 4;
     const int tl = wave * 16 + ln;
     const int by = F.div_bw.div(tl), bx = tl - by * F.BW;
-    const uint32_t lane_base = 4u * (uint32_t)(lq * F.chan_floats + (by < F.BH ? by * F.tile_row_step + bx : 0));
-    const uint32_t row_bytes = (uint32_t)F.row_floats * 4u, chan_bytes = (uint32_t)F.chan_floats * 4u;
+    // a lane reads channel lq of a group's element: 16 bytes per element, four bytes per channel
+    const uint32_t lane_base = 16u * (uint32_t)(by < F.BH ? by * F.tile_row_step + bx : 0) + 4u * (uint32_t)lq;
+    const uint32_t row_bytes = (uint32_t)F.row_elems * 16u, group_bytes = (uint32_t)F.group_elems * 16u;
     const size_t img = (size_t)F.OH * F.OW;
     const int region = F.nrows * F.lw_in;
-    const char* ldsb = reinterpret_cast<const char*>(lds);
+    const int G = 1 << F.glog, NE = 1 << F.nelog;
+
+    if (tid < F.npp) reinterpret_cast<int2*>(lds + (tab0 >> 2))[tid] = make_int2(F.po0[tid], F.po1[tid]);
+    // (the first barrier below comes before any wave reads the table)
 
     const int nblocks = F.N * F.nbh * F.nbw;
     for (int b = blockIdx.x; b < nblocks; b += gridDim.x) {
@@ -151,42 +158,47 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
         const int ty = ty0 + by, tx = tx0 + bx;
         const bool tile_ok = by < F.BH && ty < F.TH && tx < F.TW;
 
-        // what this thread stages of every channel: up to kBsMaxSlots elements of the block's region of
-        // dy; positions outside the image get an offset past the buffer's end, which reads as zero
+        // What this thread stages of every chunk: slot gs = (group gs >> nelog of the chunk, element
+        // tid + 256 * (gs & (NE - 1)) of the block's region of dy), four channels each.  Positions outside the
+        // image get an offset past the buffer's end, which reads as zero.
         uint32_t goff[kBsMaxSlots];
         int loff[kBsMaxSlots];
 #pragma unroll
-        for (int e = 0; e < kBsMaxSlots; ++e) {
-            const int idx = tid + 256 * e;
+        for (int gs = 0; gs < kBsMaxSlots; ++gs) {
+            const int idx = tid + 256 * (gs & (NE - 1));
             const int r = F.div_lw.div(idx), c = idx - r * F.lw_in;
             const int row = 2 * ty0 - F.Lh + r, col = 2 * tx0 - F.Lw + c;
             const bool inb = idx < region && row >= 0 && row < F.OH && col >= 0 && col < F.OW;
-            goff[e] = inb ? (uint32_t)(row * F.OW + col) * 4u : 0x80000000u;
-            loff[e] = idx < region ? 4 * (r * F.row_floats + (c & 1) * F.lwp + (c >> 1)) : -1;
+            goff[gs] = inb ? (uint32_t)(row * F.OW + col) * 4u : 0x80000000u;
+            loff[gs] = idx < region && gs < (G << F.nelog)
+                           ? (int)((uint32_t)(gs >> F.nelog) * group_bytes) + 16 * (r * F.row_elems + (c & 1) * F.lwp + (c >> 1))
+                           : -1;
         }
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float*>(dy + (size_t)n * F.K * img), 0, (int)((size_t)F.K * img * 4), 0x00020000);
 
-        float sv[kBsChunk][kBsMaxSlots];
+        bs_float4 sv[kBsMaxSlots];
         auto stage_load = [&](int chunk) {  // chunk's region of dy -> registers
+            const int k0 = chunk * F.ck;
 #pragma unroll
-            for (int ch = 0; ch < kBsChunk; ++ch) {
-                const int k = chunk * kBsChunk + ch;
-                const uint32_t koff = k < F.K ? 0u : 0x80000000u;  // channels past K: zeros
-                const uint32_t soff = (uint32_t)((size_t)min(k, F.K - 1) * img * 4);
+            for (int gs = 0; gs < kBsMaxSlots; ++gs) {
+                if (gs < (G << F.nelog)) {
+                    const int g = gs >> F.nelog;
 #pragma unroll
-                for (int e = 0; e < kBsMaxSlots; ++e)
-                    if (e < F.ne) sv[ch][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, goff[e] | koff, soff, 0));
+                    for (int j = 0; j < 4; ++j) {
+                        const int k = k0 + 4 * g + j;
+                        const uint32_t koff = k < F.K ? 0u : 0x80000000u;  // channels past K: zeros
+                        const uint32_t soff = (uint32_t)((size_t)min(k, F.K - 1) * img * 4);
+                        sv[gs][j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, goff[gs] | koff, soff, 0));
+                    }
+                }
             }
         };
-        auto stage_write = [&](int buf) {  // registers -> LDS
-            float* xb = lds + buf * F.xs_floats;
+        auto stage_write = [&](int buf) {  // registers -> LDS, four channels of an element at a time
+            char* xb = reinterpret_cast<char*>(lds) + (uint32_t)buf * xs_bytes;
 #pragma unroll
-            for (int ch = 0; ch < kBsChunk; ++ch)
-#pragma unroll
-                for (int e = 0; e < kBsMaxSlots; ++e)
-                    if (e < F.ne && loff[e] >= 0)
-                        *reinterpret_cast<float*>(reinterpret_cast<char*>(xb) + (uint32_t)loff[e] + (uint32_t)ch * chan_bytes) = sv[ch][e];
+            for (int gs = 0; gs < kBsMaxSlots; ++gs)
+                if (gs < (G << F.nelog) && loff[gs] >= 0) *reinterpret_cast<bs_float4*>(xb + (uint32_t)loff[gs]) = sv[gs];
         };
 
         for (int cb = 0; cb < F.ncb; ++cb) {
@@ -222,22 +234,25 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
                 const char* ub = ldsb + us0 + (uint32_t)buf * us_bytes + (uint32_t)lane * 16u;
                 const char* ur = ldsb + us0 + (uint32_t)buf * us_bytes + (uint32_t)(G4 * 1024) + (uint32_t)lane * 4u;
 
-                auto read_patch = [&](int st, float (&d)[NF][NF]) {
-                    const char* p0 = xb + F.so0[st];
-                    const char* p1 = xb + F.so1[st];
+                // step st of a chunk = (pair of pieces st >> glog, group st & (G - 1))
+                auto read_tab = [&](int st) {
+                    return *reinterpret_cast<const int2*>(ldsb + tab0 + (uint32_t)(st >> F.glog) * 8u);
+                };
+                auto read_patch = [&](int st, int2 t, float (&d)[NF][NF]) {
+                    const uint32_t go = (uint32_t)(st & (G - 1)) * group_bytes;
+                    const char* p0 = xb + go + (uint32_t)t.x;
+                    const char* p1 = xb + go + (uint32_t)t.y;
 #pragma unroll
                     for (int i = 0; i < NF; ++i) {
                         const float* q0 = reinterpret_cast<const float*>(p0 + (uint32_t)i * row_bytes);
                         const float* q1 = reinterpret_cast<const float*>(p1 + (uint32_t)i * row_bytes);
                         d[i][0] = q0[0];
-                        d[i][2] = q0[1];
+                        d[i][2] = q0[4];  // two columns on: the next element of the same parity
                         d[i][1] = q1[0];
-                        if constexpr (FOUR) d[i][3] = q1[1];
+                        if constexpr (FOUR) d[i][3] = q1[4];
                     }
                 };
-                auto step = [&](int st, const float (&d)[NF][NF], float (&dn)[NF][NF], bool next) {
-                    // A operands of this step
-                    float a[PL];
+                auto read_a = [&](int st, float (&a)[PL]) {
                     const char* us = ub + (uint32_t)st * (uint32_t)(PL * 256);
 #pragma unroll
                     for (int g = 0; g < G4; ++g) {
@@ -247,7 +262,15 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
 #pragma unroll
                     for (int r = 0; r < REM; ++r)
                         a[4 * G4 + r] = *reinterpret_cast<const float*>(ur + (uint32_t)st * (uint32_t)(PL * 256) + r * 256);
-                    if (next) read_patch(st + 1, dn);
+                };
+                // operands (patch and A) travel a step ahead; the two steps of a loop pass share their pair of
+                // pieces (the groups of a chunk: a power of two >= 2), whose table entry is read a pass ahead
+                auto step = [&](auto next_tag, int st, const float (&d)[NF][NF], float (&dn)[NF][NF], const float (&a)[PL],
+                                float (&an)[PL], int2 t) {
+                    if constexpr (decltype(next_tag)::value) {
+                        read_a(st + 1, an);
+                        read_patch(st + 1, t, dn);
+                    }
                     float tmp[NF][NF], v[NF][NF];
 #pragma unroll
                     for (int j = 0; j < NF; ++j) {
@@ -267,12 +290,19 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
                             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i * NF + j], v[i][j], acc[i][j], 0, 0, 0);
                 };
 
-                float d0[NF][NF], d1[NF][NF];
-                read_patch(0, d0);
-                for (int st = 0; st < F.steps; st += 2) {  // steps per chunk: a multiple of two
-                    step(st, d0, d1, true);
-                    step(st + 1, d1, d0, st + 2 < F.steps);
+                float d0[NF][NF], d1[NF][NF], a0[PL], a1[PL];
+                int2 tc = read_tab(0);
+                read_a(0, a0);
+                read_patch(0, tc, d0);
+                int st = 0;
+                for (; st + 2 < F.steps; st += 2) {  // steps per chunk: a multiple of two
+                    const int2 tn = read_tab(st + 2);
+                    step(std::true_type{}, st, d0, d1, a0, a1, tc);
+                    step(std::true_type{}, st + 1, d1, d0, a1, a0, tn);
+                    tc = tn;
                 }
+                step(std::true_type{}, st, d0, d1, a0, a1, tc);
+                step(std::false_type{}, st + 1, d1, d0, a1, a0, tc);
                 if (more) {
                     wait_vmcnt<0>();
                     stage_write(buf ^ 1);
@@ -370,7 +400,7 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
 
 dwm_status_t launch_bwd_small_filter(const BwdSmallArgs& a, int R, int S, const float* w, float* U, void* stream)
 {
-    const long long total = (long long)a.ncb * 16 * a.nchunks * kBsChunk * a.npp;
+    const long long total = (long long)a.ncb * 16 * a.nchunks * a.ck * a.npp;
     if (total > 0x7fffffffLL * 256) return DWM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(bwd_small_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a,
                        R, S, w, U);

@@ -216,9 +216,8 @@ struct InLdsArgs {
 // of dy; the window is cut into pieces of two and three taps (Sec. 4.1, eq. 8) and a tile of 2x2
 // window positions produces a 2*stride x 2*stride block of every channel of dx.
 constexpr int kBsMaxPieces = 4;  // pieces per dimension of the window (at most 11 taps)
-constexpr int kBsMaxSteps = 32;  // MFMA steps (four reduction rows each) per chunk of channels
-constexpr int kBsChunk = 8;      // channels of dy staged per chunk
-constexpr int kBsMaxSlots = 4;   // staged elements per thread and channel
+constexpr int kBsMaxPairs = kBsMaxPieces * kBsMaxPieces;
+constexpr int kBsMaxSlots = 8;   // (group of four channels, staged element) pairs per thread and chunk
 struct BwdSmallArgs {
     int N, C, H, W, K, OH, OW, s;
     int nf, ncb;                                // columns C*s*s, blocks of 16 columns
@@ -231,11 +230,13 @@ struct BwdSmallArgs {
     int four;                                   // some piece has three taps: four frequencies per dimension
     int TH, TW, BH, BW, nbh, nbw;               // tiles per image, block of tiles of a workgroup, blocks per image
     int eff_pct;                                // lanes of a workgroup that hold a tile, in percent
-    int nrows, lw_in, lwp, row_floats, chan_floats, tile_row_step;  // staged region of one channel
-    int nchunks, steps;                         // chunks of kBsChunk channels, MFMA steps per chunk
-    int ne;                                     // staged elements per thread and channel
+    // staged region of dy, per group of four channels: [row][column parity][lwp] elements of four floats
+    int nrows, lw_in, lwp, row_elems, group_elems, tile_row_step;
+    int glog, ck;                               // a chunk is 2^glog groups = ck channels of dy
+    int nchunks, steps;                         // chunks, MFMA steps per chunk = pairs * groups
+    int nelog;                                  // a thread stages 2^nelog elements of every group
     int xs_floats, us_floats;                   // LDS floats of one staged chunk of dy / of the filter copy
-    int so0[kBsMaxSteps], so1[kBsMaxSteps];     // per step of a chunk: LDS byte offset of patch column 0 / 1, row 0
+    int po0[kBsMaxPairs], po1[kBsMaxPairs];     // per pair of pieces: LDS byte offset of patch column 0 / 1, row 0
     FastDiv div_bw, div_lw;
     size_t lds_bytes, u_floats;
 };

@@ -243,17 +243,28 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
     for (int i = 0; i < f.nph; ++i) f.four |= f.lh[i] == 3;
     for (int i = 0; i < f.npw; ++i) f.four |= f.lw[i] == 3;
     const int nfreq = f.four ? 4 : 3, planes = nfreq * nfreq;
-    f.steps = kBsChunk * f.npp / 4;
-    if (f.steps > kBsMaxSteps) return false;
-    f.nchunks = (K + kBsChunk - 1) / kBsChunk;
-    f.us_floats = (f.steps * planes * 64 + 255) / 256 * 256;  // whole 1 KB pieces: one DMA instruction of a wave each
     const int th = (H + s - 1) / s, tw = (W + s - 1) / s;  // window positions per dimension
     f.TH = (th + 1) / 2; f.TW = (tw + 1) / 2;
     // the patch of a piece is read nfreq wide whatever its length
     const int max_oh = f.jh[f.nph - 1] + nfreq - 1, max_ow = f.jw[f.npw - 1] + nfreq - 1;
-    const size_t budget = 150 * 1024;  // (two workgroups per CU where it is at most half of that)
+    // LDS words (mod 64 = banks) the lanes of a wave read together: lane (tile, q) reads word
+    // 4*(element of its tile) + q; the worst multiplicity of a bank over the four waves
+    auto conflicts = [&](int bw, int bh, int lwp) {
+        int worst = 0;
+        for (int wave = 0; wave < 4; ++wave) {
+            int cnt[64] = {0};
+            for (int n = 0; n < 16; ++n) {
+                const int tl = wave * 16 + n, by = tl / bw, bx = tl % bw;
+                const int el = by < bh ? by * 4 * lwp + bx : 0;
+                for (int q = 0; q < 4; ++q) worst = std::max(worst, ++cnt[(4 * el + q) & 63]);
+            }
+        }
+        return worst;
+    };
+    // block of tiles: most useful lanes first, then the cheapest staged region; the chunk of channels is the
+    // largest (8, 16 or 32) with which two workgroups fit a CU, else 8
     double best_eff = 0.0;
-    long long best_x = 0;
+    long long best_x = 0, best_cost = 0;
     for (int bw = 1; bw <= 64 && bw <= f.TW; ++bw) {
         int bh = 64 / bw;
         if (bh > f.TH) bh = f.TH;
@@ -262,36 +273,57 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
         const double eff = (double)f.TH * f.TW / ((double)nbh * nbw * 64);
         const long long nrows = 2LL * (bh - 1) + max_oh + 1;
         const long long lw_in = 2LL * (bw - 1) + max_ow + 1;
-        const long long lwp = ((lw_in + 1) / 2) | 1;
-        const long long chan = nrows * 2 * lwp;
-        if (nrows * lw_in > 256LL * kBsMaxSlots) continue;
-        const long long xs = (kBsChunk * chan + 3) / 4 * 4;
-        if (2 * (xs + f.us_floats) * (long long)sizeof(float) > (long long)budget) continue;
-        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && xs < best_x)) {
-            best_eff = eff; best_x = xs;
+        if (nrows * lw_in > 256LL * kBsMaxSlots / 2) continue;
+        int nelog = 0;
+        while ((256LL << nelog) < nrows * lw_in) ++nelog;
+        // the largest chunk first; for it, the row padding with the fewest bank conflicts that still fits
+        const long long lwp0 = (lw_in + 1) / 2;
+        long long lwp = lwp0, group = 0;
+        int glog = -1;
+        for (int g = 3; g >= 1 && glog < 0; --g) {
+            if ((1 << g) << nelog > kBsMaxSlots) continue;
+            const long long us = ((long long)(f.npp << g) * planes * 64 + 255) / 256 * 256;
+            int best_c = 1 << 30;
+            for (long long l = lwp0; l < lwp0 + 4; ++l) {
+                const long long grp = nrows * 2 * l;  // elements of four floats
+                const long long bytes = 2 * ((grp << g) * 4 + us) * (long long)sizeof(float);
+                if (bytes > (g > 1 ? 79 : 150) * 1024) continue;
+                const int c = conflicts(bw, bh, (int)l);
+                if (c < best_c) { best_c = c; lwp = l; group = grp; glog = g; }
+            }
+        }
+        if (glog < 0) continue;
+        const long long xs = (group << glog) * 4;
+        // among equally full blocks: the least to load, a row of the region counted 16 elements longer than
+        // it is (short rows waste most of the memory transactions that fetch them)
+        const long long cost = nrows * (lw_in + 16);
+        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && cost < best_cost)) {
+            best_eff = eff; best_x = xs; best_cost = cost;
             f.BH = bh; f.BW = bw; f.nbh = nbh; f.nbw = nbw;
             f.nrows = (int)nrows; f.lw_in = (int)lw_in; f.lwp = (int)lwp;
+            f.glog = glog; f.nelog = nelog;
         }
     }
     if (best_eff <= 0.0) return false;
     f.eff_pct = (int)(best_eff * 100.0);
     if ((long long)N * f.nbh * f.nbw > 0x7fffffffLL) return false;
-    f.row_floats = 2 * f.lwp;
-    f.chan_floats = f.nrows * f.row_floats;
-    f.tile_row_step = 2 * f.row_floats;
+    f.ck = 4 << f.glog;
+    f.steps = f.npp << f.glog;
+    f.nchunks = (K + f.ck - 1) / f.ck;
+    f.us_floats = (f.steps * planes * 64 + 255) / 256 * 256;  // whole 1 KB pieces: one DMA instruction of a wave each
+    f.row_elems = 2 * f.lwp;
+    f.group_elems = f.nrows * f.row_elems;
+    f.tile_row_step = 2 * f.row_elems;
     f.xs_floats = (int)best_x;
-    f.ne = (f.nrows * f.lw_in + 255) / 256;
     f.div_bw.init((unsigned)f.BW);
     f.div_lw.init((unsigned)f.lw_in);
-    // rows of a chunk: (pair of pieces, channel); a step takes four channels of one pair
-    for (int st = 0; st < f.steps; ++st) {
-        const int pp = st / (kBsChunk / 4), chq = st % (kBsChunk / 4);
+    for (int pp = 0; pp < f.npp; ++pp) {
         const int jh = f.jh[pp / f.npw], jw = f.jw[pp % f.npw];
-        const int base = chq * 4 * f.chan_floats + jh * f.row_floats;
-        f.so0[st] = 4 * (base + (jw & 1) * f.lwp + (jw >> 1));
-        f.so1[st] = 4 * (base + ((jw + 1) & 1) * f.lwp + ((jw + 1) >> 1));
+        f.po0[pp] = 16 * (jh * f.row_elems + (jw & 1) * f.lwp + (jw >> 1));
+        f.po1[pp] = 16 * (jh * f.row_elems + ((jw + 1) & 1) * f.lwp + ((jw + 1) >> 1));
     }
-    f.lds_bytes = 2 * ((size_t)f.xs_floats + f.us_floats) * sizeof(float);
+    // LDS: two staged chunks of dy, two chunks of the filter copy, the table of patch offsets
+    f.lds_bytes = 2 * ((size_t)f.xs_floats + f.us_floats) * sizeof(float) + kBsMaxPairs * 8;
     f.u_floats = (size_t)f.ncb * f.nchunks * f.us_floats;
     *out = f;
     return true;
