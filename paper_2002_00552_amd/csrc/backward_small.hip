@@ -123,13 +123,14 @@ __device__ __forceinline__ void bs_at(const bs_float4 (&m)[NF], bs_float4 (&o)[2
     if constexpr (NF == 4) o[1] -= m[3];
 }
 
+// (nine planes: registers for three waves per SIMD; sixteen: two)
 template <bool FOUR>
-__global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const float* __restrict__ dy,
+__global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallArgs F, const float* __restrict__ dy,
                                                            const float* __restrict__ U, float* __restrict__ dx)
 {
     constexpr int NF = FOUR ? 4 : 3, PL = NF * NF, G4 = PL / 4, REM = PL - 4 * G4;
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    // LDS: two staged chunks of dy [group of 4 channels][row][column parity][lwp][4 channels] | two chunks of
+    // LDS: two staged chunks of dy [group of 4 channels][channel pair][row][column parity][lwp][2 channels] | two chunks of
     // the filter copy | per pair of pieces the byte offsets of patch column 0 and 1
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;  // LDS byte address of the array
     const uint32_t xs_bytes = (uint32_t)F.xs_floats * 4u, us_bytes = (uint32_t)F.us_floats * 4u;
@@ -141,9 +142,11 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
     const int ln = lane & 15, lq = lane >> 4;
     const int tl = wave * 16 + ln;
     const int by = F.div_bw.div(tl), bx = tl - by * F.BW;
-    // a lane reads channel lq of a group's element: 16 bytes per element, four bytes per channel
-    const uint32_t lane_base = 16u * (uint32_t)(by < F.BH ? by * F.tile_row_step + bx : 0) + 4u * (uint32_t)lq;
-    const uint32_t row_bytes = (uint32_t)F.row_elems * 16u, group_bytes = (uint32_t)F.group_elems * 16u;
+    // a lane reads channel lq of a group: plane lq >> 1 of the group, 8 bytes per element, channel lq & 1 of it
+    const uint32_t row_bytes = (uint32_t)F.row_elems * 8u, pair_bytes = (uint32_t)F.group_elems * 8u;
+    const uint32_t group_bytes = 2u * pair_bytes;
+    const uint32_t lane_base = 8u * (uint32_t)(by < F.BH ? by * F.tile_row_step + bx : 0) + 4u * (uint32_t)(lq & 1) +
+                               (uint32_t)(lq >> 1) * pair_bytes;
     const size_t img = (size_t)F.OH * F.OW;
     const int region = F.nrows * F.lw_in;
     const int G = 1 << F.glog, NE = 1 << F.nelog;
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
             const bool inb = idx < region && row >= 0 && row < F.OH && col >= 0 && col < F.OW;
             goff[gs] = inb ? (uint32_t)(row * F.OW + col) * 4u : 0x80000000u;
             loff[gs] = idx < region && gs < (G << F.nelog)
-                           ? (int)((uint32_t)(gs >> F.nelog) * group_bytes) + 16 * (r * F.row_elems + (c & 1) * F.lwp + (c >> 1))
+                           ? (int)((uint32_t)(gs >> F.nelog) * group_bytes) + 8 * (r * F.row_elems + (c & 1) * F.lwp + (c >> 1))
                            : -1;
         }
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -194,11 +197,14 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
                 }
             }
         };
-        auto stage_write = [&](int buf) {  // registers -> LDS, four channels of an element at a time
+        auto stage_write = [&](int buf) {  // registers -> LDS, the two channels of a pair at a time
             char* xb = reinterpret_cast<char*>(lds) + (uint32_t)buf * xs_bytes;
 #pragma unroll
             for (int gs = 0; gs < kBsMaxSlots; ++gs)
-                if (gs < (G << F.nelog) && loff[gs] >= 0) *reinterpret_cast<bs_float4*>(xb + (uint32_t)loff[gs]) = sv[gs];
+                if (gs < (G << F.nelog) && loff[gs] >= 0) {
+                    *reinterpret_cast<float2*>(xb + (uint32_t)loff[gs]) = make_float2(sv[gs][0], sv[gs][1]);
+                    *reinterpret_cast<float2*>(xb + (uint32_t)loff[gs] + pair_bytes) = make_float2(sv[gs][2], sv[gs][3]);
+                }
         };
 
         for (int cb = 0; cb < F.ncb; ++cb) {
@@ -222,6 +228,7 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
             wait_vmcnt<0>();
             stage_write(0);
             __syncthreads();
+            const int2 tab_first = *reinterpret_cast<const int2*>(ldsb + tab0);  // every chunk starts with it
 
             for (int ci = 0; ci < F.nchunks; ++ci) {
                 const int buf = ci & 1;
@@ -247,9 +254,9 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
                         const float* q0 = reinterpret_cast<const float*>(p0 + (uint32_t)i * row_bytes);
                         const float* q1 = reinterpret_cast<const float*>(p1 + (uint32_t)i * row_bytes);
                         d[i][0] = q0[0];
-                        d[i][2] = q0[4];  // two columns on: the next element of the same parity
+                        d[i][2] = q0[2];  // two columns on: the next element of the same parity
                         d[i][1] = q1[0];
-                        if constexpr (FOUR) d[i][3] = q1[4];
+                        if constexpr (FOUR) d[i][3] = q1[2];
                     }
                 };
                 auto read_a = [&](int st, float (&a)[PL]) {
@@ -263,8 +270,7 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
                     for (int r = 0; r < REM; ++r)
                         a[4 * G4 + r] = *reinterpret_cast<const float*>(ur + (uint32_t)st * (uint32_t)(PL * 256) + r * 256);
                 };
-                // operands (patch and A) travel a step ahead; the two steps of a loop pass share their pair of
-                // pieces (the groups of a chunk: a power of two >= 2), whose table entry is read a pass ahead
+                // operands (patch and A) travel a step ahead, the table entries of their pairs of pieces a pass ahead
                 auto step = [&](auto next_tag, int st, const float (&d)[NF][NF], float (&dn)[NF][NF], const float (&a)[PL],
                                 float (&an)[PL], int2 t) {
                     if constexpr (decltype(next_tag)::value) {
@@ -291,18 +297,18 @@ __global__ __launch_bounds__(256, 2) void bwd_small_kernel(BwdSmallArgs F, const
                 };
 
                 float d0[NF][NF], d1[NF][NF], a0[PL], a1[PL];
-                int2 tc = read_tab(0);
+                int2 t1 = read_tab(1);
                 read_a(0, a0);
-                read_patch(0, tc, d0);
+                read_patch(0, tab_first, d0);
                 int st = 0;
                 for (; st + 2 < F.steps; st += 2) {  // steps per chunk: a multiple of two
-                    const int2 tn = read_tab(st + 2);
-                    step(std::true_type{}, st, d0, d1, a0, a1, tc);
-                    step(std::true_type{}, st + 1, d1, d0, a1, a0, tn);
-                    tc = tn;
+                    const int2 t2 = read_tab(st + 2), t3 = read_tab(st + 3);
+                    step(std::true_type{}, st, d0, d1, a0, a1, t1);
+                    step(std::true_type{}, st + 1, d1, d0, a1, a0, t2);
+                    t1 = t3;
                 }
-                step(std::true_type{}, st, d0, d1, a0, a1, tc);
-                step(std::false_type{}, st + 1, d1, d0, a1, a0, tc);
+                step(std::true_type{}, st, d0, d1, a0, a1, t1);
+                step(std::false_type{}, st + 1, d1, d0, a1, a0, t1);
                 if (more) {
                     wait_vmcnt<0>();
                     stage_write(buf ^ 1);
@@ -420,9 +426,10 @@ dwm_status_t launch_bwd_small(const BwdSmallArgs& a, const float* dy, const floa
         }();
         if (attr != hipSuccess) return DWM_ERR_HIP;
     }
-    // persistent workgroups, two per CU (fewer where there are fewer blocks)
+    // persistent workgroups, as many per CU as fit (fewer where there are fewer blocks)
     const long long nblocks = (long long)a.N * a.nbh * a.nbw;
-    dim3 grid((unsigned)std::min<long long>(nblocks, 2 * kNumCUs)), block(256);
+    const int per_cu = a.four ? 2 : std::max(1, std::min(3, (int)(156 * 1024 / a.lds_bytes)));
+    dim3 grid((unsigned)std::min<long long>(nblocks, per_cu * kNumCUs)), block(256);
     hipLaunchKernelGGL(kernel, grid, block, a.lds_bytes, (hipStream_t)stream, a, dy, U, dx);
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;
 }

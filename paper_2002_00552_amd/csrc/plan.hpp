@@ -230,7 +230,8 @@ struct BwdSmallArgs {
     int four;                                   // some piece has three taps: four frequencies per dimension
     int TH, TW, BH, BW, nbh, nbw;               // tiles per image, block of tiles of a workgroup, blocks per image
     int eff_pct;                                // lanes of a workgroup that hold a tile, in percent
-    // staged region of dy, per group of four channels: [row][column parity][lwp] elements of four floats
+    // staged region of dy, per group of four channels: two planes (channel pairs) of [row][column parity][lwp]
+    // elements of two floats
     int nrows, lw_in, lwp, row_elems, group_elems, tile_row_step;
     int glog, ck;                               // a chunk is 2^glog groups = ck channels of dy
     int nchunks, steps;                         // chunks, MFMA steps per chunk = pairs * groups

@@ -247,16 +247,18 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
     f.TH = (th + 1) / 2; f.TW = (tw + 1) / 2;
     // the patch of a piece is read nfreq wide whatever its length
     const int max_oh = f.jh[f.nph - 1] + nfreq - 1, max_ow = f.jw[f.npw - 1] + nfreq - 1;
-    // LDS words (mod 64 = banks) the lanes of a wave read together: lane (tile, q) reads word
-    // 4*(element of its tile) + q; the worst multiplicity of a bank over the four waves
+    // Bank conflicts of a patch read: LDS serves 32 lanes a cycle from 32 banks of four bytes.  A group of
+    // four channels is staged as two planes of channel pairs, [element][2]; the lanes of half a wave are
+    // 16 tiles x the two channels of one pair and read word 2*(element of the tile) + (channel & 1).
+    // Returns the worst multiplicity of a bank over the four waves.
     auto conflicts = [&](int bw, int bh, int lwp) {
         int worst = 0;
         for (int wave = 0; wave < 4; ++wave) {
-            int cnt[64] = {0};
+            int cnt[32] = {0};
             for (int n = 0; n < 16; ++n) {
                 const int tl = wave * 16 + n, by = tl / bw, bx = tl % bw;
                 const int el = by < bh ? by * 4 * lwp + bx : 0;
-                for (int q = 0; q < 4; ++q) worst = std::max(worst, ++cnt[(4 * el + q) & 63]);
+                for (int q = 0; q < 2; ++q) worst = std::max(worst, ++cnt[(2 * el + q) & 31]);
             }
         }
         return worst;
@@ -280,14 +282,17 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
         const long long lwp0 = (lw_in + 1) / 2;
         long long lwp = lwp0, group = 0;
         int glog = -1;
-        for (int g = 3; g >= 1 && glog < 0; --g) {
-            if ((1 << g) << nelog > kBsMaxSlots) continue;
+        // (nine planes leave registers for three waves per SIMD: three workgroups per CU, 52 KB each;
+        // sixteen planes: two, 79 KB each; a chunk of four channels only with an even number of steps)
+        const int wg_kb = f.four ? 79 : 52;
+        for (int g = 3; g >= 0 && glog < 0; --g) {
+            if ((1 << g) << nelog > kBsMaxSlots || ((f.npp << g) & 1)) continue;
             const long long us = ((long long)(f.npp << g) * planes * 64 + 255) / 256 * 256;
             int best_c = 1 << 30;
             for (long long l = lwp0; l < lwp0 + 4; ++l) {
                 const long long grp = nrows * 2 * l;  // elements of four floats
                 const long long bytes = 2 * ((grp << g) * 4 + us) * (long long)sizeof(float);
-                if (bytes > (g > 1 ? 79 : 150) * 1024) continue;
+                if (bytes > (g > (f.npp & 1) ? wg_kb : 150) * 1024) continue;
                 const int c = conflicts(bw, bh, (int)l);
                 if (c < best_c) { best_c = c; lwp = l; group = grp; glog = g; }
             }
@@ -319,8 +324,8 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
     f.div_lw.init((unsigned)f.lw_in);
     for (int pp = 0; pp < f.npp; ++pp) {
         const int jh = f.jh[pp / f.npw], jw = f.jw[pp % f.npw];
-        f.po0[pp] = 16 * (jh * f.row_elems + (jw & 1) * f.lwp + (jw >> 1));
-        f.po1[pp] = 16 * (jh * f.row_elems + ((jw + 1) & 1) * f.lwp + ((jw + 1) >> 1));
+        f.po0[pp] = 8 * (jh * f.row_elems + (jw & 1) * f.lwp + (jw >> 1));
+        f.po1[pp] = 8 * (jh * f.row_elems + ((jw + 1) & 1) * f.lwp + ((jw + 1) >> 1));
     }
     // LDS: two staged chunks of dy, two chunks of the filter copy, the table of patch offsets
     f.lds_bytes = 2 * ((size_t)f.xs_floats + f.us_floats) * sizeof(float) + kBsMaxPairs * 8;
