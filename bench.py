@@ -92,8 +92,9 @@ def cpu_baseline(x, w, L, target_s=12.0):
 
 
 def bench_backward_data(args, L, x, w):
-    """A step = one dwm_conv_backward_data (stride^2 stride-1 sub-convolutions of dy) on resident
-    buffers; the filter transform of the flipped, phase-split weights runs once before."""
+    """A step = one dwm_conv_backward_data on resident buffers (stride^2 stride-1 sub-convolutions of
+    dy, or one kernel for layers with few input channels: --bwd-path 0 / 1 forces either); the
+    filter transform of the flipped, phase-split weights runs once before."""
     import numpy as np
     import torch
 
@@ -103,7 +104,12 @@ def bench_backward_data(args, L, x, w):
     OH, OW = wl.out_hw(L)
     dy = np.random.default_rng(3100).uniform(-1, 1, (L.N, L.K, OH, OW)).astype(np.float32)
     plan = dwm.dwm_bwd_data_plan_create(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
+    try:
+        dwm.dwm_bwd_data_set_variant(plan, "path", args.bwd_path)
+    except dwm.DwmError:
+        raise SystemExit("bench.py: --bwd-path %d does not apply to %s" % (args.bwd_path, L.name))
     info = dwm.dwm_bwd_data_plan_info(plan)
+    single = bool(info.single_kernel)
     dyd, wd = torch.from_numpy(dy).cuda(), torch.from_numpy(w).cuda()
     U = torch.empty(dwm.dwm_bwd_data_filter_bytes(plan) // 4, dtype=torch.float32, device="cuda")
     ws = torch.empty(max(dwm.dwm_bwd_data_workspace_bytes(plan) // 4, 64), dtype=torch.float32, device="cuda")
@@ -125,8 +131,9 @@ def bench_backward_data(args, L, x, w):
         "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": L.name + "_backward_data", "phases": info.n_phases, "subconvs": info.n_subconvs,
+                   "path": "single kernel" if single else "sub-convolutions",
                    "direct_GFLOP": info.direct_flops / 1e9, "winograd_GFLOP": info.winograd_flops / 1e9},
-        "roofline": {"kernel": "all sub-convolutions", "bound": "mfma", "achieved": info.winograd_flops / dt / 1e12,
+        "roofline": {"kernel": "bwd_small_kernel" if single else "all sub-convolutions", "bound": "mfma", "achieved": info.winograd_flops / dt / 1e12,
                      "peak": PEAK_MFMA_F32, "unit": "TFLOP/s", "frac": info.winograd_flops / dt / 1e12 / PEAK_MFMA_F32,
                      "traffic": None},
     }
@@ -427,6 +434,7 @@ def main():
     ap.add_argument("--forward-variant", type=int, default=-1, help="0 staged, 1 single kernel, -1 planner")
     ap.add_argument("--backward-data", action="store_true",
                     help="time the gradient with respect to the input of the same layer instead of the forward pass")
+    ap.add_argument("--bwd-path", type=int, default=-1, help="data gradient: 0 sub-convolutions, 1 single kernel, -1 planner")
     ap.add_argument("--backward-filter", action="store_true",
                     help="time the gradient with respect to the filter of the same layer instead of the forward pass")
     ap.add_argument("--half", action="store_true",

@@ -246,6 +246,7 @@ typedef struct {
     long long mults_per_input_block; /* sum over sub-convolutions of their multiplications per 2x2 tile */
     double direct_flops;             /* 2*N*K*C*R*S*OH*OW, the same as the forward pass */
     double winograd_flops;           /* sum over sub-convolutions */
+    int single_kernel;               /* 1: the path in use is the single kernel (see dwm_bwd_data_set_variant) */
 } dwm_bwd_data_info_t;
 
 typedef struct {
@@ -269,7 +270,7 @@ DWM_API dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void*
  * cut by eq. 8; for layers with few input channels; needs no workspace; DWM_ERR_UNSUPPORTED where
  * it does not apply: a window of fewer than two or more than eleven taps, more than 256 columns,
  * an image of dy of 2 GiB or more, a filter slice that does not fit in LDS -- windows of seven taps
- * and more), -1 = the planner's choice (1 where C <= 8, C*stride^2 <= 64, two workgroups fit a CU and at
+ * and more), -1 = the planner's choice (1 where C <= 16, C*stride^2 <= 64, two workgroups fit a CU and at
  * least half of a workgroup's lanes hold a tile).
  * Both give the same dx up to fp32 summation order.  May be called at any time. */
 DWM_API dwm_status_t dwm_bwd_data_set_variant(dwm_bwd_data_plan_t* plan, const char* stage, int variant);

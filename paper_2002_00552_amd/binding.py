@@ -51,7 +51,7 @@ class dwm_fused_row_t(ctypes.Structure):
 
 class dwm_bwd_data_info_t(ctypes.Structure):
     _fields_ = [("n_phases", ctypes.c_int), ("n_subconvs", ctypes.c_int), ("mults_per_input_block", ctypes.c_longlong),
-                ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double)]
+                ("direct_flops", ctypes.c_double), ("winograd_flops", ctypes.c_double), ("single_kernel", ctypes.c_int)]
 
 
 class dwm_bwd_phase_t(ctypes.Structure):

@@ -327,7 +327,7 @@ dwm_status_t dwm_bwd_data_plan_create(dwm_bwd_data_plan_t** out, int N, int C, i
         }
     // the single-kernel form: chosen where the sub-convolutions would have only a handful of filters
     bp->small_ok = bwd_small_setup(N, C, H, W, K, R, S, stride, pad, &bp->small);
-    bp->small_default = bp->small_ok && C <= 8 && bp->small.nf <= 64 && bp->small.lds_bytes <= 78 * 1024 &&
+    bp->small_default = bp->small_ok && C <= 16 && bp->small.nf <= 64 && bp->small.lds_bytes <= 78 * 1024 &&
                         bp->small.eff_pct >= 50;
     bp->variant_path = -1;
     bp->u_small_off = off;
@@ -364,6 +364,7 @@ dwm_status_t dwm_bwd_data_plan_info(const dwm_bwd_data_plan_t* plan, dwm_bwd_dat
             info->mults_per_input_block += si.mults_per_tile;
         }
     info->direct_flops = plan->direct_flops;
+    info->single_kernel = plan->use_small() ? 1 : 0;
     return DWM_OK;
 }
 

@@ -46,14 +46,6 @@ __device__ __forceinline__ float bs_g_row(int i, float v0, float v1, float v2)
     }
 }
 
-// Position of (plane, lane) inside one step of the filter copy: planes in groups of four, a lane's
-// four planes adjacent (one 16-byte LDS read); the planes left over follow, 64 lanes each.
-__host__ __device__ __forceinline__ int bs_upos(int planes, int plane, int lane)
-{
-    const int g4 = planes / 4;
-    return plane < 4 * g4 ? (plane >> 2) * 256 + lane * 4 + (plane & 3) : g4 * 256 + (plane - 4 * g4) * 64 + lane;
-}
-
 // ---------------------------------------------------------------------------------
 // Filter copy UB[column block][chunk][step][plane, lane]: the A operands exactly as a chunk
 // lies in LDS (a chunk padded to whole KB; the padding is copied and never read).  Lane (i, q)

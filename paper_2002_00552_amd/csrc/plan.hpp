@@ -242,6 +242,17 @@ struct BwdSmallArgs {
     size_t lds_bytes, u_floats;
 };
 
+// Position of (plane, lane) inside one step of that kernel's filter copy: planes in groups of four, a
+// lane's four planes adjacent (one 16-byte LDS read); the planes left over follow, 64 lanes each.
+#ifdef __HIPCC__
+__host__ __device__
+#endif
+inline int bs_upos(int planes, int plane, int lane)
+{
+    const int g4 = planes / 4;
+    return plane < 4 * g4 ? (plane >> 2) * 256 + lane * 4 + (plane & 3) : g4 * 256 + (plane - 4 * g4) * 64 + lane;
+}
+
 // Several stride-1 sub-convolutions contracted in one launch (contract_batch.hip): their planes
 // are concatenated in one PlaneTable, their (K tile, T tile) grids in one grid.
 constexpr int kMaxBatch = 16;

@@ -130,10 +130,126 @@ static int walk(int N, int C, int H, int W, int K, int R, int S, int s, int P)
     return 1;
 }
 
+// The single-kernel data gradient: its geometry is built on the host (setup.cpp) and the kernel's
+// address arithmetic follows from it.  Here that arithmetic is replayed: every LDS offset the
+// kernel forms stays inside what it allocates, a staged element is found again where the patch
+// reads look for it, and -- on small shapes, in exact integer arithmetic -- the window/tap tables
+// give the gradient that the definition gives.
+static int walk_bwd_small(int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    using namespace dwm;
+    BwdSmallArgs f;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 0;
+    if (H + 2 * P < R || W + 2 * P < S) return 0;
+    if (!bwd_small_setup(N, C, H, W, K, R, S, s, P, &f)) return 0;
+    const int nfreq = f.four ? 4 : 3, planes = nfreq * nfreq;
+    CHECK(f.OH == (H + 2 * P - R) / s + 1 && f.OW == (W + 2 * P - S) / s + 1);
+    CHECK(f.nf == C * s * s && f.ncb == (f.nf + 15) / 16);
+    // the pieces tile the window, two or three taps each
+    int sum = 0;
+    for (int i = 0; i < f.nph; ++i) { CHECK(f.jh[i] == sum && (f.lh[i] == 2 || f.lh[i] == 3)); sum += f.lh[i]; }
+    CHECK(sum == f.nwh && f.nph <= kBsMaxPieces);
+    sum = 0;
+    for (int i = 0; i < f.npw; ++i) { CHECK(f.jw[i] == sum && (f.lw[i] == 2 || f.lw[i] == 3)); sum += f.lw[i]; }
+    CHECK(sum == f.nww && f.npw <= kBsMaxPieces && f.npp == f.nph * f.npw);
+    // every tap of a residue lies inside the window
+    for (int rho = 0; rho < s; ++rho) {
+        for (int i = 0; i < f.rn_h[rho]; ++i) {
+            const int j = f.re_h[rho] + f.Lh - i;
+            CHECK(j >= 0 && j < f.nwh && s * i + f.ra_h[rho] < R);
+        }
+        for (int i = 0; i < f.rn_w[rho]; ++i) {
+            const int j = f.re_w[rho] + f.Lw - i;
+            CHECK(j >= 0 && j < f.nww && s * i + f.ra_w[rho] < S);
+        }
+    }
+    // tiles and blocks cover the image
+    CHECK(2 * s * f.TH >= H && 2 * s * f.TW >= W && f.nbh * f.BH >= f.TH && f.nbw * f.BW >= f.TW && f.BH * f.BW <= 64);
+    // LDS: chunks of dy, chunks of the filter copy, the table
+    const int G = 1 << f.glog, NE = 1 << f.nelog;
+    const long long xs_bytes = 4LL * f.xs_floats, us_bytes = 4LL * f.us_floats;
+    const long long pair_bytes = 8LL * f.group_elems, group_bytes = 2 * pair_bytes, row_bytes = 8LL * f.row_elems;
+    CHECK((long long)f.lds_bytes == 2 * (xs_bytes + us_bytes) + kBsMaxPairs * 8 && f.lds_bytes <= 160 * 1024);
+    CHECK(G * group_bytes <= xs_bytes && xs_bytes % 16 == 0 && us_bytes % 1024 == 0);
+    CHECK(f.ck == 4 * G && f.steps == f.npp * G && f.steps % 2 == 0 && f.steps >= 2);
+    CHECK(f.nchunks * f.ck >= K && (f.nchunks - 1) * f.ck < K);
+    CHECK((long long)f.steps * planes * 256 <= us_bytes);
+    CHECK(f.u_floats == (size_t)f.ncb * f.nchunks * f.us_floats);
+    CHECK(G * NE <= kBsMaxSlots && f.nrows * f.lw_in <= 256 * NE);
+    CHECK(f.row_elems == 2 * f.lwp && f.group_elems == f.nrows * f.row_elems && f.tile_row_step == 2 * f.row_elems);
+    // a staged element (r, c) of a channel pair: where the staging writes it; all distinct, all inside
+    auto elem_off = [&](int r, int c) { return 8LL * (r * f.row_elems + (c & 1) * f.lwp + (c >> 1)); };
+    std::vector<char> used((size_t)(pair_bytes / 8), 0);
+    for (int r = 0; r < f.nrows; ++r)
+        for (int c = 0; c < f.lw_in; ++c) {
+            const long long o = elem_off(r, c);
+            CHECK(o >= 0 && o + 8 <= pair_bytes && !used[(size_t)(o / 8)]);
+            used[(size_t)(o / 8)] = 1;
+        }
+    // where a lane looks for patch element (i, j) of piece pair pp: the offsets the kernel adds up
+    for (int tl = 0; tl < 64; ++tl) {
+        const int by = tl / f.BW, bx = tl % f.BW;
+        if (by >= f.BH) continue;
+        const long long lane_base = 8LL * (by * f.tile_row_step + bx);
+        for (int pp = 0; pp < f.npp; ++pp) {
+            const int jh = f.jh[pp / f.npw], jw = f.jw[pp % f.npw];
+            for (int i = 0; i < nfreq; ++i)
+                for (int j = 0; j < nfreq; ++j) {
+                    const long long got = lane_base + ((j & 1) ? f.po1[pp] : f.po0[pp]) + i * row_bytes + (j >> 1) * 8;
+                    const int r = 2 * by + jh + i, c = 2 * bx + jw + j;
+                    CHECK(r < f.nrows && c < f.lw_in && got == elem_off(r, c));
+                }
+        }
+    }
+    // the filter copy: (plane, lane) -> position inside a step is one-to-one
+    std::vector<char> upos((size_t)planes * 64, 0);
+    for (int pl = 0; pl < planes; ++pl)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int o = bs_upos(planes, pl, lane);
+            CHECK(o >= 0 && o < planes * 64 && !upos[(size_t)o]);
+            upos[(size_t)o] = 1;
+        }
+    // 32-bit offsets: one image of dy, one channel of dx
+    CHECK((long long)K * f.OH * f.OW * 4 < (1LL << 31) && (long long)H * W < (1LL << 29));
+
+    // small shapes: the window and tap tables against the definition, in integers
+    if ((long long)C * K * H * W * R * S <= 200000 && N <= 2) {
+        std::vector<long long> w((size_t)K * C * R * S), dy((size_t)K * f.OH * f.OW);
+        for (auto& v : w) v = pick(-3, 3);
+        for (auto& v : dy) v = pick(-3, 3);
+        for (int c = 0; c < C; ++c)
+            for (int ih = 0; ih < H; ++ih)
+                for (int iw = 0; iw < W; ++iw) {
+                    long long ref = 0;
+                    for (int k = 0; k < K; ++k)
+                        for (int r = 0; r < R; ++r)
+                            for (int q = 0; q < S; ++q) {
+                                const int a = ih + P - r, b = iw + P - q;
+                                if (a < 0 || b < 0 || a % s || b % s || a / s >= f.OH || b / s >= f.OW) continue;
+                                ref += dy[((size_t)k * f.OH + a / s) * f.OW + b / s] * w[(((size_t)k * C + c) * R + r) * S + q];
+                            }
+                    const int th = ih / s, rh = ih % s, tw = iw / s, rw = iw % s;
+                    long long got = 0;
+                    for (int k = 0; k < K; ++k)
+                        for (int jh = 0; jh < f.nwh; ++jh)
+                            for (int jw = 0; jw < f.nww; ++jw) {
+                                const int i = f.re_h[rh] + f.Lh - jh, j = f.re_w[rw] + f.Lw - jw;
+                                if (i < 0 || i >= f.rn_h[rh] || j < 0 || j >= f.rn_w[rw]) continue;
+                                const int a = th - f.Lh + jh, b = tw - f.Lw + jw;
+                                if (a < 0 || a >= f.OH || b < 0 || b >= f.OW) continue;
+                                got += dy[((size_t)k * f.OH + a) * f.OW + b] *
+                                       w[(((size_t)k * C + c) * R + (s * i + f.ra_h[rh])) * S + (s * j + f.ra_w[rw])];
+                            }
+                    CHECK(got == ref);
+                }
+    }
+    return 1;
+}
+
 int main(int argc, char** argv)
 {
     const int iters = argc > 1 ? std::atoi(argv[1]) : 3000;
-    int ok = 0, tried = 0;
+    int ok = 0, tried = 0, small = 0;
     // the benchmark layers and corner shapes first
     const int fixed[][9] = {
         {1, 16, 32, 32, 16, 5, 5, 1, 2},   {32, 128, 56, 56, 256, 3, 3, 2, 1}, {32, 256, 28, 28, 256, 7, 7, 1, 3},
@@ -147,6 +263,7 @@ int main(int argc, char** argv)
     for (const auto& f : fixed) {
         ++tried;
         ok += walk(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
+        small += walk_bwd_small(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
     }
     CHECK(dwm_plan_create(nullptr, 1, 1, 3, 3, 1, 3, 3, 1, 1) == DWM_ERR_INVALID_ARG);
     CHECK(dwm_plan_destroy(nullptr) == DWM_ERR_INVALID_ARG);
@@ -159,7 +276,9 @@ int main(int argc, char** argv)
         const int N = pick(1, big ? 3 : 70);
         ++tried;
         ok += walk(N, C, H, W, K, R, S, s, P);
+        small += walk_bwd_small(N, C < 20 ? C : C % 9 + 1, H, W, K, R, S, s, P);
     }
-    std::printf("planner fuzz: %d shapes tried, %d planned\n", tried, ok);
+    CHECK(small > tried / 8);
+    std::printf("planner fuzz: %d shapes tried, %d planned, %d with a single-kernel data gradient\n", tried, ok, small);
     return ok > tried / 2 ? 0 : 3;
 }
