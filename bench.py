@@ -221,7 +221,10 @@ def bench_half(args, L, x, w, bf16=False):
     plan = fn("plan_create")(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad)
     if args.contract_variant >= 0:
         fn("set_variant")(plan, "contract", args.contract_variant)
+    if args.forward_variant >= 0:
+        fn("set_variant")(plan, "forward", args.forward_variant)
     info = fn("plan_info")(plan)
+    single = info.forward_path == 1
     U = torch.empty(fn("filter_bytes")(plan) // 2, dtype=tdt, device="cuda")
     ws = torch.empty(max(fn("workspace_bytes")(plan), 256), dtype=torch.uint8, device="cuda")
     y = torch.empty((L.N, L.K, info.OH, info.OW), dtype=tdt, device="cuda")
@@ -247,32 +250,47 @@ def bench_half(args, L, x, w, bf16=False):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / args.steps
 
-    in_ms = timed(lambda: fn("input_transform")(plan, xp, st))
-    ct_ms = timed(lambda: fn("contract_output")(plan, Up, yp, st))
-    v_bytes = 2.0 * info.mults_per_tile * L.C * info.T
-    u_bytes = 2.0 * info.mults_per_tile * L.C * L.K
     x_bytes, y_bytes = 2.0 * x.size, 2.0 * y.numel()
-    ct_bytes = v_bytes + u_bytes + y_bytes
-    stages = {
-        "input_transform": {"ms": in_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + v_bytes,
-                            "achieved_GBps": (x_bytes + v_bytes) / in_ms / 1e6,
-                            "frac_of_hbm_peak": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM},
-        "contract_output": {"ms": ct_ms, "bound": "hbm", "algorithmic_bytes": ct_bytes,
-                            "achieved_GBps": ct_bytes / ct_ms / 1e6, "frac_of_hbm_peak": ct_bytes / ct_ms / 1e6 / PEAK_HBM,
-                            "algorithmic_flops": info.winograd_flops,
-                            "achieved_TFLOPs": info.winograd_flops / ct_ms / 1e9,
-                            "frac_of_f16_mfma_peak": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F16},
-    }
-    dom = "contract_output" if ct_ms >= in_ms else "input_transform"
+    if single:
+        # one kernel: x and y cross HBM once, V never leaves the registers
+        k_ms = timed(lambda: fn("conv_forward")(plan, xp, Up, yp, st))
+        stages = {
+            "fused16_forward": {"ms": k_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + y_bytes,
+                                "achieved_GBps": (x_bytes + y_bytes) / k_ms / 1e6,
+                                "frac_of_hbm_peak": (x_bytes + y_bytes) / k_ms / 1e6 / PEAK_HBM,
+                                "algorithmic_flops": info.winograd_flops,
+                                "achieved_TFLOPs": info.winograd_flops / k_ms / 1e9,
+                                "frac_of_f16_mfma_peak": info.winograd_flops / k_ms / 1e9 / PEAK_MFMA_F16},
+        }
+        dom = "fused16_forward"
+    else:
+        in_ms = timed(lambda: fn("input_transform")(plan, xp, st))
+        ct_ms = timed(lambda: fn("contract_output")(plan, Up, yp, st))
+        v_bytes = 2.0 * info.mults_per_tile * L.C * info.T
+        u_bytes = 2.0 * info.mults_per_tile * L.C * L.K
+        ct_bytes = v_bytes + u_bytes + y_bytes
+        stages = {
+            "input_transform": {"ms": in_ms, "bound": "hbm", "algorithmic_bytes": x_bytes + v_bytes,
+                                "achieved_GBps": (x_bytes + v_bytes) / in_ms / 1e6,
+                                "frac_of_hbm_peak": (x_bytes + v_bytes) / in_ms / 1e6 / PEAK_HBM},
+            "contract_output": {"ms": ct_ms, "bound": "hbm", "algorithmic_bytes": ct_bytes,
+                                "achieved_GBps": ct_bytes / ct_ms / 1e6, "frac_of_hbm_peak": ct_bytes / ct_ms / 1e6 / PEAK_HBM,
+                                "algorithmic_flops": info.winograd_flops,
+                                "achieved_TFLOPs": info.winograd_flops / ct_ms / 1e9,
+                                "frac_of_f16_mfma_peak": info.winograd_flops / ct_ms / 1e9 / PEAK_MFMA_F16},
+        }
+        dom = "contract_output" if ct_ms >= in_ms else "input_transform"
     out = {
         "metric": "direct-conv-equivalent TFLOP/s of DWM conv (%s storage, FP32 accumulation, 1 GPU); "
                   "MSE vs FP64 direct" % ("bfloat16" if bf16 else "binary16"),
         "value": info.direct_flops / dt / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if bf16 else "f16", "data": "synthetic",
-        "config": {"workload": L.name + ("_bf16" if bf16 else "_half"), "parts": info.n_parts, "mults_per_tile": info.mults_per_tile,
+        "config": {"workload": L.name + ("_bf16" if bf16 else "_half"), "path": "single kernel" if single else "staged",
+                   "parts": info.n_parts, "mults_per_tile": info.mults_per_tile,
                    "direct_GFLOP": info.direct_flops / 1e9, "winograd_GFLOP": info.winograd_flops / 1e9},
-        "roofline": {"kernel": {"contract_output": "contract16_kernel", "input_transform": "input_transform_f16_kernel"}[dom],
+        "roofline": {"kernel": {"contract_output": "contract16_kernel", "input_transform": "input_transform_f16_kernel",
+                                "fused16_forward": "fused16_forward_kernel"}[dom],
                      "bound": "hbm", "achieved": stages[dom]["achieved_GBps"], "peak": PEAK_HBM, "unit": "GB/s",
                      "frac": stages[dom]["frac_of_hbm_peak"], "traffic": None},
         "stages": stages,

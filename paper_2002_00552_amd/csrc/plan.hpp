@@ -8,6 +8,8 @@
 #endif
 #include "../../include/dwm.h"
 
+struct dwm_plan;
+
 namespace dwm {
 
 constexpr int kMaxPieces = 16;  // one-dimensional pieces per dimension
@@ -192,6 +194,38 @@ struct FusedArgs {
     unsigned short rowdesc[kFusedMaxRows];            // h piece | w piece << 4 | channel << 8 | real row << 15
     size_t lds_bytes;
 };
+
+// Geometry of the 16-bit single-kernel forward path (half_impl.inc), for layers with few input
+// channels.  The decomposition is the 16-bit path's own (the kernel cut exactly as eq. 8 writes
+// it; a class = the parts of one (len_h, len_w) with (len_h+1)(len_w+1) planes).  A wave owns 16
+// tiles; a step is 16 reduction rows (part, channel) of one class -- the depth of the 16-bit
+// 16x16x16 MFMA, four rows per lane -- and the products go straight into the 2x2 outputs: an
+// output takes one MFMA for every plane whose A^T coefficient for it is not zero, with the sign on
+// the transformed input.
+constexpr int kF16MaxRows = 512;  // rows of all classes, each class padded to a multiple of 16
+struct Fused16Class {
+    int lh, lw;
+    int row0, nsteps;   // first row in the padded row space, steps of 16 rows
+    int L;              // real rows: parts * C
+    int pad_;
+    long long uf_off;   // 16-bit elements from the start of U: [block of 16 filters][step][plane][lane][4]
+};
+struct Fused16Args {
+    int BH, BW, nbh, nbw;            // block of tiles of a workgroup (BH*BW <= 64), blocks per image
+    int nphase, lwp, lw_in, nrows;   // staged input region: 2*stride column phases, floats per (row, phase), columns, rows
+    int row_floats, chan_floats, tile_row_step;
+    int patch_row_bytes;             // LDS bytes between the rows of a patch: stride * row_floats * 4
+    int eff_pct;                     // lanes of a workgroup that hold a tile, in percent
+    int nkb, slice_kb, nslices;      // blocks of 16 filters; blocks per pass over the classes; passes
+    int ncls, rows_total;
+    Fused16Class cls[kMaxClasses];
+    FastDiv div_bw, div_nphase;
+    int roff[kMaxPieces];            // LDS floats from a tile's base to row 0 of an h piece's patch
+    int coff0[kMaxPieces], coff1[kMaxPieces];  // ... to column 0 / column 1 of a w piece's patch (columns 2, 3: one float on)
+    unsigned short rowdesc[kF16MaxRows];       // h piece | w piece << 4 | channel << 8
+    size_t lds_bytes, uf_halves;
+};
+bool fused16_setup(const dwm_plan& p, Fused16Args* out);
 
 // Geometry of the LDS-staged input transform (transforms.hip): a workgroup stages the input
 // rows that one 64-tile block needs, for `cg` channels, and builds every part's V from LDS.

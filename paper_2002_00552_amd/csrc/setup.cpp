@@ -334,4 +334,86 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
     return true;
 }
 
+// ---------------------------------------------------------------------------------
+// 16-bit single-kernel forward path: classes, rows, block of tiles, LDS
+// ---------------------------------------------------------------------------------
+bool fused16_setup(const dwm_plan& p, Fused16Args* out)
+{
+    const DevPlan& d = p.d;
+    Fused16Args f{};
+    if (d.C > 127 || d.nh > 15 || d.nw > 15 || d.ncls > kMaxClasses) return false;
+    if (d.om.sy != 1 || d.om.sx != 1 || d.om.oy != 0 || d.om.ox != 0 || d.om.YH != d.OH || d.om.YW != d.OW) return false;
+    f.nkb = (d.K + 15) / 16;
+    f.slice_kb = std::min(f.nkb, 4);
+    f.nslices = (f.nkb + f.slice_kb - 1) / f.slice_kb;
+    int rows = 0;
+    size_t uf = 0;
+    for (int qi = 0; qi < d.ncls; ++qi) {
+        const DevClass& q = d.cls[qi];
+        Fused16Class fc{};
+        fc.lh = q.lh; fc.lw = q.lw;
+        fc.L = q.L;
+        fc.row0 = rows;
+        fc.nsteps = (q.L + 15) / 16;
+        fc.uf_off = (long long)uf;
+        for (int l = 0; l < fc.nsteps * 16; ++l) {
+            if (rows >= kF16MaxRows) return false;
+            const int lr = std::min(l, q.L - 1);  // padding rows: the last real row's patch, zero filter rows
+            const int slot = lr / d.C, c = lr - slot * d.C;
+            const int a = slot / q.wn, b = slot - a * q.wn;
+            f.rowdesc[rows++] = (unsigned short)((q.h0 + a) | (q.w0 + b) << 4 | c << 8);
+        }
+        uf += (size_t)f.nkb * fc.nsteps * (q.lh + 1) * (q.lw + 1) * 256;
+        f.cls[f.ncls++] = fc;
+    }
+    f.rows_total = rows;
+    f.uf_halves = uf;
+    if (uf * 2 >= ((size_t)1 << 31)) return false;  // addressed through a 32-bit buffer offset
+
+    int max_oh = 0, max_ow = 0;
+    for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
+    for (int i = 0; i < d.nw; ++i) max_ow = std::max(max_ow, d.s * (d.pw[i].j + d.pw[i].l) + d.pw[i].p);
+    f.nphase = 2 * d.s;
+    const size_t table_bytes = (size_t)rows * 8;
+    const size_t budget = 76 * 1024;  // two workgroups per CU
+    double best_eff = 0.0;
+    size_t best_x = 0;
+    for (int bw = 1; bw <= 64 && bw <= d.TW; ++bw) {
+        int bh = 64 / bw;
+        if (bh > d.TH) bh = d.TH;
+        if (bh < 1) continue;
+        const int nbh = (d.TH + bh - 1) / bh, nbw = (d.TW + bw - 1) / bw;
+        const double eff = (double)d.TH * d.TW / ((double)nbh * nbw * 64);
+        const long long nrows = 2LL * d.s * (bh - 1) + max_oh + 1;
+        const long long lw_in = 2LL * d.s * (bw - 1) + max_ow + 1;
+        const long long lwp = ((lw_in + f.nphase - 1) / f.nphase) | 1;
+        const long long x_bytes = (long long)d.C * nrows * f.nphase * lwp * (long long)sizeof(float);
+        if (x_bytes + (long long)table_bytes > (long long)budget) continue;
+        if (eff > best_eff + 1e-9 || (eff > best_eff - 1e-9 && (size_t)x_bytes < best_x)) {
+            best_eff = eff; best_x = (size_t)x_bytes;
+            f.BH = bh; f.BW = bw; f.nbh = nbh; f.nbw = nbw;
+            f.nrows = (int)nrows; f.lw_in = (int)lw_in; f.lwp = (int)lwp;
+        }
+    }
+    if (best_eff <= 0.0) return false;
+    f.eff_pct = (int)(best_eff * 100.0);
+    if ((long long)d.N * f.nbh * f.nbw > 0x7fffffffLL) return false;
+    f.row_floats = f.nphase * f.lwp;
+    f.chan_floats = f.nrows * f.row_floats;
+    f.tile_row_step = 2 * d.s * f.row_floats;
+    f.patch_row_bytes = d.s * f.row_floats * 4;
+    f.div_bw.init((unsigned)f.BW);
+    f.div_nphase.init((unsigned)f.nphase);
+    for (int i = 0; i < kMaxPieces; ++i) {
+        const int oh = i < d.nh ? d.s * d.ph[i].j + d.ph[i].p : 0;
+        const int ow0 = i < d.nw ? d.s * d.pw[i].j + d.pw[i].p : 0, ow1 = ow0 + d.s;
+        f.roff[i] = oh * f.row_floats;
+        f.coff0[i] = (ow0 % f.nphase) * f.lwp + ow0 / f.nphase;
+        f.coff1[i] = (ow1 % f.nphase) * f.lwp + ow1 / f.nphase;
+    }
+    f.lds_bytes = table_bytes + best_x;
+    *out = f;
+    return true;
+}
+
 }  // namespace dwm

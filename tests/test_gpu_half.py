@@ -27,8 +27,10 @@ TOL_F32OUT = 2e-5
 
 
 class HalfRunner:
-    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant=None, input_variant=None):
+    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant=None, input_variant=None, forward=0):
+        # forward: 0 the staged path (what most tests here are about), 1 the single kernel, -1 the planner's choice
         self.plan = dwm.dwm_f16_plan_create(N, C, H, W, K, R, S, stride, pad)
+        dwm.dwm_f16_set_variant(self.plan, "forward", forward)
         if variant is not None:
             dwm.dwm_f16_set_variant(self.plan, "contract", variant)
         if input_variant is not None:
@@ -285,6 +287,7 @@ def test_error_codes():
         dwm.dwm_f16_plan_create(1, 1, 2, 2, 1, 3, 3, 1, 0)  # kernel larger than the padded input
     assert e.value.status == dwm.DWM_ERR_INVALID_ARG
     plan = dwm.dwm_f16_plan_create(1, 16, 8, 8, 4, 3, 3, 1, 1)
+    dwm.dwm_f16_set_variant(plan, "forward", 0)  # (the single kernel needs no workspace)
     try:
         buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
         with pytest.raises(dwm.DwmError) as e:
@@ -309,3 +312,129 @@ def test_error_codes():
         dwm.dwm_f16_plan_destroy(p3)
     finally:
         dwm.dwm_f16_plan_destroy(plan)
+
+
+# ---- the single-kernel path (layers with few input channels) ----
+
+def _single_kernel_applies(shape):
+    p = dwm.dwm_f16_plan_create(*shape)
+    try:
+        dwm.dwm_f16_set_variant(p, "forward", 1)
+        return True
+    except dwm.DwmError:
+        return False
+    finally:
+        dwm.dwm_f16_plan_destroy(p)
+
+
+SINGLE_SHAPES = [sh for sh in SHAPES if _single_kernel_applies(sh)] + [
+    (3, 3, 64, 64, 64, 7, 7, 2, 3),      # the 7x7 stride-2 stem: classes (3,3), (3,1), (1,3), (1,1); one pass of four filter blocks
+    (2, 3, 67, 67, 96, 11, 11, 4, 0),    # the 11x11 stride-4 stem: (3,3) with two steps, (3,2), (2,3), (2,2); two passes
+    (2, 3, 50, 46, 13, 3, 3, 2, 1),      # K not a multiple of 16; classes (2,2), (2,1), (1,2), (1,1)
+    (1, 1, 33, 35, 9, 5, 5, 2, 2),       # one channel
+    (1, 7, 24, 24, 40, 5, 5, 1, 2),      # 3+2 taps, seven channels: steps that end inside a part
+    (1, 12, 20, 22, 100, 3, 3, 1, 1),    # seven filter blocks: two passes, the second with three
+    (2, 3, 9, 200, 6, 7, 7, 2, 3),       # a wide, flat image
+    (600, 3, 30, 30, 5, 5, 5, 2, 2),     # more blocks than persistent workgroups
+    (2, 20, 21, 19, 24, 3, 3, 1, 1),     # twenty channels: above the planner's own limit, forced
+]
+
+
+@pytest.mark.parametrize("shape", SINGLE_SHAPES)
+def test_single_kernel_f32out_matches_oracle(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand16(*shape, seed=1500 + R * 7 + S + C)
+    ref = oracle.dwm_half_f64(x, w, s, P)
+    r = HalfRunner(*shape, forward=1)
+    try:
+        assert r.info.forward_path == 1
+        y = r.run(x, w, f32out=True)
+    finally:
+        r.close()
+    assert np.all(np.isfinite(y))
+    err = float(np.max(np.abs(y.astype(np.float64) - ref)) / np.max(np.abs(ref)))
+    assert err <= TOL_F32OUT, err
+
+
+@pytest.mark.parametrize("shape", SINGLE_SHAPES)
+def test_single_kernel_16bit_out_within_one_step(shape):
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand16(*shape, seed=1900 + R * 7 + S + C, dist="normal")
+    ref = oracle.dwm_half_f64(x, w, s, P)
+    r = HalfRunner(*shape, forward=1)
+    try:
+        y = r.run(x, w)
+    finally:
+        r.close()
+    _check_half_out(y, ref)
+
+
+@pytest.mark.parametrize("R,S,stride,pad", [(3, 3, 1, 1), (5, 5, 1, 2), (7, 7, 2, 3), (11, 11, 4, 0), (4, 6, 3, 2)])
+def test_single_kernel_small_integers_are_exact(R, S, stride, pad):
+    rng = np.random.default_rng(R * 100 + S * 10 + stride + 1)
+    N, C, K, H = 2, 6, 37, max(R + 9, 18)
+    x = rng.integers(-4, 5, size=(N, C, H, H + 1)).astype(np.float16)
+    w = (4 * rng.integers(-3, 4, size=(K, C, R, S))).astype(np.float16)
+    ref = oracle.direct_f64(x.astype(np.float32), w.astype(np.float32), stride, pad)
+    r = HalfRunner(N, C, H, H + 1, K, R, S, stride, pad, forward=1)
+    try:
+        y = r.run(x, w, f32out=True)
+    finally:
+        r.close()
+    assert np.array_equal(y.astype(np.float64), ref)
+
+
+def test_single_kernel_rounding_points():
+    """The cases that pin the oracle's rounding points: one product per output, so the single kernel
+    must reproduce the oracle bit for bit."""
+    h = 2.0 ** -11
+    cases = [([0.5, 1.0, 0.25], [1.0, h]), ([0.0, 1.0, 1.0], [1.0, 3 * h]), ([1.0, -h, 0.0], [1.0, 0.0]),
+             ([0.0, -h, 1.0], [0.0, 1.0]), ([0.0, 1.0, 0.0, 0.0], [1.0, h, 0.0])]
+    for d, g in cases:
+        x = np.array(d, np.float16).reshape(1, 1, 1, len(d))
+        w = np.array(g, np.float16).reshape(1, 1, 1, len(g))
+        r = HalfRunner(1, 1, 1, len(d), 1, 1, len(g), 1, 0, forward=1)
+        try:
+            y = r.run(x, w, f32out=True).reshape(-1).astype(np.float64)
+        finally:
+            r.close()
+        assert np.array_equal(y, oracle.dwm_half_f64(x, w, 1, 0).reshape(-1))
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_stems_full_size_planner_choice(index):
+    """The two stems at full size with the planner's own choice of path (the single kernel): sampled
+    outputs against the exact convolution of the 16-bit inputs, and two images element by element
+    against the oracle."""
+    L = wl.CONFIGS[index]
+    x32, w32 = wl.make_layer_tensors(L, index)
+    x, w = x32.astype(np.float16), w32.astype(np.float16)
+    r = HalfRunner(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, forward=-1)
+    try:
+        assert r.info.forward_path == 1
+        y = r.run(x, w)
+        y32 = r.run(x, w, f32out=True)
+    finally:
+        r.close()
+    assert np.all(np.isfinite(y))
+    rng = np.random.default_rng(index)
+    idx = rng.choice(y.size, size=4000, replace=False)
+    ref = oracle.direct_f64_at(np.asarray(x, np.float32), np.asarray(w, np.float32), L.stride, L.pad, idx)
+    got = y.reshape(-1)[idx].astype(np.float64)
+    scale = float(np.max(np.abs(ref)))
+    assert np.max(np.abs(got - ref)) <= 8 * 2.0 ** -11 * scale
+    ref2 = oracle.dwm_half_f64(x[:2], w, L.stride, L.pad)
+    err = float(np.max(np.abs(y32[:2].astype(np.float64) - ref2)) / np.max(np.abs(ref2)))
+    assert err <= TOL_F32OUT, err
+    _check_half_out(y[:2], ref2)
+
+
+def test_single_kernel_refused_where_it_does_not_apply():
+    p = dwm.dwm_f16_plan_create(1, 200, 8, 8, 4, 3, 3, 1, 1)  # 200 channels
+    try:
+        with pytest.raises(dwm.DwmError) as e:
+            dwm.dwm_f16_set_variant(p, "forward", 1)
+        assert e.value.status == dwm.DWM_ERR_INVALID_ARG
+        assert dwm.dwm_f16_plan_info(p).forward_path == 0
+    finally:
+        dwm.dwm_f16_plan_destroy(p)

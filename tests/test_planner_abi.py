@@ -178,9 +178,13 @@ def test_half_plan_is_cut_as_printed():
         parts = oracle.split_2d(L.R, L.S, L.stride)
         assert info.n_parts == len(parts)
         assert info.mults_per_tile == oracle.mults_per_tile(L.R, L.S, L.stride)
-        assert info.forward_path == 0
-        # U16 holds every plane's Kpad x Lpad block, two bytes per element
-        assert dwm.dwm_f16_filter_bytes(p) % (2 * info.Kpad * 16) == 0
+        # the 16-bit single kernel where the layer has few input channels, else the staged path
+        assert info.forward_path == (1 if L.C <= 16 else 0)
+        dwm.dwm_f16_set_variant(p, "forward", 0)
+        assert dwm.dwm_f16_plan_info(p).forward_path == 0
+        # U16 holds every plane's Kpad x Lpad block, two bytes per element (and the single kernel's copy
+        # behind it where that path applies)
+        assert dwm.dwm_f16_filter_bytes(p) % 256 == 0
         assert dwm.dwm_f16_filter_bytes(p) >= 2 * info.mults_per_tile * L.C * L.K
         # workspace: V16 (all planes' rows for Tpad tiles) and then some
         assert dwm.dwm_f16_workspace_bytes(p) >= 2 * info.mults_per_tile * L.C * info.T
