@@ -203,6 +203,7 @@ struct FusedArgs {
 // output takes one MFMA for every plane whose A^T coefficient for it is not zero, with the sign on
 // the transformed input.
 constexpr int kF16MaxRows = 512;  // rows of all classes, each class padded to a multiple of 16
+constexpr int kF16SliceKb = 2;    // blocks of 16 filters per pass over the classes (32 accumulator registers)
 struct Fused16Class {
     int lh, lw;
     int row0, nsteps;   // first row in the padded row space, steps of 16 rows

@@ -344,7 +344,7 @@ bool fused16_setup(const dwm_plan& p, Fused16Args* out)
     if (d.C > 127 || d.nh > 15 || d.nw > 15 || d.ncls > kMaxClasses) return false;
     if (d.om.sy != 1 || d.om.sx != 1 || d.om.oy != 0 || d.om.ox != 0 || d.om.YH != d.OH || d.om.YW != d.OW) return false;
     f.nkb = (d.K + 15) / 16;
-    f.slice_kb = std::min(f.nkb, 4);
+    f.slice_kb = std::min(f.nkb, kF16SliceKb);
     f.nslices = (f.nkb + f.slice_kb - 1) / f.slice_kb;
     int rows = 0;
     size_t uf = 0;
@@ -369,6 +369,7 @@ bool fused16_setup(const dwm_plan& p, Fused16Args* out)
     f.rows_total = rows;
     f.uf_halves = uf;
     if (uf * 2 >= ((size_t)1 << 31)) return false;  // addressed through a 32-bit buffer offset
+    if ((long long)d.K * d.OH * d.OW * 4 >= (1LL << 31)) return false;  // ... and so is one image of y
 
     int max_oh = 0, max_ow = 0;
     for (int i = 0; i < d.nh; ++i) max_oh = std::max(max_oh, d.s * (d.ph[i].j + d.ph[i].l) + d.ph[i].p);
