@@ -203,7 +203,6 @@ struct FusedArgs {
 // output takes one MFMA for every plane whose A^T coefficient for it is not zero, with the sign on
 // the transformed input.
 constexpr int kF16MaxRows = 512;  // rows of all classes, each class padded to a multiple of 16
-constexpr int kF16SliceKb = 2;    // blocks of 16 filters per pass over the classes (32 accumulator registers)
 struct Fused16Class {
     int lh, lw;
     int row0, nsteps;   // first row in the padded row space, steps of 16 rows
@@ -217,7 +216,7 @@ struct Fused16Args {
     int row_floats, chan_floats, tile_row_step;
     int patch_row_bytes;             // LDS bytes between the rows of a patch: stride * row_floats * 4
     int eff_pct;                     // lanes of a workgroup that hold a tile, in percent
-    int nkb, slice_kb, nslices;      // blocks of 16 filters; blocks per pass over the classes; passes
+    int nkb, slice_kb, nslices;      // blocks of 16 filters; blocks per pass over the classes and passes (set at launch)
     int ncls, rows_total;
     Fused16Class cls[kMaxClasses];
     FastDiv div_bw, div_nphase;

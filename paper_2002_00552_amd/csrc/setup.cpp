@@ -344,7 +344,7 @@ bool fused16_setup(const dwm_plan& p, Fused16Args* out)
     if (d.C > 127 || d.nh > 15 || d.nw > 15 || d.ncls > kMaxClasses) return false;
     if (d.om.sy != 1 || d.om.sx != 1 || d.om.oy != 0 || d.om.ox != 0 || d.om.YH != d.OH || d.om.YW != d.OW) return false;
     f.nkb = (d.K + 15) / 16;
-    f.slice_kb = std::min(f.nkb, kF16SliceKb);
+    f.slice_kb = std::min(f.nkb, 2);  // (the launcher sets what its kernel takes)
     f.nslices = (f.nkb + f.slice_kb - 1) / f.slice_kb;
     int rows = 0;
     size_t uf = 0;
