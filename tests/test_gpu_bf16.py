@@ -28,10 +28,12 @@ TOL_F32OUT = 2e-5
 
 
 class Bf16Runner:
-    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant=None, input_variant=None, forward=0):
+    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant=None, input_variant=None, forward=0, classes=-1):
         # forward: 0 the staged path (what most tests here are about), 1 the single kernel, -1 the planner's choice
         self.plan = dwm.dwm_bf16_plan_create(N, C, H, W, K, R, S, stride, pad)
         dwm.dwm_bf16_set_variant(self.plan, "forward", forward)
+        # classes: 0 the general single kernel, -1 the one built for the layer's list of classes where there is one
+        dwm.dwm_bf16_set_variant(self.plan, "classes", classes)
         if variant is not None:
             dwm.dwm_bf16_set_variant(self.plan, "contract", variant)
         if input_variant is not None:
@@ -444,3 +446,29 @@ def test_single_kernel_refused_where_it_does_not_apply():
         assert dwm.dwm_bf16_plan_info(p).forward_path == 0
     finally:
         dwm.dwm_bf16_plan_destroy(p)
+
+
+@pytest.mark.parametrize("shape", [
+    (3, 3, 64, 64, 64, 7, 7, 2, 3),      # classes (3,3), (3,1), (1,3), (1,1)
+    (2, 3, 67, 67, 96, 11, 11, 4, 0),    # (3,3), (3,2), (2,3), (2,2)
+    (2, 3, 50, 46, 13, 3, 3, 2, 1),      # (2,2), (2,1), (1,2), (1,1)
+    (1, 12, 20, 22, 100, 3, 3, 1, 1),    # (3,3) alone
+    (1, 7, 24, 24, 40, 5, 5, 1, 2),      # (3,3), (3,2), (2,3), (2,2) with steps that end inside a part
+])
+def test_single_kernel_general_and_built_for_the_classes_agree(shape):
+    """The kernel built for the layer's list of classes (four filter blocks per pass) and the general
+    one (class switch, two blocks per pass) issue the same MFMAs in the same order per output: the
+    same bits; the general one is then also checked against the oracle."""
+    N, C, H, W, K, R, S, s, P = shape
+    x, w = _rand16(*shape, seed=2300 + R + C, dist="relu_normal")
+    ys = []
+    for classes in (-1, 0):
+        r = Bf16Runner(*shape, forward=1, classes=classes)
+        try:
+            ys.append(r.run(x, w, f32out=True))
+        finally:
+            r.close()
+    assert np.array_equal(ys[0].view(np.uint32), ys[1].view(np.uint32))
+    ref = oracle.dwm_bf16_f64(x, w, s, P)
+    err = float(np.max(np.abs(ys[1].astype(np.float64) - ref)) / np.max(np.abs(ref)))
+    assert err <= TOL_F32OUT, err
