@@ -326,11 +326,20 @@ DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan,
  * Same conventions as the single-precision calls: the plan is host memory, every *_dev pointer is
  * caller-owned device memory, kernels go to `stream`, nothing is allocated or synchronised, errors
  * are return codes.  Workspace: dwm_f16_workspace_bytes, 256-byte aligned (V in binary16, partial
- * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes.
+ * outputs, arrival counters).  U_dev: dwm_f16_filter_bytes (the staged path's U, then the single
+ * kernel's copy where that path applies; dwm_f16_filter_transform writes both).
  * dwm_f16_set_variant(plan, "contract", v): v in 30..47 selects the contraction's tile shape
  * (v < 0: the planner's choice; before dwm_f16_set_workspace only); (plan, "input", v): 0 = gather form of the input transform,
  * 1 = LDS-staged form (C a multiple of 8, or at most 64, and a staged region that fits), v < 0: the planner's
  * choice; DWM_ERR_INVALID_ARG if the variant does not apply to the layer.
+ * (plan, "forward", v): 0 = the staged path (input transform, then contraction: needs the workspace),
+ * 1 = the single kernel for layers with few input channels (V stays in registers, the products go
+ * straight into the 2x2 outputs, same rounding points; needs no workspace; applies with at most 127
+ * channels, 512 reduction rows after padding every class to 16, a staged input region that fits in
+ * LDS, and an image of y below 2 GiB), v < 0: the planner's choice (1 where it applies, C <= 16 and at
+ * least half of a workgroup's lanes hold a tile); dwm_f16_plan_info's forward_path says which is in use.
+ * (plan, "classes", v): 0 = always the general single kernel, v < 0: the one built for the layer's list
+ * of classes where there is one (the same arithmetic in the same order: for tests).
  * dwm_f16_conv_forward_f32out is the same computation with y left in FP32 (not rounded): it
  * exists so that tests can compare everything before the last rounding.
  * dwm_f16_input_transform / dwm_f16_contract_output are the two stages of dwm_f16_conv_forward,
