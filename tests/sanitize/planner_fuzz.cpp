@@ -246,10 +246,75 @@ static int walk_bwd_small(int N, int C, int H, int W, int K, int R, int S, int s
     return 1;
 }
 
+// The 16-bit single kernel: its geometry (setup.cpp) on the plan cut as eq. 8 prints it.  Every patch
+// element a lane reads -- tile base + row entry + row step + column pair -- must be the staged copy of
+// the input element the decomposition names, inside the staged region; every padded row must name a
+// real (piece, piece, channel); the filter copy must have room for every (class, step, plane, block).
+static int walk_fused16(int N, int C, int H, int W, int K, int R, int S, int s, int P)
+{
+    using namespace dwm;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1 || s < 1 || P < 0) return 0;
+    if (H + 2 * P < R || W + 2 * P < S) return 0;
+    PlanSpec sp{};
+    sp.N = N; sp.C = C; sp.H = H; sp.W = W; sp.K = K; sp.R = R; sp.S = S; sp.stride = s;
+    sp.pad_h = sp.pad_w = P;
+    sp.OH = (H + 2 * P - R) / s + 1;
+    sp.OW = (W + 2 * P - S) / s + 1;
+    sp.om = OutMap{sp.OH, sp.OW, 1, 0, 1, 0};
+    dwm_plan_t* p = nullptr;
+    if (plan_from_spec_as_printed(&p, sp) != DWM_OK) return 0;
+    Fused16Args f;
+    if (!fused16_setup(*p, &f)) {
+        dwm_plan_destroy(p);
+        return 0;
+    }
+    const DevPlan& d = p->d;
+    CHECK(f.ncls == d.ncls && f.nkb == (K + 15) / 16 && f.BH * f.BW <= 64 && f.nbh * f.BH >= d.TH && f.nbw * f.BW >= d.TW);
+    CHECK(f.row_floats == f.nphase * f.lwp && f.nphase == 2 * s && f.chan_floats == f.nrows * f.row_floats);
+    CHECK(f.lds_bytes == (size_t)f.rows_total * 8 + (size_t)C * f.chan_floats * 4 && f.lds_bytes <= 160 * 1024);
+    CHECK(f.patch_row_bytes == s * f.row_floats * 4 && f.tile_row_step == 2 * s * f.row_floats);
+    auto staged = [&](int r, int c) { return (long long)r * f.row_floats + (c % f.nphase) * f.lwp + c / f.nphase; };
+    size_t uf = 0;
+    int rows = 0;
+    for (int qi = 0; qi < f.ncls; ++qi) {
+        const Fused16Class& fc = f.cls[qi];
+        const DevClass& q = d.cls[qi];
+        CHECK(fc.lh == q.lh && fc.lw == q.lw && fc.L == q.L && fc.row0 == rows && fc.nsteps == (q.L + 15) / 16);
+        CHECK((size_t)fc.uf_off == uf);
+        uf += (size_t)f.nkb * fc.nsteps * (q.lh + 1) * (q.lw + 1) * 256;
+        for (int l = 0; l < 16 * fc.nsteps; ++l, ++rows) {
+            const unsigned desc = f.rowdesc[rows];
+            const int ph = desc & 15, pw = (desc >> 4) & 15, c = desc >> 8;
+            const int lr = l < q.L ? l : q.L - 1;
+            const int slot = lr / C;
+            CHECK(c == lr % C && ph == q.h0 + slot / q.wn && pw == q.w0 + slot % q.wn);
+            CHECK(ph < d.nh && pw < d.nw && d.ph[ph].l == q.lh && d.pw[pw].l == q.lw);
+            for (int tl = 0; tl < 64; ++tl) {
+                const int by = tl / f.BW, bx = tl % f.BW;
+                if (by >= f.BH) continue;
+                const long long base = (long long)by * f.tile_row_step + bx + (long long)c * f.chan_floats + f.roff[ph];
+                for (int i = 0; i <= q.lh; ++i)
+                    for (int j = 0; j <= q.lw; ++j) {
+                        const long long got = base + (long long)i * (f.patch_row_bytes / 4) + ((j & 1) ? f.coff1[pw] : f.coff0[pw]) + (j >> 1);
+                        const int r = 2 * s * by + s * (d.ph[ph].j + i) + d.ph[ph].p;
+                        const int cc = 2 * s * bx + s * (d.pw[pw].j + j) + d.pw[pw].p;
+                        CHECK(r < f.nrows && cc < f.lw_in);
+                        CHECK(got == (long long)c * f.chan_floats + staged(r, cc));
+                        CHECK(got >= 0 && (got + 1) * 4 <= (long long)C * f.chan_floats * 4);
+                    }
+            }
+        }
+    }
+    CHECK(rows == f.rows_total && uf == f.uf_halves && rows <= kF16MaxRows);
+    CHECK((long long)K * d.OH * d.OW * 4 < (1LL << 31) && uf * 2 < ((size_t)1 << 31));
+    dwm_plan_destroy(p);
+    return 1;
+}
+
 int main(int argc, char** argv)
 {
     const int iters = argc > 1 ? std::atoi(argv[1]) : 3000;
-    int ok = 0, tried = 0, small = 0;
+    int ok = 0, tried = 0, small = 0, single16 = 0;
     // the benchmark layers and corner shapes first
     const int fixed[][9] = {
         {1, 16, 32, 32, 16, 5, 5, 1, 2},   {32, 128, 56, 56, 256, 3, 3, 2, 1}, {32, 256, 28, 28, 256, 7, 7, 1, 3},
@@ -264,6 +329,7 @@ int main(int argc, char** argv)
         ++tried;
         ok += walk(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
         small += walk_bwd_small(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
+        single16 += walk_fused16(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
     }
     CHECK(dwm_plan_create(nullptr, 1, 1, 3, 3, 1, 3, 3, 1, 1) == DWM_ERR_INVALID_ARG);
     CHECK(dwm_plan_destroy(nullptr) == DWM_ERR_INVALID_ARG);
@@ -277,8 +343,10 @@ int main(int argc, char** argv)
         ++tried;
         ok += walk(N, C, H, W, K, R, S, s, P);
         small += walk_bwd_small(N, C < 20 ? C : C % 9 + 1, H, W, K, R, S, s, P);
+        single16 += walk_fused16(N, C < 20 ? C : C % 9 + 1, H, W, K, R, S, s, P);
     }
-    CHECK(small > tried / 8);
-    std::printf("planner fuzz: %d shapes tried, %d planned, %d with a single-kernel data gradient\n", tried, ok, small);
+    CHECK(small > tried / 8 && single16 > tried / 8);
+    std::printf("planner fuzz: %d shapes tried, %d planned, %d with a single-kernel data gradient, %d with a 16-bit single kernel\n",
+                tried, ok, small, single16);
     return ok > tried / 2 ? 0 : 3;
 }
