@@ -647,14 +647,20 @@ static bool small_setup(dwm_bwd_filter_plan& bp, int max_rows)
     }
     if (n1 > kMaxClasses || n2 > kMaxClasses) return false;
     WgradArgs& a = bp.a;
-    bp.small_kt = a.Kp / 64;
     const long long t16 = ((long long)d.T + 15) / 16 * 16;
-    long long want = std::max(1, 2 * kNumCUs / bp.small_kt);
+    const int small_kt = a.Kp / 64;
+    long long want = std::max(1, 2 * kNumCUs / small_kt);
     long long per = (t16 + want - 1) / want;
     per = std::max<long long>(64, (per + 15) / 16 * 16);
     const long long nsplit = (t16 + per - 1) / per;
     if (per > 0x7fffffffLL || nsplit > 65535 * 16) return false;
+    // (the plan's state is touched only once nothing can fail any more: if this form is refused, the GEMM form
+    // must find its own offsets untouched)
+    long long total = 0;
+    for (int c = 0; c < d.ncls; ++c) total += (long long)(d.cls[c].lh + 1) * (d.cls[c].lw + 1) * a.Kp * d.cls[c].Lpad;
+    if (total * nsplit > (1LL << 40)) return false;
     long long off = 0;
+    bp.small_kt = small_kt;
     bp.n_pass = 0;
     for (int c = 0; c < d.ncls; ++c) {
         const DevClass& q = d.cls[c];
@@ -678,7 +684,6 @@ static bool small_setup(dwm_bwd_filter_plan& bp, int max_rows)
         }
         off += (long long)planes * a.Kp * q.Lpad;
     }
-    if (off * nsplit > (1LL << 40)) return false;
     for (int c = 0; c < bp.n_pass; ++c) bp.sc[c].split_floats = off;
     a.split_floats = off;
     a.splits = (int)nsplit;  // what the plan reports; the final kernel reads the summed dU (one "split")
