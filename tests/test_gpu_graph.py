@@ -77,6 +77,7 @@ def _replay_and_compare(g, out, eager, eager_again):
 @pytest.mark.parametrize("shape", [
     (2, 10, 20, 24, 150, 3, 3, 2, 1),    # four sub-convolutions, one merged input transform, one batched contraction
     (2, 24, 14, 14, 40, 7, 7, 1, 3),     # one sub-convolution on the forward kernels (tiles cut into ranges)
+    (2, 3, 37, 35, 33, 7, 7, 2, 3),      # three channels: the whole gradient in one kernel
 ])
 def test_backward_data_replays_from_a_graph(shape):
     N, C, H, W, K, R, S, s, P = shape
@@ -144,7 +145,8 @@ def test_backward_filter_replays_from_a_graph(shape):
 
 @pytest.mark.parametrize("shape", [
     (2, 64, 30, 30, 64, 3, 3, 1, 1),     # LDS-staged input transform, whole and split tiles
-    (2, 3, 37, 35, 33, 7, 7, 2, 3),      # three channels: eight-row items across parts and channels
+    (2, 3, 37, 35, 33, 7, 7, 2, 3),      # three channels: the 16-bit single kernel
+    (2, 24, 14, 14, 40, 7, 7, 1, 3),     # 24 channels: eight-row items of the LDS-staged input transform
 ])
 def test_half_precision_forward_replays_from_a_graph(shape):
     N, C, H, W, K, R, S, s, P = shape
