@@ -495,6 +495,11 @@ __global__ __launch_bounds__(256, 2) void fused_forward_kernel(DevPlan P, FusedA
             }
         }
 
+        // The next slice's first operands are on their way: they are waited for HERE, before the stores, because
+        // the counter of outstanding memory operations runs in issue order -- a wait placed after the stores (whose
+        // number depends on the lane's tile and filters, so the compiler cannot count past them) would wait for
+        // the stores' round trip as well.
+        if constexpr (PAIRS) __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0), nothing else
         // ---- scatter: lane (ln, lq) holds tile ln and filters 32*ks + 16*half + 4*lq + r ----
         if (tile_ok) {
             if (dense) {
