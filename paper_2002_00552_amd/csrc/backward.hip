@@ -327,7 +327,10 @@ dwm_status_t dwm_bwd_data_plan_create(dwm_bwd_data_plan_t** out, int N, int C, i
         }
     // the single-kernel form: chosen where the sub-convolutions would have only a handful of filters
     bp->small_ok = bwd_small_setup(N, C, H, W, K, R, S, stride, pad, &bp->small);
-    bp->small_default = bp->small_ok && C <= 16 && bp->small.nf <= 64 && bp->small.lds_bytes <= 78 * 1024 &&
+    // (LDS: room for the workgroups per CU its registers allow -- one where a wave holds several column blocks of
+    // sixteen planes, else at least two)
+    const size_t small_lds_max = (bp->small.nb > 1 && bp->small.four ? 152 : 78) * 1024;
+    bp->small_default = bp->small_ok && C <= 16 && bp->small.nf <= 64 && bp->small.lds_bytes <= small_lds_max &&
                         bp->small.eff_pct >= 50;
     bp->variant_path = -1;
     bp->u_small_off = off;

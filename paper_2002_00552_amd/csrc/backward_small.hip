@@ -47,7 +47,7 @@ __device__ __forceinline__ float bs_g_row(int i, float v0, float v1, float v2)
 }
 
 // ---------------------------------------------------------------------------------
-// Filter copy UB[column block][chunk][step][plane, lane]: the A operands exactly as a chunk
+// Filter copy UB[chunk][column block][step][plane, lane]: the A operands exactly as a chunk
 // lies in LDS (a chunk padded to whole KB; the padding is copied and never read).  Lane (i, q)
 // of a step holds column 16*cb + i and the step's row q; the rows of a chunk are (pair of
 // pieces, channel of the chunk).  One thread per (column, channel, pair).
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void bwd_small_filter_kernel(BwdSmallArgs F, i
                                                                float* __restrict__ U)
 {
     const int kpad = F.nchunks * F.ck;
-    const long long total = (long long)F.ncb * 16 * kpad * F.npp;
+    const long long total = (long long)F.ncbp * 16 * kpad * F.npp;  // (blocks that pad the count to whole groups: zeros)
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
     const int pp = (int)(e % F.npp);
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void bwd_small_filter_kernel(BwdSmallArgs F, i
     const int nfreq = F.four ? 4 : 3, planes = nfreq * nfreq;
     const int chunk = k / F.ck, row = pp * F.ck + (k % F.ck);
     const int step = row >> 2, lane = (row & 3) * 16 + (f & 15);
-    float* dst = U + ((size_t)(f >> 4) * F.nchunks + chunk) * (size_t)F.us_floats + (size_t)step * (planes * 64);
+    float* dst = U + ((size_t)chunk * F.ncbp + (f >> 4)) * (size_t)F.us_floats + (size_t)step * (planes * 64);
 #pragma unroll
     for (int fh = 0; fh < 4; ++fh)
 #pragma unroll
@@ -115,9 +115,11 @@ __device__ __forceinline__ void bs_at(const bs_float4 (&m)[NF], bs_float4 (&o)[2
     if constexpr (NF == 4) o[1] -= m[3];
 }
 
-// (nine planes: registers for three waves per SIMD; sixteen: two)
-template <bool FOUR>
-__global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallArgs F, const float* __restrict__ dy,
+// NB: blocks of 16 columns a wave keeps accumulators for (one pass over dy serves them all: B^T d B is computed
+// once).  Waves per SIMD by the registers that takes: nine planes 3 (NB = 1) or 2; sixteen planes 2 (NB = 1) or 1
+// (up to 192 accumulator registers: the MFMAs of one wave, 48 a step, then cover its own vector work).
+template <bool FOUR, int NB>
+__global__ __launch_bounds__(256, FOUR ? (NB == 1 ? 2 : 1) : (NB == 1 ? 3 : 2)) void bwd_small_kernel(BwdSmallArgs F, const float* __restrict__ dy,
                                                            const float* __restrict__ U, float* __restrict__ dx)
 {
     constexpr int NF = FOUR ? 4 : 3, PL = NF * NF, G4 = PL / 4, REM = PL - 4 * G4;
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
     // the filter copy | per pair of pieces the byte offsets of patch column 0 and 1
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;  // LDS byte address of the array
     const uint32_t xs_bytes = (uint32_t)F.xs_floats * 4u, us_bytes = (uint32_t)F.us_floats * 4u;
-    const uint32_t us0 = 2u * xs_bytes, tab0 = us0 + 2u * us_bytes;
+    const uint32_t us0 = 2u * xs_bytes, tab0 = us0 + 2u * (uint32_t)NB * us_bytes;  // (a stage holds NB column blocks)
     const char* ldsb = reinterpret_cast<const char*>(lds);
 
     const int tid = threadIdx.x;
@@ -199,21 +201,23 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
                 }
         };
 
-        for (int cb = 0; cb < F.ncb; ++cb) {
-            // a chunk of the filter copy -> LDS by DMA: 16 bytes per lane, 1 KB per wave and instruction
-            const float* ucb = U + (size_t)cb * F.nchunks * F.us_floats;
+        for (int cb0 = 0; cb0 < F.ncb; cb0 += NB) {
+            // a chunk of the filter copy (NB column blocks, adjacent in memory) -> LDS by DMA: 16 bytes per lane,
+            // 1 KB per wave and instruction
             auto stage_u = [&](int chunk, int buf) {
-                const float* src = ucb + (size_t)chunk * F.us_floats;
-                const uint32_t dst = lds0 + us0 + (uint32_t)buf * us_bytes;
-                for (uint32_t o = (uint32_t)wave * 1024u; o < us_bytes; o += 4096u)  // us_bytes: a multiple of 1 KB
+                const float* src = U + ((size_t)chunk * F.ncbp + cb0) * F.us_floats;
+                const uint32_t dst = lds0 + us0 + (uint32_t)buf * (uint32_t)NB * us_bytes;
+                for (uint32_t o = (uint32_t)wave * 1024u; o < (uint32_t)NB * us_bytes; o += 4096u)  // whole KBs
                     dma16s(src, o + (uint32_t)lane * 16u, (uint32_t)__builtin_amdgcn_readfirstlane((int)(dst + o)));
             };
 
-            bs_float4 acc[NF][NF];
+            bs_float4 acc[NB][NF][NF];
 #pragma unroll
-            for (int i = 0; i < NF; ++i)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int j = 0; j < NF; ++j) acc[i][j] = bs_float4{0.f, 0.f, 0.f, 0.f};
+                for (int i = 0; i < NF; ++i)
+#pragma unroll
+                    for (int j = 0; j < NF; ++j) acc[nb][i][j] = bs_float4{0.f, 0.f, 0.f, 0.f};
 
             stage_load(0);
             stage_u(0, 0);
@@ -230,8 +234,8 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
                     stage_u(ci + 1, buf ^ 1);
                 }
                 const char* xb = ldsb + (uint32_t)buf * xs_bytes + lane_base;
-                const char* ub = ldsb + us0 + (uint32_t)buf * us_bytes + (uint32_t)lane * 16u;
-                const char* ur = ldsb + us0 + (uint32_t)buf * us_bytes + (uint32_t)(G4 * 1024) + (uint32_t)lane * 4u;
+                const char* ub = ldsb + us0 + (uint32_t)buf * (uint32_t)NB * us_bytes + (uint32_t)lane * 16u;
+                const char* ur = ub + (uint32_t)(G4 * 1024) - (uint32_t)lane * 12u;  // (lane * 4 past the 16-byte groups)
 
                 // step st of a chunk = (pair of pieces st >> glog, group st & (G - 1))
                 auto read_tab = [&](int st) {
@@ -251,20 +255,22 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
                         if constexpr (FOUR) d[i][3] = q1[2];
                     }
                 };
-                auto read_a = [&](int st, float (&a)[PL]) {
-                    const char* us = ub + (uint32_t)st * (uint32_t)(PL * 256);
+                auto read_a = [&](int st, float (&a)[NB][PL]) {
 #pragma unroll
-                    for (int g = 0; g < G4; ++g) {
-                        const bs_float4 v = *reinterpret_cast<const bs_float4*>(us + g * 1024);
-                        a[4 * g] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const uint32_t so = (uint32_t)nb * us_bytes + (uint32_t)st * (uint32_t)(PL * 256);
+#pragma unroll
+                        for (int g = 0; g < G4; ++g) {
+                            const bs_float4 v = *reinterpret_cast<const bs_float4*>(ub + so + g * 1024);
+                            a[nb][4 * g] = v.x; a[nb][4 * g + 1] = v.y; a[nb][4 * g + 2] = v.z; a[nb][4 * g + 3] = v.w;
+                        }
+#pragma unroll
+                        for (int r = 0; r < REM; ++r) a[nb][4 * G4 + r] = *reinterpret_cast<const float*>(ur + so + r * 256);
                     }
-#pragma unroll
-                    for (int r = 0; r < REM; ++r)
-                        a[4 * G4 + r] = *reinterpret_cast<const float*>(ur + (uint32_t)st * (uint32_t)(PL * 256) + r * 256);
                 };
                 // operands (patch and A) travel a step ahead, the table entries of their pairs of pieces a pass ahead
-                auto step = [&](auto next_tag, int st, const float (&d)[NF][NF], float (&dn)[NF][NF], const float (&a)[PL],
-                                float (&an)[PL], int2 t) {
+                auto step = [&](auto next_tag, int st, const float (&d)[NF][NF], float (&dn)[NF][NF], const float (&a)[NB][PL],
+                                float (&an)[NB][PL], int2 t) {
                     if constexpr (decltype(next_tag)::value) {
                         read_a(st + 1, an);
                         read_patch(st + 1, t, dn);
@@ -282,13 +288,15 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
 #pragma unroll
                     for (int i = 0; i < NF; ++i) bs_bt<NF>(tmp[i], v[i]);
 #pragma unroll
-                    for (int i = 0; i < NF; ++i)
+                    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                        for (int j = 0; j < NF; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i * NF + j], v[i][j], acc[i][j], 0, 0, 0);
+                        for (int i = 0; i < NF; ++i)
+#pragma unroll
+                            for (int j = 0; j < NF; ++j)
+                                acc[nb][i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[nb][i * NF + j], v[i][j], acc[nb][i][j], 0, 0, 0);
                 };
 
-                float d0[NF][NF], d1[NF][NF], a0[PL], a1[PL];
+                float d0[NF][NF], d1[NF][NF], a0[NB][PL], a1[NB][PL];
                 int2 t1 = read_tab(1);
                 read_a(0, a0);
                 read_patch(0, tab_first, d0);
@@ -309,11 +317,14 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
             }
 
             // ---- A^T M A, then the lane's pixels: columns 16*cb + 4*lq + r of tile (ty, tx) ----
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+            const int cb = cb0 + nb;
             bs_float4 Y[2][2];
             {
                 bs_float4 t[NF][2];
 #pragma unroll
-                for (int i = 0; i < NF; ++i) bs_at<NF>(acc[i], t[i]);
+                for (int i = 0; i < NF; ++i) bs_at<NF>(acc[nb][i], t[i]);
 #pragma unroll
                 for (int bcol = 0; bcol < 2; ++bcol) {
                     bs_float4 m[NF], o[2];
@@ -324,7 +335,7 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
                     Y[1][bcol] = o[1];
                 }
             }
-            if (tile_ok) {
+            if (tile_ok && cb < F.ncb) {
                 const int f0 = cb * 16 + lq * 4;
                 const int s = F.s, ss = s * s;
                 float* dxn = dx + (size_t)n * F.C * F.H * F.W;
@@ -392,13 +403,14 @@ __global__ __launch_bounds__(256, FOUR ? 2 : 3) void bwd_small_kernel(BwdSmallAr
                     }
                 }
             }
+            }  // nb
         }
     }
 }
 
 dwm_status_t launch_bwd_small_filter(const BwdSmallArgs& a, int R, int S, const float* w, float* U, void* stream)
 {
-    const long long total = (long long)a.ncb * 16 * a.nchunks * a.ck * a.npp;
+    const long long total = (long long)a.ncbp * 16 * a.nchunks * a.ck * a.npp;
     if (total > 0x7fffffffLL * 256) return DWM_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(bwd_small_filter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a,
                        R, S, w, U);
@@ -407,20 +419,27 @@ dwm_status_t launch_bwd_small_filter(const BwdSmallArgs& a, int R, int S, const 
 
 dwm_status_t launch_bwd_small(const BwdSmallArgs& a, const float* dy, const float* U, float* dx, void* stream)
 {
-    auto kernel = a.four ? bwd_small_kernel<true> : bwd_small_kernel<false>;
+    using kernel_t = void (*)(BwdSmallArgs, const float*, const float*, float*);
+    static const kernel_t kernels[2][3] = {{bwd_small_kernel<false, 1>, bwd_small_kernel<false, 2>, bwd_small_kernel<false, 3>},
+                                           {bwd_small_kernel<true, 1>, bwd_small_kernel<true, 2>, bwd_small_kernel<true, 3>}};
+    if (a.nb < 1 || a.nb > 3 || a.ncbp % a.nb != 0 || a.ncbp < a.ncb) return DWM_ERR_INVALID_ARG;
+    kernel_t kernel = kernels[a.four ? 1 : 0][a.nb - 1];
     if (a.lds_bytes > 64 * 1024) {
         static const hipError_t attr = [] {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_small_kernel<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            return hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_small_kernel<false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            for (int f = 0; f < 2; ++f)
+                for (int n = 0; n < 3; ++n) {
+                    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[f][n]),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                    if (e != hipSuccess) return e;
+                }
+            return hipSuccess;
         }();
         if (attr != hipSuccess) return DWM_ERR_HIP;
     }
-    // persistent workgroups, as many per CU as fit (fewer where there are fewer blocks)
+    // persistent workgroups, as many per CU as registers and LDS allow (fewer where there are fewer blocks)
     const long long nblocks = (long long)a.N * a.nbh * a.nbw;
-    const int per_cu = a.four ? 2 : std::max(1, std::min(3, (int)(156 * 1024 / a.lds_bytes)));
+    const int by_regs = a.four ? (a.nb == 1 ? 2 : 1) : (a.nb == 1 ? 3 : 2);
+    const int per_cu = std::max(1, std::min(by_regs, (int)(156 * 1024 / a.lds_bytes)));
     dim3 grid((unsigned)std::min<long long>(nblocks, per_cu * kNumCUs)), block(256);
     hipLaunchKernelGGL(kernel, grid, block, a.lds_bytes, (hipStream_t)stream, a, dy, U, dx);
     return hipGetLastError() == hipSuccess ? DWM_OK : DWM_ERR_HIP;

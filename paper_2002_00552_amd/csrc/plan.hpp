@@ -255,6 +255,7 @@ constexpr int kBsMaxSlots = 8;   // (group of four channels, staged element) pai
 struct BwdSmallArgs {
     int N, C, H, W, K, OH, OW, s;
     int nf, ncb;                                // columns C*s*s, blocks of 16 columns
+    int nb, ncbp;                               // blocks a wave accumulates at once (1..3); ncb rounded up to whole groups
     int Lh, Lw, nwh, nww;                       // window offset and taps per dimension
     int nph, npw, npp;                          // pieces per dimension, pairs of pieces
     int jh[kBsMaxPieces], lh[kBsMaxPieces];     // first tap and length of the pieces

@@ -236,6 +236,11 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
     if (nf > 256) return false;
     f.nf = (int)nf;
     f.ncb = (f.nf + 15) / 16;
+    // column blocks a wave accumulates in one pass over dy: the fewest passes, then the fewest blocks per pass
+    f.nb = 1;
+    for (int nb = 2; nb <= 3; ++nb)
+        if ((f.ncb + nb - 1) / nb < (f.ncb + f.nb - 1) / f.nb) f.nb = nb;
+    f.ncbp = (f.ncb + f.nb - 1) / f.nb * f.nb;
     if (!bwd_small_dim(R, s, pad, f.ra_h, f.re_h, f.rn_h, &f.Lh, &f.nwh, &f.nph, f.jh, f.lh)) return false;
     if (!bwd_small_dim(S, s, pad, f.ra_w, f.re_w, f.rn_w, &f.Lw, &f.nww, &f.npw, f.jw, f.lw)) return false;
     f.npp = f.nph * f.npw;
@@ -283,15 +288,16 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
         long long lwp = lwp0, group = 0;
         int glog = -1;
         // (nine planes leave registers for three waves per SIMD: three workgroups per CU, 52 KB each;
-        // sixteen planes: two, 79 KB each; a chunk of four channels only with an even number of steps)
-        const int wg_kb = f.four ? 79 : 52;
+        // sixteen planes: two, 79 KB each; with several column blocks per wave two and one, 79 and 150 KB;
+        // a chunk of four channels only with an even number of steps)
+        const int wg_kb = f.nb > 1 ? (f.four ? 150 : 79) : (f.four ? 79 : 52);
         for (int g = 3; g >= 0 && glog < 0; --g) {
             if ((1 << g) << nelog > kBsMaxSlots || ((f.npp << g) & 1)) continue;
             const long long us = ((long long)(f.npp << g) * planes * 64 + 255) / 256 * 256;
             int best_c = 1 << 30;
             for (long long l = lwp0; l < lwp0 + 4; ++l) {
                 const long long grp = nrows * 2 * l;  // elements of four floats
-                const long long bytes = 2 * ((grp << g) * 4 + us) * (long long)sizeof(float);
+                const long long bytes = 2 * ((grp << g) * 4 + f.nb * us) * (long long)sizeof(float);
                 if (bytes > (g > (f.npp & 1) ? wg_kb : 150) * 1024) continue;
                 const int c = conflicts(bw, bh, (int)l);
                 if (c < best_c) { best_c = c; lwp = l; group = grp; glog = g; }
@@ -328,8 +334,8 @@ bool bwd_small_setup(int N, int C, int H, int W, int K, int R, int S, int stride
         f.po1[pp] = 8 * (jh * f.row_elems + ((jw + 1) & 1) * f.lwp + ((jw + 1) >> 1));
     }
     // LDS: two staged chunks of dy, two chunks of the filter copy, the table of patch offsets
-    f.lds_bytes = 2 * ((size_t)f.xs_floats + f.us_floats) * sizeof(float) + kBsMaxPairs * 8;
-    f.u_floats = (size_t)f.ncb * f.nchunks * f.us_floats;
+    f.lds_bytes = 2 * ((size_t)f.xs_floats + (size_t)f.nb * f.us_floats) * sizeof(float) + kBsMaxPairs * 8;
+    f.u_floats = (size_t)f.ncbp * f.nchunks * f.us_floats;
     *out = f;
     return true;
 }

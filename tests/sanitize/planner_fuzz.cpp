@@ -169,12 +169,13 @@ static int walk_bwd_small(int N, int C, int H, int W, int K, int R, int S, int s
     const int G = 1 << f.glog, NE = 1 << f.nelog;
     const long long xs_bytes = 4LL * f.xs_floats, us_bytes = 4LL * f.us_floats;
     const long long pair_bytes = 8LL * f.group_elems, group_bytes = 2 * pair_bytes, row_bytes = 8LL * f.row_elems;
-    CHECK((long long)f.lds_bytes == 2 * (xs_bytes + us_bytes) + kBsMaxPairs * 8 && f.lds_bytes <= 160 * 1024);
+    CHECK((long long)f.lds_bytes == 2 * (xs_bytes + f.nb * us_bytes) + kBsMaxPairs * 8 && f.lds_bytes <= 160 * 1024);
     CHECK(G * group_bytes <= xs_bytes && xs_bytes % 16 == 0 && us_bytes % 1024 == 0);
     CHECK(f.ck == 4 * G && f.steps == f.npp * G && f.steps % 2 == 0 && f.steps >= 2);
     CHECK(f.nchunks * f.ck >= K && (f.nchunks - 1) * f.ck < K);
     CHECK((long long)f.steps * planes * 256 <= us_bytes);
-    CHECK(f.u_floats == (size_t)f.ncb * f.nchunks * f.us_floats);
+    CHECK(f.nb >= 1 && f.nb <= 3 && f.ncbp >= f.ncb && f.ncbp % f.nb == 0 && f.ncbp < f.ncb + f.nb);
+    CHECK(f.u_floats == (size_t)f.ncbp * f.nchunks * f.us_floats);
     CHECK(G * NE <= kBsMaxSlots && f.nrows * f.lw_in <= 256 * NE);
     CHECK(f.row_elems == 2 * f.lwp && f.group_elems == f.nrows * f.row_elems && f.tile_row_step == 2 * f.row_elems);
     // a staged element (r, c) of a channel pair: where the staging writes it; all distinct, all inside
