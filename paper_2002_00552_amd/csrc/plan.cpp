@@ -60,12 +60,14 @@ int at_entry(int l, int a, int f)
 // 64x64 tiles; the deepest reduction chunk the padding allows, except that long launches take 32-step chunks in three
 // stages: 48 KB of LDS instead of 64, so a CU holds three workgroups, and a chunk's loads have a whole chunk to land
 // in.  "Long" is three or more rounds of whole tiles (a tile's start-up and stores hide behind two others: measured
-// 3-10 % faster on 784- and 1568-tile layers) or a reduction of 8192 rows or more per tile (rows = all planes'
-// padded reductions; measured with 392 tiles: 25 600 rows 0.806 -> 0.765 ms, 3200 rows 0.130 -> 0.132 ms).
+// 3-10 % faster on 784- and 1568-tile layers) or, above one tile per CU, a reduction of 8192 rows or more per tile
+// (rows = all planes' padded reductions; measured with 392 tiles: 25 600 rows 0.806 -> 0.765 ms, 3200 rows 0.130 ->
+// 0.132 ms; with at most one tile per CU every tile is cut into ranges of its own and the deep chunks measure 1-7 %
+// faster on 100- to 256-tile layers).
 int default_contract_variant(int lgran, long long K, long long T, long long rows)
 {
     const long long tiles = ((K + 63) / 64) * ((T + 63) / 64);
-    return lgran >= 64 ? (tiles >= 3 * dwm::kNumCUs || rows >= 8192 ? 11 : 12) : lgran >= 32 ? 11 : 10;
+    return lgran >= 64 ? (tiles >= 3 * dwm::kNumCUs || (tiles > dwm::kNumCUs && rows >= 8192) ? 11 : 12) : lgran >= 32 ? 11 : 10;
 }
 
 long long plane_rows(const dwm_plan& p)
