@@ -24,6 +24,26 @@ def test_library_exports_every_declared_symbol():
     assert declared == dwm.EXPORTS  # the binding carries the same names
 
 
+def test_probe_library_exports_its_entry_points():
+    """The peak probes beside bench.py (their own library): every PROBE_API function is exported, and the
+    operand-delivery probe refuses arguments that would take its addresses outside its buffers."""
+    import bench_probes
+    if not os.path.exists(bench_probes.PROBE_LIB):
+        bench_probes.build()
+    src = open(os.path.join(ROOT, "bench_probes.hip")).read()
+    declared = sorted(set(re.findall(r"PROBE_API\s+int\s+(dwm_probe_\w+)\s*\(", src)))
+    assert declared == ["dwm_probe_copy", "dwm_probe_fill", "dwm_probe_mfma", "dwm_probe_mix", "dwm_probe_read"]
+    L = bench_probes.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    # refused on the host, before anything is launched: too many workgroups, a mask that is not 2^n - 1, a stream
+    # stride whose 128 streams would not fit
+    assert L.dwm_probe_mix(None, None, 0, 1, 257, 0, (1 << 20) - 1, None) == 1
+    assert L.dwm_probe_mix(None, None, 0, 1, 196, 0, (1 << 20), None) == 1
+    assert L.dwm_probe_mix(None, None, 0, 1, 196, (1 << 24) + 1, (1 << 20) - 1, None) == 1
+    assert L.dwm_probe_mix(None, None, 9, 0, 196, 0, (1 << 20) - 1, None) == 1
+
+
 def _plan(*a):
     p = dwm.dwm_plan_create(*a)
     return p, dwm.dwm_plan_info(p)
