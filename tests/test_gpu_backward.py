@@ -106,6 +106,9 @@ SMALL_SHAPES = [sh for sh in SHAPES if _single_kernel_applies(sh)] + [
     (1, 8, 24, 24, 12, 6, 6, 2, 2),      # 32 columns
     (2, 3, 9, 200, 6, 7, 7, 2, 3),       # a wide, flat image: blocks of one row of tiles
     (600, 3, 12, 12, 5, 5, 5, 2, 2),     # more blocks than persistent workgroups: each takes several
+    (1, 16, 20, 20, 6, 4, 4, 2, 1),      # 64 columns: two groups of two column blocks per wave
+    (1, 5, 18, 22, 7, 7, 7, 4, 3),       # 80 columns: a group of three blocks, then two and a padding block
+    (2, 7, 15, 17, 9, 5, 5, 3, 1),       # 63 columns, stride 3: the last block one column short
 ]
 
 
