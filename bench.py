@@ -10,7 +10,9 @@ timed region (it is a function of the weights only).  Prints ONE JSON line.
 --config picks one of the five layers of dwm_workloads.CONFIGS (default 2: the 7x7 stride-1
 layer with 256 channels, the largest of the five, 161 GFLOP of direct convolution per step).
 The headline line also carries `per_config`: every one of the five layers measured the same
-way in the same run (the paper's runtime table, Table 4, is per layer as well).
+way in the same run (the paper's runtime table, Table 4, is per layer as well), and under
+`other_paths` the same layer's binary16 and bfloat16 forward pass and its two gradients, each
+timed as its own mode of this script times it (--half, --bf16, --backward-data, --backward-filter).
 --paper-layer KERNEL,HW,STRIDE runs one of the paper's own single-layer shapes instead
 (Sec. 5: batch 256, same padding, 14x14 maps with 256 channels/filters or 28x28 with 128,
 standard-normal inputs AND weights).
@@ -148,7 +150,7 @@ def bench_backward_data(args, L, x, w):
                            "mse_vs_fp64": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
                            "sampled_outputs": int(idx.size)}
     dwm.dwm_bwd_data_plan_destroy(plan)
-    print(json.dumps(out))
+    return out
 
 
 def bench_backward_filter(args, L, x, w):
@@ -199,7 +201,7 @@ def bench_backward_filter(args, L, x, w):
                            "mse_vs_fp64": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
                            "checked_filters": len(ks)}
     dwm.dwm_bwd_filter_plan_destroy(plan)
-    print(json.dumps(out))
+    return out
 
 
 def bench_half(args, L, x, w, bf16=False):
@@ -306,7 +308,7 @@ def bench_half(args, L, x, w, bf16=False):
                            "mse_vs_fp64_direct": mse, "log10_mse_plus_10": float(np.log10(mse) + 10),
                            "sampled_outputs": int(idx.size)}
     fn("plan_destroy")(plan)
-    print(json.dumps(out))
+    return out
 
 
 def measure_forward(L, index, steps, warmup, args, check=True):
@@ -487,10 +489,13 @@ def main():
     if args.backward_data or args.backward_filter or args.half or args.bf16:
         x, w = wl.make_layer_tensors(L, index)
         if args.backward_data:
-            return bench_backward_data(args, L, x, w)
-        if args.backward_filter:
-            return bench_backward_filter(args, L, x, w)
-        return bench_half(args, L, x, w, bf16=args.bf16)
+            out = bench_backward_data(args, L, x, w)
+        elif args.backward_filter:
+            out = bench_backward_filter(args, L, x, w)
+        else:
+            out = bench_half(args, L, x, w, bf16=args.bf16)
+        print(json.dumps(out))
+        return
 
     res, x, w = measure_forward(L, index, args.steps, args.warmup, args, check=not args.no_check)
     out = {
@@ -519,6 +524,22 @@ def main():
             if "accuracy" in r:
                 e["max_rel_err"] = r["accuracy"]["max_rel_err"]
                 e["log10_mse_plus_10"] = r["accuracy"]["log10_mse_plus_10"]
+            # the other paths of the same layer, each timed like its own mode of this script
+            import copy
+            a2 = copy.copy(args)
+            a2.steps, a2.warmup = min(args.steps, 100), min(args.warmup, 30)
+            a2.forward_variant = a2.contract_variant = a2.input_variant = a2.bwd_path = -1
+            xi, wi = wl.make_layer_tensors(Li, i)
+            other = {}
+            for name, fn in (("binary16_forward", lambda: bench_half(a2, Li, xi, wi)),
+                             ("bfloat16_forward", lambda: bench_half(a2, Li, xi, wi, bf16=True)),
+                             ("backward_data", lambda: bench_backward_data(a2, Li, xi, wi)),
+                             ("backward_filter", lambda: bench_backward_filter(a2, Li, xi, wi))):
+                o = fn()
+                other[name] = {"ms_per_step": o["ms_per_step"], "path": o["config"].get("path"),
+                               "max_rel_err": o.get("accuracy", {}).get("max_rel_err")}
+            del xi, wi
+            e["other_paths"] = other
             per.append(e)
         out["per_config"] = per
     print(json.dumps(out))
