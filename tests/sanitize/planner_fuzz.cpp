@@ -332,6 +332,23 @@ int main(int argc, char** argv)
         small += walk_bwd_small(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
         single16 += walk_fused16(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]);
     }
+    // the contraction the planner picks: the three-stage ring of 32-row chunks (11) for three rounds of tiles and for
+    // long reductions above one tile per CU, the two-stage ring of 64-row chunks (12) otherwise
+    {
+        const int pinned[][10] = {
+            {32, 256, 28, 28, 256, 7, 7, 1, 3, 11},   // 392 tiles of 25 600 rows
+            {32, 128, 56, 56, 256, 3, 3, 2, 1, 12},   // 392 tiles of 3200 rows
+            {16, 256, 28, 28, 256, 7, 7, 1, 3, 12},   // 196 tiles: every tile cut into ranges of its own
+            {64, 256, 28, 28, 256, 3, 3, 1, 1, 11},   // 784 tiles: three rounds
+            {8, 64, 28, 28, 64, 3, 3, 1, 1, 12},      // 25 tiles of short reductions
+        };
+        for (const auto& f : pinned) {
+            dwm_plan_t* p = nullptr;
+            CHECK(dwm_plan_create(&p, f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7], f[8]) == DWM_OK);
+            CHECK(p->geo.variant == f[9]);
+            CHECK(dwm_plan_destroy(p) == DWM_OK);
+        }
+    }
     CHECK(dwm_plan_create(nullptr, 1, 1, 3, 3, 1, 3, 3, 1, 1) == DWM_ERR_INVALID_ARG);
     CHECK(dwm_plan_destroy(nullptr) == DWM_ERR_INVALID_ARG);
     CHECK(dwm_plan_filter_bytes(nullptr) == 0 && dwm_plan_workspace_bytes(nullptr) == 0);
