@@ -27,6 +27,11 @@
  *                              unrounded.  The paper does not say where its FP16
  *                              implementation rounds; this reading is the one a matrix
  *                              unit with FP16 operands and a wide accumulator computes.
+ *                              U is rounded from its exact value; V from B^T d B evaluated in
+ *                              binary32, columns first (part_input_transform_binary32): the
+ *                              precision in which the 16-bit value of an element is decided
+ *                              is part of the reading, and binary32 is what such a path
+ *                              transforms in (exact for all but sums spanning 13+ binades).
  *   O2b oracle_dwm_bf16_f64    the same reading with bfloat16 storage (8 significant bits,
  *                              binary32's exponent range): the other 16-bit format such
  *                              matrix units take.
@@ -335,6 +340,53 @@ int oracle_part_input_transform(const float* x, int C, int H, int W, int s, int 
     return 0;
 }
 
+/*
+ * The same transform evaluated in binary32: B^T applied down the columns of the patch first, then
+ * along the rows, every sum rounded to binary32.  Each row of B^T has at most two entries (+-1), so
+ * each of the two passes is ONE addition or subtraction per output and the order inside a pass does
+ * not matter.  With 16-bit inputs the result equals the exact one unless a sum spans more than 13
+ * binades (binary16) or 16 binades (bfloat16); it is the arithmetic in which the 16-bit paths decide
+ * which 16-bit value an element of V becomes (the paper fixes no precision for its FP16 version).
+ */
+static int part_input_transform_binary32(const float* x, int C, int H, int W, int s, int P,
+                                         int TH, int TW, int n, const oracle_part* pt, double* V)
+{
+    const int lh = pt->lh, lw = pt->lw, th = lh + 1, tw = lw + 1;
+    for (int c = 0; c < C; ++c)
+        for (int ty = 0; ty < TH; ++ty)
+            for (int tx = 0; tx < TW; ++tx) {
+                float d[4][4], Bd[4][4];
+                for (int a = 0; a < th; ++a)
+                    for (int b = 0; b < tw; ++b) {
+                        int ih = s * (2 * ty + pt->jh + a) + pt->ph - P;
+                        int iw = s * (2 * tx + pt->jw + b) + pt->pw - P;
+                        d[a][b] = (ih < 0 || ih >= H || iw < 0 || iw >= W)
+                                      ? 0.0f
+                                      : x[(((size_t)n * C + c) * H + ih) * W + iw];
+                    }
+                for (int i = 0; i < th; ++i)
+                    for (int b = 0; b < tw; ++b) {
+                        float acc = 0.0f;
+                        for (int a = 0; a < th; ++a) {
+                            const float coef = (float)BT_[LIDX(lh)][i][a];
+                            if (coef != 0.0f) acc = acc + coef * d[a][b];
+                        }
+                        Bd[i][b] = acc;
+                    }
+                double* v = V + (((size_t)c * TH + ty) * TW + tx) * th * tw;
+                for (int i = 0; i < th; ++i)
+                    for (int j = 0; j < tw; ++j) {
+                        float acc = 0.0f;
+                        for (int b = 0; b < tw; ++b) {
+                            const float coef = (float)BT_[LIDX(lw)][j][b];
+                            if (coef != 0.0f) acc = acc + coef * Bd[i][b];
+                        }
+                        v[i * tw + j] = (double)acc;
+                    }
+            }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------- */
 /* O2: the whole method                                                       */
 /* ------------------------------------------------------------------------- */
@@ -416,7 +468,8 @@ static int dwm_forward(const float* x, const float* w, double* y,
                 U[i] = half_storage == 2 ? round_bfloat16(U[i]) : round_binary16(U[i]);
         for (int n = 0; n < N && !rc; ++n) {
             /* Splitting (input side) + Transformation: V = B^T d B. */
-            rc = oracle_part_input_transform(x, C, H, W, s, P, TH, TW, n, pt, V);
+            rc = half_storage ? part_input_transform_binary32(x, C, H, W, s, P, TH, TW, n, pt, V)
+                              : oracle_part_input_transform(x, C, H, W, s, P, TH, TW, n, pt, V);
             if (rc) break;
             if (half_storage)
                 for (size_t i = 0; i < (size_t)C * TH * TW * th * tw; ++i)

@@ -392,6 +392,26 @@ def test_single_kernel_small_integers_are_exact(R, S, stride, pad):
     assert np.array_equal(y.astype(np.float64), ref)
 
 
+@pytest.mark.parametrize("forward", [0, 1])
+def test_input_transform_is_evaluated_in_binary32_before_its_rounding(forward):
+    """The closed-form case that separates "V rounded from its binary32 evaluation" from "V rounded from its
+    exact value" (derived at the oracle's test of the same name): both forward forms give the former."""
+    a, b, c = 1 + 2.0 ** -6, 2.0 ** -8, 2.0 ** -24
+    x = np.zeros((1, 1, 4, 4), np.float32)
+    x[0, 0, 0, 0], x[0, 0, 2, 0], x[0, 0, 0, 2] = a, b, c
+    w = np.zeros((1, 1, 3, 3), np.float32)
+    w[0, 0, 0, 0] = 1.0
+    r = Bf16Runner(1, 1, 4, 4, 1, 3, 3, 1, 0, forward=forward)
+    try:
+        y = r.run(x, w, f32out=True).astype(np.float64)
+    finally:
+        r.close()
+    ref = oracle.dwm_bf16_f64(x, w, 1, 0)
+    assert ref[0, 0, 0, 0] == (1 + 2.0 ** -6) + c + b
+    assert abs(y[0, 0, 0, 0] - ref[0, 0, 0, 0]) <= 2.0 ** -23  # (FP32 accumulation of the 2^-24 beside 1)
+    assert np.max(np.abs(y - ref)) <= 2.0 ** -23
+
+
 def test_single_kernel_rounding_points():
     """The cases that pin the oracle's rounding points: one product per output, so the single kernel
     must reproduce the oracle bit for bit."""

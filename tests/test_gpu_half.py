@@ -185,6 +185,29 @@ def test_rounding_points_closed_forms():
                 assert got == exp
 
 
+@pytest.mark.parametrize("forward", [0, 1])
+def test_input_transform_is_evaluated_in_binary32_before_its_rounding(forward):
+    """The closed-form case that separates "V rounded from its binary32 evaluation" from "V rounded from its
+    exact value" (derived at the oracle's test of the same name): both forward forms give the former."""
+    a, b, c = 1 + 2.0 ** -9, 2.0 ** -11, 2.0 ** -24
+    x = np.zeros((1, 1, 4, 4), np.float16)
+    x[0, 0, 0, 0], x[0, 0, 2, 0], x[0, 0, 0, 2] = a, b, c
+    assert float(x[0, 0, 0, 0]) == a and float(x[0, 0, 2, 0]) == b and float(x[0, 0, 0, 2]) == c
+    w = np.zeros((1, 1, 3, 3), np.float16)
+    w[0, 0, 0, 0] = 1.0
+    r = HalfRunner(1, 1, 4, 4, 1, 3, 3, 1, 0, forward=forward)
+    try:
+        y = r.run(x, w, f32out=True).astype(np.float64)
+    finally:
+        r.close()
+    ref = oracle.dwm_half_f64(x, w, 1, 0)
+    assert ref[0, 0, 0, 0] == (1 + 2.0 ** -9) + c + b
+    # the FP32 accumulator cannot hold the 2^-24 of c beside 1: one FP32 step of slack, against the 2^-10
+    # between the two readings
+    assert abs(y[0, 0, 0, 0] - ref[0, 0, 0, 0]) <= 2.0 ** -23
+    assert np.max(np.abs(y - ref)) <= 2.0 ** -23
+
+
 @pytest.mark.parametrize("variant", list(range(30, 48)))
 def test_every_contraction_variant(variant):
     shape = (3, 64, 26, 26, 200, 3, 3, 1, 1)  # 64-row reductions: every chunk depth applies

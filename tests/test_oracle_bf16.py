@@ -142,6 +142,24 @@ def test_it_is_not_the_binary16_rounding():
     assert yh[0] == -1.0 + (1.0 + 2.0 ** -9)
 
 
+def test_input_transform_is_evaluated_in_binary32_before_its_rounding():
+    """As for binary16 (same layer, same derivation: y00 = V00 + c + b with V00 the rounded a - b - c), with
+    bfloat16's 8 significant bits: a = 1 + 2^-6, b = 2^-8, c = 2^-24.  a - b = 1 + 2^-7 + 2^-8 is the midpoint of
+    1 + 2^-7 and 1 + 2^-6; exactly, a - b - c rounds down to 1 + 2^-7; in binary32 it ties to a - b, whose
+    bfloat16 tie goes to the even 1 + 2^-6."""
+    a, b, c = 1 + 2.0 ** -6, 2.0 ** -8, 2.0 ** -24
+    x = np.zeros((1, 1, 4, 4), np.float32)
+    x[0, 0, 0, 0], x[0, 0, 2, 0], x[0, 0, 0, 2] = a, b, c
+    w = np.zeros((1, 1, 3, 3), np.float32)
+    w[0, 0, 0, 0] = 1.0
+    yb = oracle.dwm_bf16_f64(x, w, 1, 0)
+    assert oracle.direct_f64(x, w, 1, 0)[0, 0, 0, 0] == a
+    assert yb[0, 0, 0, 0] == (1 + 2.0 ** -6) + c + b
+    assert yb[0, 0, 0, 0] != (1 + 2.0 ** -7) + c + b
+    x[0, 0, 0, 2] = 2.0 ** -16  # every sum exact in binary32: the exact value's rounding
+    assert oracle.dwm_bf16_f64(x, w, 1, 0)[0, 0, 0, 0] == (1 + 2.0 ** -7) + 2.0 ** -16 + b
+
+
 def test_sums_are_not_rounded():
     x = np.array([1.0, 2.0 ** -15], np.float32).reshape(1, 2, 1, 1)
     w = np.array([1.0, 2.0 ** -15], np.float32).reshape(1, 2, 1, 1)

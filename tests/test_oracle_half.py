@@ -104,6 +104,30 @@ def test_three_tap_filter_rounding():
     assert yh[1] == 0.5 + (0.5 - h / 2)
 
 
+def test_input_transform_is_evaluated_in_binary32_before_its_rounding():
+    """The reading's precision for V (the paper fixes none): B^T d B in binary32, columns first, then ONE
+    rounding to binary16.  It differs from rounding the exact value only where a sum spans more than 13
+    binades.  3x3 filter with the single tap g00 = 1 on a 4x4 input: U = G e0 (G e0)^T with G e0 =
+    (1, 1/2, 1/2, 0), and with d00 = a, d20 = b, d02 = c the transform is
+    V = [[a-b-c, c, c, 0], [b, 0, 0, 0], [b, 0, 0, 0], 0], so y00 = V00 + (c + c)/2 + (b + b)/2.
+    a = 1 + 2^-9, b = 2^-11, c = 2^-24: a - b = 1 + 2^-10 + 2^-11 is the midpoint of 1 + 2^-10 and 1 + 2^-9;
+    the exact a - b - c lies below it (-> 1 + 2^-10), in binary32 it is a tie at 2^-24 that goes to the even
+    neighbour a - b, and the binary16 tie there goes to the even 1 + 2^-9."""
+    a, b, c = 1 + 2.0 ** -9, 2.0 ** -11, 2.0 ** -24
+    x = np.zeros((1, 1, 4, 4), np.float32)
+    x[0, 0, 0, 0], x[0, 0, 2, 0], x[0, 0, 0, 2] = a, b, c
+    w = np.zeros((1, 1, 3, 3), np.float32)
+    w[0, 0, 0, 0] = 1.0
+    assert np.float32(np.float32(a) - np.float32(b)) - np.float32(c) == np.float32(a - b)  # the binary32 tie
+    yh = oracle.dwm_half_f64(x, w, 1, 0)
+    assert oracle.direct_f64(x, w, 1, 0)[0, 0, 0, 0] == a
+    assert yh[0, 0, 0, 0] == (1 + 2.0 ** -9) + c + b
+    assert yh[0, 0, 0, 0] != (1 + 2.0 ** -10) + c + b  # what rounding the exact a - b - c would give
+    # where every sum is exact in binary32 the two evaluations agree: the same case with c = 2^-20
+    x[0, 0, 0, 2] = 2.0 ** -20
+    assert oracle.dwm_half_f64(x, w, 1, 0)[0, 0, 0, 0] == (1 + 2.0 ** -10) + 2.0 ** -20 + b
+
+
 def test_sums_are_not_rounded():
     # 1x1 kernel: no transform, y = sum_c d_c g_c; 1 + 2^-30 needs 31 bits
     x = np.array([1.0, 2.0 ** -15], np.float32).reshape(1, 2, 1, 1)
