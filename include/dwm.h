@@ -275,7 +275,10 @@ DWM_API dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void*
  * Both give the same dx up to fp32 summation order.  May be called at any time. */
 DWM_API dwm_status_t dwm_bwd_data_set_variant(dwm_bwd_data_plan_t* plan, const char* stage, int variant);
 /* w_dev is the forward layer's [K][C][R][S]; Ugw_dev (dwm_bwd_data_filter_bytes long) receives, per
- * phase, the transformed filter of that phase's flipped taps with filters and channels swapped. */
+ * phase, the transformed filter of that phase's flipped taps with filters and channels swapped.
+ * Where no tap reaches any pixel of dx (stride above the kernel size on a narrow image) there is nothing to
+ * transform: dwm_bwd_data_filter_bytes is 0 and Ugw_dev may be NULL here and in dwm_conv_backward_data, which
+ * then writes zeros. */
 DWM_API dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, const float* w_dev, float* Ugw_dev,
                                                    void* stream);
 /* dy_dev [N][K][OH][OW], dx_dev [N][C][H][W] (fully overwritten). */

@@ -420,7 +420,9 @@ dwm_status_t dwm_bwd_data_set_workspace(dwm_bwd_data_plan_t* plan, void* ws_dev,
 dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, const float* w_dev, float* Ugw_dev,
                                            void* stream)
 {
-    if (!plan || !w_dev || !Ugw_dev) return DWM_ERR_INVALID_ARG;
+    // (a layer in which no tap reaches any pixel of dx -- stride above the kernel size on a narrow image -- has no
+    // transformed filter at all: zero bytes, and no buffer to ask for)
+    if (!plan || !w_dev || (!Ugw_dev && plan->filter_floats > 0)) return DWM_ERR_INVALID_ARG;
     for (const auto& ph : plan->phases) {
         if (!ph.sub) continue;
         const size_t total = (size_t)plan->C * plan->K * ph.na * ph.nb;
@@ -440,7 +442,7 @@ dwm_status_t dwm_bwd_data_filter_transform(const dwm_bwd_data_plan_t* plan, cons
 dwm_status_t dwm_conv_backward_data(const dwm_bwd_data_plan_t* plan, const float* dy_dev, const float* Ugw_dev,
                                     float* dx_dev, void* stream)
 {
-    if (!plan || !dy_dev || !Ugw_dev || !dx_dev) return DWM_ERR_INVALID_ARG;
+    if (!plan || !dy_dev || (!Ugw_dev && plan->filter_floats > 0) || !dx_dev) return DWM_ERR_INVALID_ARG;
     if (plan->use_small()) return dwm::launch_bwd_small(plan->small, dy_dev, Ugw_dev + plan->u_small_off, dx_dev, stream);
     for (const auto& ph : plan->phases) {
         if (ph.UH <= 0 || ph.UW <= 0) continue;

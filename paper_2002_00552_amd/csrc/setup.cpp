@@ -166,6 +166,7 @@ bool input_lds_setup(const dwm_plan& p, InLdsArgs* out, int cg_wish)
     // channels per workgroup: one per wave (measured best: many small workgroups keep more loads
     // and stores in flight than fewer large ones)
     int cg = d.C < 4 ? d.C : 4;
+    while (cg > 1 && cg * chan_bytes > 150 * 1024) --cg;  // (a channel's region fits by the check above)
     if (cg_wish > 0 && cg_wish <= d.C && cg_wish * chan_bytes <= 150 * 1024) cg = cg_wish;
     a.cg = cg;
     a.ncg = (d.C + cg - 1) / cg;

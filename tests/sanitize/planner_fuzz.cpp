@@ -48,6 +48,9 @@ static int walk(int N, int C, int H, int W, int K, int R, int S, int s, int P)
     CHECK(dwm_plan_info(p, &in) == DWM_OK);
     CHECK(in.OH == (H + 2 * P - R) / s + 1 && in.OW == (W + 2 * P - S) / s + 1);
     CHECK(in.T == (long long)N * in.TH * in.TW);
+    // what a launch would ask of a CU: the LDS of the staged input transform and of the single kernel
+    CHECK(!p->inlds_ok || (p->inlds.lds_bytes <= 160 * 1024 && p->inlds.cg >= 1 && p->inlds.cg * p->inlds.ncg >= C));
+    CHECK(!p->fused_ok || p->fused.lds_bytes <= 160 * 1024);
     // every tap belongs to exactly one part; the multiplication count is the sum over the parts
     std::vector<int> seen((size_t)R * S, 0);
     long long mults = 0;
@@ -325,6 +328,7 @@ int main(int argc, char** argv)
         {1, 1, 3, 3, 1, 3, 3, 1, -1},      {1, 127, 64, 64, 1, 3, 3, 1, 1},      {1, 128, 64, 64, 1, 3, 3, 1, 1},
         {1, 1, 1 << 20, 2, 1, 3, 1, 1, 1}, {1, 1, 2, (1 << 20) + 1, 1, 1, 3, 1, 1}, {4096, 1, 1024, 1024, 1, 3, 3, 1, 1},
         {1, 2, 12, 6000, 3, 3, 3, 1, 1},   {1, 3, 300, 300, 8, 33, 3, 16, 5},    {2, 5, 40, 40, 33, 47, 47, 1, 23},
+        {6, 12, 68, 10, 116, 10, 10, 4, 3},  // one tile per row: a block of 64 tiles spans whole images (45 KB a channel)
     };
     for (const auto& f : fixed) {
         ++tried;

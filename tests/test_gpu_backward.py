@@ -138,6 +138,30 @@ def test_backward_data_single_kernel_matches_fp64_definition(shape):
     assert _relerr(dx, ref) <= TOL, shape
 
 
+def test_backward_data_where_no_tap_reaches_the_image():
+    """Stride above the kernel size on a one-pixel-wide image: every pixel of dx is untouched by the forward
+    pass, the plan has no sub-convolution and no transformed filter (zero bytes: no buffer is passed), dx = 0."""
+    shape = (7, 7, 42, 1, 170, 2, 2, 3, 2)
+    N, C, H, W, K, R, S, s, P = shape
+    w, dy = _rand(*shape, seed=41)
+    ref = oracle.backward_data_f64(dy, w, (N, C, H, W), s, P)
+    assert not ref.any()
+    plan = dwm.dwm_bwd_data_plan_create(*shape)
+    try:
+        assert dwm.dwm_bwd_data_filter_bytes(plan) == 0 and dwm.dwm_bwd_data_plan_info(plan).n_subconvs == 0
+        st = torch.cuda.current_stream().cuda_stream
+        wd, dyd = torch.from_numpy(w).cuda(), torch.from_numpy(dy).cuda()
+        dx = torch.full((N, C, H, W), float("nan"), dtype=torch.float32, device="cuda:0")
+        ws = torch.zeros(max(dwm.dwm_bwd_data_workspace_bytes(plan) // 4, 64), dtype=torch.float32, device="cuda:0")
+        dwm.dwm_bwd_data_set_workspace(plan, ws.data_ptr(), ws.numel() * 4)
+        dwm.dwm_bwd_data_filter_transform(plan, wd.data_ptr(), None, st)
+        dwm.dwm_conv_backward_data(plan, dyd.data_ptr(), None, dx.data_ptr(), st)
+        torch.cuda.synchronize()
+        assert not dx.cpu().numpy().any()
+    finally:
+        dwm.dwm_bwd_data_plan_destroy(plan)
+
+
 def test_backward_data_is_deterministic_and_plan_reusable():
     shape = (2, 8, 21, 20, 9, 5, 5, 2, 2)
     w, dy = _rand(*shape, seed=5)

@@ -205,6 +205,7 @@ E2E_SHAPES = [
     (2, 2, 301, 64, 3, 7, 3, 1, 3),      # tall image
     (3, 16, 56, 56, 256, 5, 5, 1, 2),    # 148 long tiles on 256 CUs: every tile is cut into two ranges of its own
     (11, 32, 56, 56, 256, 5, 5, 2, 2),   # the same with 136 tiles of 49 32-step chunks (odd: ranges of 25 and 24)
+    (6, 12, 68, 10, 116, 10, 10, 4, 3),  # one tile per row: a block of 64 tiles stages whole images, 45 KB a channel
 ]
 
 
