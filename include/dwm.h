@@ -321,8 +321,10 @@ DWM_API dwm_status_t dwm_conv_backward_filter(const dwm_bwd_filter_plan_t* plan,
  * discussed in Sec. 5.1).  x [N][C][H][W], w [K][C][R][S] and y [N][K][OH][OW] are dense IEEE
  * binary16 (dwm_half_t = the 16-bit pattern).  The paper does not say where its FP16 version
  * rounds; here the transformed filter U = G g G^T and the transformed input V = B^T d B are each
- * rounded ONCE to binary16 (nearest, ties to even), their products are summed over channels and
- * parts in FP32 on the FP16 matrix cores, the output transform is FP32 and y is rounded once.
+ * rounded ONCE to binary16 (nearest, ties to even) -- U from its exact value, V from B^T d B evaluated in
+ * binary32, columns of the patch first, then rows (exact unless a sum spans more than 13 binades) --, their
+ * products are summed over channels and parts in FP32 on the FP16 matrix cores, the output transform is
+ * FP32 and y is rounded once.
  * The kernel is cut exactly as eq. 8 writes it (3,3,...,remainder), so that the rounding points
  * are those of the method as printed.
  *
