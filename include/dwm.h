@@ -127,7 +127,8 @@ typedef struct {
  * that one-tap pieces only come from phases that hold a single tap.
  * Host only; no GPU call is made.
  * Limits: at most 16 one-dimensional pieces per dimension (e.g. R <= 48 at stride 1),
- * N*TH*TW and every buffer's element count below 2^31.  Returns DWM_ERR_INVALID_ARG for
+ * N*TH*TW and the element counts of x, w and y below 2^31 (the workspace may be larger: the transformed input
+ * is addressed block by block, tested to 12 GiB).  Returns DWM_ERR_INVALID_ARG for
  * non-positive sizes, negative pad or an empty output, DWM_ERR_UNSUPPORTED beyond the limits.
  * *out is set only on DWM_OK and must be released with dwm_plan_destroy.
  */
